@@ -1,0 +1,19 @@
+"""Seeded synthetic inputs shared by the CPU oracle's tests and the HIP path's tests.
+
+Nothing in this package performs any step of the method (no dequantization, no
+masking, no index compaction, no layout permutation, no dot products): it only
+draws random tensors of the documented shapes and distributions, encodes them in
+the row-major *source* format that both sides take as input, and picks thresholds
+as order statistics of |x|.
+"""
+from .synth import (  # noqa: F401
+    GROUP,
+    TILE_ROWS,
+    CONFIG_SHAPES,
+    seed_for,
+    make_weights,
+    make_x,
+    quantile_threshold,
+    calibrated_threshold,
+    make_case,
+)
