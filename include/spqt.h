@@ -1,0 +1,147 @@
+/*
+ * libspqt - batch-1 decode GEMV over group-wise int4 weights with dynamic activation
+ * sparsity, for AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * The three calls follow the paper's problem statement (Section 3.2, "The Operations"):
+ * the model is converted once, offline, into the zigzag layout (spqt_pack); at every
+ * decode GEMV the hidden state first goes through a sparse-index-collecting kernel with a
+ * calibrated threshold (spqt_gather), and the index list together with the hidden state
+ * is fed to the GEMV kernel that touches only the listed weight columns (spqt_gemv).
+ *
+ * Conventions
+ *   - Every function returns SPQT_OK (0) or a negative spqt_status.  Nothing throws,
+ *     aborts, or synchronizes a stream unless stated.  Argument errors are detected on the
+ *     host before anything is launched.
+ *   - "HOST" pointers are ordinary host memory; "DEVICE" pointers are device memory of the
+ *     current HIP device.  The caller owns every buffer; the library keeps no state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device calls
+ *     are asynchronous on that stream and never read device results back to the host:
+ *     the kept count n_ns stays on the device between spqt_gather and spqt_gemv.
+ *   - Shapes: W is M (outputs) x K (inputs).  M % 256 == 0, K % 128 == 0, group == 128,
+ *     batch in 1..4; anything else is SPQT_ESHAPE.
+ *
+ * Packed layout ("zigzag", paper Section 4.1.2: weights are grouped along a column - one
+ * block is 256 consecutive rows of ONE column - and the blocks are stored row-major: all
+ * columns of block-row 0, then block-row 1, ...).  The quantization groups stay along K
+ * (the source is row-major group-128 int4 and is not requantized), so the unit of storage
+ * is one chunk per (block-row t, group g):
+ *
+ *     T = M/256, NG = K/128, chunk (t, g) at byte offset (t*NG + g) * 16896
+ *       bytes [0, 512)          fp16 bits of scale[256t + r][g], r = 0..255, little endian
+ *       bytes [512 + 128c + j]  column k = 128g + c, c = 0..127, j = 0..127:
+ *                               low nibble  = code of row 256t + 2j
+ *                               high nibble = code of row 256t + 2j + 1
+ *                               stored code = (q + 8) & 15  (offset binary, q in [-8, 7])
+ *     total = T*NG*16896 = M*K/2 + M*NG*2 bytes, no padding.
+ *
+ * One activation column's 256 weights of a block-row are therefore one aligned 128-byte
+ * run (a skipped column is a skipped cache line), and the scales of its group sit at the
+ * head of the same chunk.
+ */
+#ifndef SPQT_H
+#define SPQT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPQT_OK = 0,
+    SPQT_EINVAL = -1, /* null pointer or bad scalar argument */
+    SPQT_ESHAPE = -2, /* M, K, group or batch not supported */
+    SPQT_EALIGN = -3, /* a device pointer is not aligned as required */
+    SPQT_ESIZE = -4,  /* an output buffer or the workspace is too small */
+    SPQT_EHIP = -5    /* the HIP runtime reported an error at launch */
+} spqt_status;
+
+#define SPQT_TILE_ROWS 256
+#define SPQT_GROUP 128
+#define SPQT_CHUNK_BYTES 16896
+#define SPQT_MAX_BATCH 4
+#define SPQT_MAX_SPLITS 64   /* most workgroups that may share one block-row */
+#define SPQT_GATHER_MAX_K 65536
+
+/* Human-readable name of a status code (static storage). */
+const char *spqt_status_str(int status);
+
+/* Size in bytes of the packed form of an M x K matrix (layout above). */
+int spqt_packed_bytes(int64_t M, int64_t K, int group, size_t *out_bytes);
+
+/* Size in bytes of the device workspace spqt_gemv needs for this shape (partial sums of
+ * the workgroups that share a block-row, plus one arrival counter per block-row).  The
+ * workspace must be prepared ONCE with spqt_workspace_init before its first use; every
+ * spqt_gemv call leaves it ready for the next one.  Two calls that may overlap in time
+ * (different streams) need two workspaces. */
+int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out_bytes);
+
+/* DEVICE, async.  Zeroes the arrival counters of a workspace (a small fill kernel, so it
+ * is safe under graph capture). */
+int spqt_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* HOST, offline, once per matrix (Section 3.2: one-time conversion; Section 4.1.2: the
+ * layout).  Pure nibble/byte permutation, no requantization.
+ *   q_rowmajor       uint8[M][K/2]; element (m,k) in byte k/2, even k in the low nibble,
+ *                    odd k in the high nibble, two's-complement int4.
+ *   scales_rowmajor  uint16[M][K/group], IEEE fp16 bit patterns.
+ *   out_packed       caller-owned, out_bytes >= spqt_packed_bytes (else SPQT_ESIZE);
+ *                    fully overwritten. */
+int spqt_pack(const uint8_t *q_rowmajor, const uint16_t *scales_rowmajor, int64_t M, int64_t K,
+              int group, void *out_packed, size_t out_bytes);
+
+/* HOST.  Exact inverse of spqt_pack. */
+int spqt_unpack(const void *packed, int64_t M, int64_t K, int group, uint8_t *q_rowmajor,
+                uint16_t *scales_rowmajor);
+
+/* DEVICE, async.  Sparse index collection (Section 4.2.3, "Sparse index collecting kernel
+ * design"; sparsity test of Section 2: an entry is sparse iff |x_i| < threshold).
+ *   x_dev          fp16[batch][K], K <= SPQT_GATHER_MAX_K.  For batch > 1 a column is kept
+ *                  if ANY row keeps it (union).
+ *   threshold      fp32; the comparison is done in fp32.  |x| == threshold is kept, NaN is
+ *                  kept, so threshold 0 keeps every column.
+ *   idx_out_dev    int32, capacity K entries; receives the kept column indices in ASCENDING
+ *                  order, contiguous from entry 0 (entries past n_ns are left untouched).
+ *   count_out_dev  int32[1]; receives n_ns.
+ * The result is deterministic (no atomics): the same input gives the same bytes. */
+int spqt_gather(const void *x_dev, int64_t K, int batch, float threshold, int32_t *idx_out_dev,
+                int32_t *count_out_dev, void *stream);
+
+/* Optional launch shape for spqt_gemv_ex (the two hyper-parameters of Section 4.2.2: how
+ * many workgroups share a block-row, and how many wavefronts each holds).  0 = choose. */
+typedef struct {
+    int splits; /* workgroups per block-row, 1..SPQT_MAX_SPLITS */
+    int waves;  /* wavefronts per workgroup: 1, 2 or 4 */
+} spqt_launch_cfg;
+
+/* DEVICE, async.  y[b][m] = sum over the listed columns k of scale[m][k/128] * q[m][k] *
+ * x[b][k], fp32 accumulation (Section 4.2.2 for the dense kernel, Section 4.2.3 for the
+ * load-balanced sparse one: the index list is split evenly over all wavefronts that work
+ * on a block-row).
+ *   packed_dev     device copy of spqt_pack's output, 128-byte aligned (else SPQT_EALIGN).
+ *   x_dev          fp16[batch][K].
+ *   idx_dev        int32 kept-column list from spqt_gather (ascending), or NULL for the
+ *                  dense kernel, which visits every column and reads neither idx nor count.
+ *   count_dev      int32[1] n_ns on the device (ignored when idx_dev == NULL).
+ *   y_dev          fp32[batch][M], fully overwritten (zeros when n_ns == 0).
+ *   workspace_dev  >= spqt_workspace_bytes(M, K, batch) bytes, prepared by
+ *                  spqt_workspace_init (else SPQT_ESIZE / SPQT_EINVAL).
+ * Deterministic: partial sums are combined in a fixed order, no floating-point atomics. */
+int spqt_gemv(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+              int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+              void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Same, with an explicit launch shape (NULL cfg == spqt_gemv). */
+int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+                 int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                 void *workspace_dev, size_t workspace_bytes, void *stream,
+                 const spqt_launch_cfg *cfg);
+
+/* The launch shape spqt_gemv would pick for this shape (host only, no device access). */
+int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spqt_launch_cfg *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPQT_H */

@@ -1,0 +1,26 @@
+"""MI355X-native SpQt hot path: zigzag repack, sparse index gather, sparse int4 GEMV.
+
+The work is done by hand-written HIP kernels in libspqt.so (C ABI in include/spqt.h); this
+package only marshals arguments.  There is no CPU fallback.
+"""
+from .binding import (  # noqa: F401
+    SpqtError,
+    LaunchCfg,
+    LIB_PATH,
+    EXPORTS,
+    TILE_ROWS,
+    GROUP,
+    CHUNK_BYTES,
+    MAX_SPLITS,
+    lib,
+    new_workspace,
+    spqt_default_cfg,
+    spqt_gather,
+    spqt_gemv,
+    spqt_pack,
+    spqt_packed_bytes,
+    spqt_status_str,
+    spqt_unpack,
+    spqt_workspace_bytes,
+    spqt_workspace_init,
+)

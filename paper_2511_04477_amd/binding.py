@@ -1,0 +1,194 @@
+"""Thin ctypes binding over libspqt.so: argument marshalling only.
+
+Same names as the C ABI (include/spqt.h).  Host calls take NumPy arrays; device calls take
+torch CUDA tensors (PyTorch supplies device memory and the stream, nothing else) and launch
+on torch's current stream unless one is given.  There is no fallback of any kind: if the
+shared library is missing, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libspqt.so")
+
+SPQT_OK = 0
+TILE_ROWS = 256
+GROUP = 128
+CHUNK_BYTES = 16896
+MAX_SPLITS = 64
+
+EXPORTS = [
+    "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",
+    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gemv", "spqt_gemv_ex", "spqt_default_cfg",
+]
+
+
+class SpqtError(RuntimeError):
+    pass
+
+
+class LaunchCfg(ctypes.Structure):
+    _fields_ = [("splits", ctypes.c_int), ("waves", ctypes.c_int)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libspqt.so (built in-tree by paper_2511_04477_amd.build); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SpqtError(f"{LIB_PATH} is not built; run `python -m paper_2511_04477_amd.build` "
+                            "(there is no CPU or PyTorch fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        vp, i64, i32, sz = c.c_void_p, c.c_int64, c.c_int, c.c_size_t
+        L.spqt_status_str.restype = c.c_char_p
+        L.spqt_status_str.argtypes = [i32]
+        L.spqt_packed_bytes.argtypes = [i64, i64, i32, c.POINTER(sz)]
+        L.spqt_workspace_bytes.argtypes = [i64, i64, i32, c.POINTER(sz)]
+        L.spqt_workspace_init.argtypes = [vp, sz, vp]
+        L.spqt_pack.argtypes = [vp, vp, i64, i64, i32, vp, sz]
+        L.spqt_unpack.argtypes = [vp, i64, i64, i32, vp, vp]
+        L.spqt_gather.argtypes = [vp, i64, i32, c.c_float, vp, vp, vp]
+        L.spqt_gemv.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.spqt_gemv_ex.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp,
+                                   c.POINTER(LaunchCfg)]
+        L.spqt_default_cfg.argtypes = [i64, i64, i32, i32, c.POINTER(LaunchCfg)]
+        for name in EXPORTS[1:]:
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != SPQT_OK:
+        raise SpqtError(lib().spqt_status_str(rc).decode())
+
+
+def spqt_status_str(status: int) -> str:
+    return lib().spqt_status_str(int(status)).decode()
+
+
+def spqt_packed_bytes(M: int, K: int, group: int = GROUP) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().spqt_packed_bytes(M, K, group, ctypes.byref(out)))
+    return out.value
+
+
+def spqt_workspace_bytes(M: int, K: int, batch: int = 1) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().spqt_workspace_bytes(M, K, batch, ctypes.byref(out)))
+    return out.value
+
+
+def spqt_default_cfg(M: int, K: int, batch: int = 1, sparse: bool = True):
+    cfg = LaunchCfg()
+    _check(lib().spqt_default_cfg(M, K, batch, int(sparse), ctypes.byref(cfg)))
+    return cfg.splits, cfg.waves
+
+
+# ----------------------------------------------------------------------------- host calls
+
+def _np_ptr(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def spqt_pack(q_rowmajor: np.ndarray, scales: np.ndarray, group: int = GROUP) -> np.ndarray:
+    """uint8[M, K/2] codes + fp16 (or uint16 bits) [M, K/group] scales -> packed uint8 bytes."""
+    q = np.ascontiguousarray(q_rowmajor, dtype=np.uint8)
+    s = np.ascontiguousarray(scales)
+    s = s.view(np.uint16) if s.dtype == np.float16 else s
+    if s.dtype != np.uint16 or q.ndim != 2 or s.ndim != 2:
+        raise SpqtError("spqt_pack: need uint8[M,K/2] codes and fp16/uint16[M,K/group] scales")
+    M, K = q.shape[0], q.shape[1] * 2
+    if s.shape != (M, K // group if group else 0):
+        raise SpqtError("spqt_pack: scales shape does not match [M, K/group]")
+    out = np.empty(spqt_packed_bytes(M, K, group), dtype=np.uint8)
+    _check(lib().spqt_pack(_np_ptr(q), _np_ptr(s), M, K, group, _np_ptr(out), out.nbytes))
+    return out
+
+
+def spqt_unpack(packed: np.ndarray, M: int, K: int, group: int = GROUP):
+    p = np.ascontiguousarray(packed, dtype=np.uint8)
+    if p.nbytes < spqt_packed_bytes(M, K, group):
+        raise SpqtError("spqt_unpack: packed buffer too small")
+    q = np.empty((M, K // 2), dtype=np.uint8)
+    s = np.empty((M, K // group), dtype=np.uint16)
+    _check(lib().spqt_unpack(_np_ptr(p), M, K, group, _np_ptr(q), _np_ptr(s)))
+    return q, s.view(np.float16)
+
+
+# --------------------------------------------------------------------------- device calls
+
+def _stream_ptr(stream) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t, dtype, what):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise SpqtError(f"{what}: need a contiguous CUDA tensor of dtype {dtype}")
+    return t.data_ptr()
+
+
+def spqt_workspace_init(workspace, stream=None) -> None:
+    import torch
+    p = _dev(workspace, torch.uint8, "workspace")
+    _check(lib().spqt_workspace_init(p, workspace.numel(), _stream_ptr(stream)))
+
+
+def new_workspace(M: int, K: int, batch: int = 1, device="cuda"):
+    """Allocate and prepare a workspace tensor for spqt_gemv on this shape."""
+    import torch
+    ws = torch.empty(spqt_workspace_bytes(M, K, batch), dtype=torch.uint8, device=device)
+    spqt_workspace_init(ws)
+    return ws
+
+
+def spqt_gather(x, threshold: float, idx_out, count_out, stream=None) -> None:
+    """x fp16[K] or [batch, K]; idx_out int32[>=K]; count_out int32[1] (all on the GPU)."""
+    import torch
+    xp = _dev(x, torch.float16, "x")
+    batch, K = (1, x.shape[0]) if x.dim() == 1 else (x.shape[0], x.shape[1])
+    ip = _dev(idx_out, torch.int32, "idx_out")
+    cp = _dev(count_out, torch.int32, "count_out")
+    if idx_out.numel() < K or count_out.numel() < 1:
+        raise SpqtError("spqt_gather: idx_out needs K entries and count_out one")
+    _check(lib().spqt_gather(xp, K, batch, float(threshold), ip, cp, _stream_ptr(stream)))
+
+
+def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, group: int = GROUP,
+              splits: int = 0, waves: int = 0) -> None:
+    """packed uint8 (device); x fp16[K] or [batch,K]; idx/count from spqt_gather or None/None
+    for the dense kernel; y fp32[M] or [batch,M]; workspace from new_workspace()."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp = _dev(y, torch.float32, "y")
+    batch = 1 if x.dim() == 1 else x.shape[0]
+    if x.shape[-1] != K or y.numel() != batch * M or packed.numel() < spqt_packed_bytes(M, K, group):
+        raise SpqtError("spqt_gemv: x / y / packed sizes do not match M, K, batch")
+    ip = cp = None
+    if idx is not None:
+        ip = _dev(idx, torch.int32, "idx")
+        cp = _dev(count, torch.int32, "count")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    if splits or waves:
+        cfg = LaunchCfg(int(splits), int(waves))
+        rc = lib().spqt_gemv_ex(pp, M, K, group, xp, batch, ip, cp, yp, wp, wbytes,
+                                _stream_ptr(stream), ctypes.byref(cfg))
+    else:
+        rc = lib().spqt_gemv(pp, M, K, group, xp, batch, ip, cp, yp, wp, wbytes, _stream_ptr(stream))
+    _check(rc)

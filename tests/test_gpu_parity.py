@@ -1,0 +1,256 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Index lists and packed bytes must match bit for bit; outputs must satisfy
+|y_gpu - y_ref| <= 1e-2 + 2e-3 * |y_ref| elementwise (fp32 accumulation vs the fp64 oracle).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import make_case, make_weights, make_x, quantile_threshold
+
+pytestmark = pytest.mark.gpu
+
+ATOL, RTOL = 1e-2, 2e-3
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2511_04477_amd as spqt
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    spqt.lib()   # raises if the HIP library is not built: there is no fallback
+    return torch, spqt, torch.device("cuda:0")
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def gpu_gather(gpu, x_np, thr, poison=-7):
+    torch, spqt, dev = gpu
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)
+    K = x.shape[-1]
+    idx = torch.full((K + 64,), poison, dtype=torch.int32, device=dev)
+    cnt = torch.full((2,), poison, dtype=torch.int32, device=dev)
+    spqt.spqt_gather(x if x.shape[0] > 1 else x[0], thr, idx, cnt)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), cnt.cpu().numpy()
+
+
+def gpu_gemv(gpu, w, x_np, thr, dense=False, splits=0, waves=0, packed=None):
+    torch, spqt, dev = gpu
+    M, K = w["q_rowmajor"].shape[0], w["q_rowmajor"].shape[1] * 2
+    if packed is None:
+        packed = torch.from_numpy(spqt.spqt_pack(w["q_rowmajor"], w["scales"])).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)
+    batch = x.shape[0]
+    xx = x if batch > 1 else x[0]
+    y = torch.full((batch, M), float("nan"), dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K, batch)
+    if dense:
+        spqt.spqt_gemv(packed, M, K, xx, None, None, y if batch > 1 else y[0], ws, splits=splits, waves=waves)
+    else:
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        spqt.spqt_gather(xx, thr, idx, cnt)
+        spqt.spqt_gemv(packed, M, K, xx, idx, cnt, y if batch > 1 else y[0], ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def assert_close(got, ref, what=""):
+    err = np.abs(got.astype(np.float64) - ref)
+    bound = ATOL + RTOL * np.abs(ref)
+    bad = np.argwhere(err > bound)
+    assert bad.size == 0, f"{what}: {bad.shape[0]} outputs out of tolerance, first {bad[0]}, max err {err.max():.4g}"
+    return float(err.max())
+
+
+# ------------------------------------------------------------------------------ gather
+
+@pytest.mark.parametrize("K", [128, 1024, 4096, 8192, 11008, 14336, 28672, 65536])
+@pytest.mark.parametrize("sparsity", [0.0, 0.25, 0.5, 0.65, 0.97])
+def test_gather_bit_exact(gpu, K, sparsity):
+    x = make_x(K, "laplace", 9000 + K)
+    thr = quantile_threshold(x, sparsity)
+    say(f"gather K={K} s={sparsity} thr={thr}")
+    idx, cnt = gpu_gather(gpu, x, thr)
+    ref, n = oracle.gather(x, thr)
+    assert cnt[0] == n and cnt[1] == -7
+    assert np.array_equal(idx[:n], ref)
+    assert np.all(idx[n:] == -7), "entries past n_ns must stay untouched"
+
+
+def test_gather_edge_thresholds_and_ties(gpu):
+    x = make_x(4096, "normal", 9100)
+    idx, cnt = gpu_gather(gpu, x, 0.0)
+    assert cnt[0] == 4096 and np.array_equal(idx[:4096], np.arange(4096))
+    idx, cnt = gpu_gather(gpu, x, float("inf"))
+    assert cnt[0] == 0 and np.all(idx == -7)
+    xt = np.zeros((1, 256), dtype=np.float16)
+    xt[0, :7] = [0.5, -0.5, 0.25, 0.0, -0.0, 0.75, 0.4995]
+    xt[0, 100] = np.nan
+    xt[0, 200] = np.inf
+    for thr in (0.5, 0.0, float("inf"), 0.25):
+        idx, cnt = gpu_gather(gpu, xt, thr)
+        ref, n = oracle.gather(xt, thr)
+        assert cnt[0] == n and np.array_equal(idx[:n], ref), thr
+
+
+def test_gather_batch_union(gpu):
+    x = make_x(8192, "laplace", 9200, batch=4)
+    for s in (0.3, 0.5, 0.7):
+        thr = quantile_threshold(x, s)
+        idx, cnt = gpu_gather(gpu, x, thr)
+        ref, n = oracle.gather(x, thr)
+        assert cnt[0] == n and np.array_equal(idx[:n], ref)
+
+
+def test_gather_is_reproducible(gpu):
+    x = make_x(28672, "laplace", 9300)
+    thr = quantile_threshold(x, 0.5)
+    first = gpu_gather(gpu, x, thr)
+    for _ in range(10):
+        again = gpu_gather(gpu, x, thr)
+        assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+
+
+# ------------------------------------------------------------------------------ packed bytes
+
+def test_packed_bytes_on_device_equal_reference_packer(gpu):
+    torch, spqt, dev = gpu
+    case = make_case(1, "w")
+    packed = torch.from_numpy(spqt.spqt_pack(case["q_rowmajor"], case["scales"])).to(dev)
+    assert np.array_equal(packed.cpu().numpy(), oracle.pack(case["q_rowmajor"], case["scales"]))
+
+
+# ------------------------------------------------------------------------------ gemv values
+
+@pytest.mark.parametrize("sparsity", [0.0, 0.25, 0.4, 0.5, 0.65, 0.9, 1.0])
+def test_config1_sparse_gemv(gpu, sparsity):
+    case = make_case(1, "w")
+    thr = quantile_threshold(case["x"], sparsity)
+    say(f"config1 s={sparsity}")
+    got = gpu_gemv(gpu, case, case["x"], thr)
+    ref = oracle.gemv(case["q_rowmajor"], case["scales"], case["x"], thr)
+    assert_close(got, ref, f"config1 s={sparsity}")
+    if sparsity == 1.0:
+        assert np.all(got == 0.0), "n_ns == 0 must still write zeros"
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (256, 256), (768, 640), (512, 1024), (1024, 4096), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (1, 4), (2, 2), (3, 4), (5, 1), (8, 4), (64, 2)])
+def test_launch_shapes_and_ragged_sizes(gpu, M, K, splits, waves):
+    w = make_weights(M, K, 7000 + M + K)
+    x = make_x(K, "laplace", 7001 + M + K)
+    thr = quantile_threshold(x, 0.5)
+    say(f"M={M} K={K} splits={splits} waves={waves}")
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    assert_close(gpu_gemv(gpu, w, x, thr, splits=splits, waves=waves), ref, "sparse")
+    ref0 = oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0)
+    assert_close(gpu_gemv(gpu, w, x, 0.0, dense=True, splits=splits, waves=waves), ref0, "dense")
+
+
+def test_threshold_zero_equals_dense_kernel_bitwise(gpu):
+    """thr = 0 lists every column, so the sparse kernel must do exactly what the index-free
+    dense kernel does (same partition, same order) - identical bits."""
+    case = make_case(1, "w")
+    a = gpu_gemv(gpu, case, case["x"], 0.0)
+    b = gpu_gemv(gpu, case, case["x"], 0.0, dense=True)
+    assert np.array_equal(a, b)
+
+
+def test_exact_arithmetic_case_is_bit_exact(gpu):
+    """Integer x, power-of-two scales: every product and partial sum is exactly representable
+    in fp32, so the GPU must equal the oracle bit for bit whatever its summation order."""
+    M, K = 512, 1024
+    rng = np.random.default_rng(5)
+    w = make_weights(M, K, 31)
+    w["scales"] = (2.0 ** rng.integers(-6, -2, size=(M, K // 128))).astype(np.float16)
+    x = rng.integers(-4, 5, size=(1, K)).astype(np.float16)
+    for thr in (0.0, 2.0, 3.0):
+        ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+        got = gpu_gemv(gpu, w, x, thr)
+        assert np.array_equal(got.astype(np.float64), ref), thr
+    got = gpu_gemv(gpu, w, x, 0.0, dense=True)
+    assert np.array_equal(got.astype(np.float64), oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0))
+
+
+def test_column_probe(gpu):
+    """x = c * e_k  =>  y = c * dequant(W[:, k]) exactly; catches any address-mapping error."""
+    torch, spqt, dev = gpu
+    M, K = 512, 384
+    w = make_weights(M, K, 41)
+    Wd = oracle.dequant(w["q_rowmajor"], w["scales"])
+    packed = torch.from_numpy(spqt.spqt_pack(w["q_rowmajor"], w["scales"])).to(dev)
+    for k in list(range(0, K, 7)) + [127, 128, 255, 256, K - 1]:
+        x = np.zeros((1, K), dtype=np.float16)
+        x[0, k] = -1.5
+        got = gpu_gemv(gpu, w, x, 1.0, packed=packed)[0].astype(np.float64)
+        want = (-1.5 * Wd[:, k])
+        assert np.array_equal(got, want.astype(np.float32).astype(np.float64)), k
+
+
+def test_clustered_sparsity(gpu):
+    """Kept columns bunched into a few groups, empty groups, a group with a single kept
+    column, and a list whose slices straddle group boundaries."""
+    M, K = 1024, 2048
+    w = make_weights(M, K, 61)
+    x = make_x(K, "laplace", 62)
+    x[0, 0:512] = 0            # four empty groups
+    x[0, 640:768] = 0
+    x[0, 700] = 3.0            # a group with one kept column
+    x[0, 1024:1152] = 2.0      # a full group
+    thr = 0.75
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    for splits, waves in [(0, 0), (1, 1), (7, 4), (16, 2)]:
+        assert_close(gpu_gemv(gpu, w, x, thr, splits=splits, waves=waves), ref, f"clustered {splits}x{waves}")
+
+
+def test_gemv_is_reproducible(gpu):
+    case = make_case(1, "w")
+    thr = quantile_threshold(case["x"], 0.5)
+    first = gpu_gemv(gpu, case, case["x"], thr)
+    for _ in range(20):
+        assert np.array_equal(first, gpu_gemv(gpu, case, case["x"], thr))
+
+
+def test_batch4_union(gpu):
+    M, K = 512, 1024
+    w = make_weights(M, K, 71)
+    x = make_x(K, "laplace", 72, batch=4)
+    for s in (0.0, 0.3, 0.5, 0.7):
+        thr = quantile_threshold(x, s)
+        ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+        assert_close(gpu_gemv(gpu, w, x, thr), ref, f"batch4 s={s}")
+    x1 = np.ascontiguousarray(np.repeat(x[:1], 4, axis=0))
+    thr = quantile_threshold(x1, 0.5)
+    y4 = gpu_gemv(gpu, w, x1, thr)
+    y1 = gpu_gemv(gpu, w, x1[:1], thr)
+    assert all(np.array_equal(y4[b], y1[0]) for b in range(4))
+
+
+# ------------------------------------------------------------------------------ full sizes
+
+FULL = [(2, "q", [0.0, 0.25, 0.4, 0.5, 0.65]),
+        (3, "gate", [0.4, 0.5]), (3, "down", [0.4, 0.5]),
+        (4, "k", [0.5]), (4, "gate", [0.5]), (4, "down", [0.5]),
+        (5, "gate", [0.3, 0.5, 0.7]), (5, "down", [0.5])]
+
+
+@pytest.mark.parametrize("config,tensor,sparsities", FULL)
+def test_full_size_default_launch(gpu, config, tensor, sparsities):
+    """Benchmark shapes in the launch configuration the benchmark times (library default)."""
+    torch, spqt, dev = gpu
+    case = make_case(config, tensor, want_q=False)
+    say(f"full config={config} tensor={tensor} M={case['M']} K={case['K']}")
+    packed_np = spqt.spqt_pack(case["q_rowmajor"], case["scales"])
+    packed = torch.from_numpy(packed_np).to(dev)
+    for s in sparsities:
+        thr = quantile_threshold(case["x"], s)
+        ref = oracle.gemv(case["q_rowmajor"], case["scales"], case["x"], thr)
+        got = gpu_gemv(gpu, case, case["x"], thr, packed=packed)
+        e = assert_close(got, ref, f"cfg{config}/{tensor} s={s}")
+        say(f"   s={s}: max|err|={e:.3e}")
+    ref = oracle.gemv(case["q_rowmajor"], case["scales"], case["x"], 0.0)
+    assert_close(gpu_gemv(gpu, case, case["x"], 0.0, dense=True, packed=packed), ref, "dense")

@@ -1,0 +1,110 @@
+"""CPU-only checks of the library's host side: it loads, exports every symbol the header
+declares, its packer matches the oracle's reference packer byte for byte, and argument
+errors come back as status codes.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2511_04477_amd as spqt
+from workloads import make_weights
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "spqt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spqt_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = spqt.lib()
+    names = declared_functions()
+    assert set(names) == set(spqt.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    assert spqt.spqt_status_str(0) == "SPQT_OK"
+    for code in (-1, -2, -3, -4, -5):
+        assert spqt.spqt_status_str(code).startswith("SPQT_E")
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 1024), (768, 640), (1024, 4096)])
+def test_pack_matches_oracle_packer_bit_exact(M, K):
+    w = make_weights(M, K, 1000 + M + K)
+    got = spqt.spqt_pack(w["q_rowmajor"], w["scales"])
+    want = oracle.pack(w["q_rowmajor"], w["scales"])
+    assert got.nbytes == want.nbytes == spqt.spqt_packed_bytes(M, K)
+    assert np.array_equal(got, want)
+
+
+def test_pack_extreme_codes_and_scale_bits():
+    M, K = 256, 256
+    raw = np.zeros((M, K // 2), dtype=np.uint8)
+    raw[0::2] = 0x87      # codes +7 (low) and -8 (high)
+    raw[1::2] = 0x78
+    sc = np.arange(M * 2, dtype=np.uint16).reshape(M, 2) * 31 + 7   # arbitrary bit patterns
+    got = spqt.spqt_pack(raw, sc)
+    assert np.array_equal(got, oracle.pack(raw, sc))
+
+
+def test_unpack_is_exact_inverse():
+    w = make_weights(512, 384, 77)
+    p = spqt.spqt_pack(w["q_rowmajor"], w["scales"])
+    q2, s2 = spqt.spqt_unpack(p, 512, 384)
+    assert np.array_equal(q2, w["q_rowmajor"])
+    assert np.array_equal(s2.view(np.uint16), w["scales"].view(np.uint16))
+    # and the library's unpack inverts the ORACLE's packer too
+    q3, s3 = spqt.spqt_unpack(oracle.pack(w["q_rowmajor"], w["scales"]), 512, 384)
+    assert np.array_equal(q3, w["q_rowmajor"]) and np.array_equal(s3.view(np.uint16), s2.view(np.uint16))
+
+
+def test_sizes():
+    assert spqt.spqt_packed_bytes(4096, 4096) == 4096 * 4096 // 2 + 4096 * 32 * 2
+    assert spqt.spqt_packed_bytes(256, 128) == spqt.CHUNK_BYTES
+    assert spqt.spqt_workspace_bytes(4096, 4096) >= 4096 * 4 * spqt.MAX_SPLITS
+
+
+@pytest.mark.parametrize("M,K,group", [(255, 128, 128), (256, 127, 128), (256, 128, 64), (0, 128, 128),
+                                       (256, 0, 128), (-256, 128, 128)])
+def test_bad_shapes_are_rejected(M, K, group):
+    out = ctypes.c_size_t()
+    assert spqt.lib().spqt_packed_bytes(M, K, group, ctypes.byref(out)) == -2   # SPQT_ESHAPE
+
+
+def test_null_and_small_buffers_are_rejected_on_the_host():
+    L = spqt.lib()
+    out = ctypes.c_size_t()
+    assert L.spqt_packed_bytes(256, 128, 128, None) == -1
+    raw = np.zeros((256, 64), dtype=np.uint8)
+    sc = np.zeros((256, 1), dtype=np.uint16)
+    small = np.zeros(100, dtype=np.uint8)
+    vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    assert L.spqt_pack(vp(raw), vp(sc), 256, 128, 128, vp(small), small.nbytes) == -4
+    assert L.spqt_pack(None, vp(sc), 256, 128, 128, vp(small), small.nbytes) == -1
+    # device entry points validate before touching the GPU, so these run without one
+    assert L.spqt_gather(None, 128, 1, ctypes.c_float(0.0), None, None, None) == -1
+    assert L.spqt_gather(16, 100, 1, ctypes.c_float(0.0), 16, 16, None) == -2
+    assert L.spqt_gather(16, 1 << 20, 1, ctypes.c_float(0.0), 16, 16, None) == -2
+    assert L.spqt_gather(16, 128, 5, ctypes.c_float(0.0), 16, 16, None) == -2
+    assert L.spqt_gather(16, 128, 1, ctypes.c_float(float("nan")), 16, 16, None) == -1
+    assert L.spqt_gather(18, 128, 1, ctypes.c_float(0.0), 16, 16, None) == -3
+    assert L.spqt_gemv(None, 256, 128, 128, 16, 1, None, None, 16, None, 0, None) == -1
+    assert L.spqt_gemv(128, 100, 128, 128, 16, 1, None, None, 16, None, 0, None) == -2
+    assert L.spqt_gemv(64, 256, 128, 128, 16, 1, None, None, 16, None, 0, None) == -3
+    assert L.spqt_gemv(128, 256, 128, 128, 16, 1, 16, None, 16, None, 0, None) == -1  # idx without count
+    assert L.spqt_gemv(128, 256, 128, 128, 16, 7, None, None, 16, None, 0, None) == -2
+
+
+@pytest.mark.parametrize("M,K", [(512, 1024), (4096, 4096), (1024, 4096), (11008, 4096), (4096, 11008),
+                                 (14336, 4096), (4096, 14336), (28672, 8192), (8192, 28672)])
+def test_default_launch_shape_is_valid(M, K):
+    for sparse in (False, True):
+        splits, waves = spqt.spqt_default_cfg(M, K, 1, sparse)
+        assert 1 <= splits <= spqt.MAX_SPLITS and waves in (1, 2, 4)

@@ -16,7 +16,7 @@ import numpy as np
 GROUP = 128      # quantization group length along the input (K) dimension
 TILE_ROWS = 256  # rows per zigzag tile (the paper's superblock height, Section 4.2.1)
 
-TENSOR_IDS = {"q": 0, "k": 1, "v": 2, "o": 3, "gate": 4, "up": 5, "down": 6}
+TENSOR_IDS = {"w": 0, "q": 0, "k": 1, "v": 2, "o": 3, "gate": 4, "up": 5, "down": 6}
 KIND_WEIGHTS, KIND_X, KIND_CALIB = 0, 50, 90
 
 # (name, M, K, activation distribution) per benchmark configuration.
@@ -38,7 +38,7 @@ CONFIG_SCALE_RANGE = {1: (0.005, 0.02), 2: (0.005, 0.02), 3: (0.005, 0.02),
 
 def seed_for(config: int, layer: int = 0, tensor: str | int = 0, kind: int = KIND_WEIGHTS) -> int:
     """One integer seed per (configuration, layer, tensor, kind of draw)."""
-    tid = TENSOR_IDS.get(tensor, tensor) if isinstance(tensor, str) else int(tensor)
+    tid = TENSOR_IDS[tensor] if isinstance(tensor, str) else int(tensor)
     return 0x5B07 * 1_000_000 + int(config) * 10_000 + int(layer) * 100 + tid + int(kind)
 
 
