@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpQt hot path on one MI355X.
+
+A step is one pass of the whole hot path over one activation vector: spqt_gather (threshold
++ index compaction) followed by the load-balanced sparse int4 GEMV, batch 1.  The headline
+workload is the Llama-7B attention-projection shape (4096 x 4096, group 128) at 50 %
+activation sparsity.  Weight buffers rotate over independently seeded copies whose total
+size is several times the 256 MB Infinity Cache, so no launch re-reads cached weights.
+
+Prints ONE JSON line (see README for the fields).  `--gpus` above 1 is refused:
+this build is a one-GPU kernel path.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
+INFINITY_CACHE_BYTES = 256 << 20
+ROTATE_BYTES = 3 * INFINITY_CACHE_BYTES   # rotate over at least this many bytes of weights
+
+
+def kept_bytes(M, K, n_ns, groups_touched=None):
+    """Algorithmic HBM bytes of one sparse GEMV: the 128-byte runs of the kept columns plus the
+    fp16 scales of every (row, group) that has a kept column."""
+    ng = K // 128 if groups_touched is None else groups_touched
+    return n_ns * M // 2 + ng * M * 2
+
+
+class Workload:
+    """Rotating set of packed weight copies + per-copy activations, thresholds and index lists
+    for one (M, K) shape at one sparsity."""
+
+    def __init__(self, torch, spqt, M, K, dist, scale_range, config, tensor, sparsity, copies=None):
+        import numpy as np
+        from workloads import make_case, make_x, quantile_threshold, seed_for, KIND_X
+        self.torch, self.spqt, self.M, self.K = torch, spqt, M, K
+        self.sparsity = sparsity
+        dev = torch.device("cuda:0")
+        pbytes = spqt.spqt_packed_bytes(M, K)
+        self.copies = copies or max(2, -(-ROTATE_BYTES // pbytes))
+        lo, hi = scale_range
+        T, NG = M // 256, K // 128
+        # copy 0: the seeded row-major tensors of the workload module, repacked by the library
+        self.case0 = make_case(config, tensor, layer=0, want_q=False)
+        self.packed = [torch.from_numpy(spqt.spqt_pack(self.case0["q_rowmajor"], self.case0["scales"])).to(dev)]
+        # other copies: independently seeded random codes and scales drawn directly in packed
+        # form on the GPU (any byte is a valid pair of codes; scale area gets fp16 U(lo, hi))
+        for layer in range(1, self.copies):
+            g = torch.Generator(device=dev)
+            g.manual_seed(seed_for(config, layer, tensor))
+            buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NG, 256), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
+            buf[:, :512] = sc.view(torch.uint8)
+            self.packed.append(buf.reshape(-1))
+        xs, thr = [], []
+        for layer in range(self.copies):
+            x = make_x(K, dist, seed_for(config, layer, tensor, KIND_X))
+            xs.append(x[0])
+            thr.append(quantile_threshold(x, sparsity))
+        self.x_np = np.stack(xs)
+        self.thr = thr
+        self.x = torch.from_numpy(self.x_np).to(dev)
+        self.idx = torch.zeros((self.copies, K), dtype=torch.int32, device=dev)
+        self.cnt = torch.zeros((self.copies, 1), dtype=torch.int32, device=dev)
+        self.y = torch.zeros((self.copies, M), dtype=torch.float32, device=dev)
+        self.ws = spqt.new_workspace(M, K)
+        for i in range(self.copies):
+            spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
+        torch.cuda.synchronize()
+        self.n_ns = self.cnt.cpu().numpy().ravel()
+        self.mean_kept_bytes = float(np.mean([kept_bytes(M, K, int(n)) for n in self.n_ns]))
+        self.dense_bytes = kept_bytes(M, K, K)
+
+    # one step of the hot path on copy i
+    def step(self, i):
+        self.spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
+        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
+
+    def gemv_only(self, i):
+        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
+
+    def gather_only(self, i):
+        self.spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
+
+    def dense_only(self, i):
+        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], None, None, self.y[i], self.ws)
+
+    def check_copy0(self):
+        """Parity of copy 0 against the oracle in exactly this launch configuration."""
+        import numpy as np
+        import oracle
+        self.step(0)
+        self.torch.cuda.synchronize()
+        c = self.case0
+        ref_idx, n = oracle.gather(self.x_np[0:1], self.thr[0])
+        ref = oracle.gemv(c["q_rowmajor"], c["scales"], self.x_np[0:1], self.thr[0])[0]
+        got = self.y[0].cpu().numpy().astype(np.float64)
+        ok_idx = int(self.cnt[0].item()) == n and np.array_equal(self.idx[0, :n].cpu().numpy(), ref_idx)
+        err = np.abs(got - ref)
+        ok_y = bool(np.all(err <= 1e-2 + 2e-3 * np.abs(ref)))
+        return ok_idx and ok_y, float(err.max())
+
+
+def make_graph(torch, fn, n):
+    """Capture fn(0..n-1) back to back into one HIP graph."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(n):
+            fn(i)
+    return g
+
+
+def time_sequence(torch, fn, copies, steps, warmup, use_graph=True):
+    """Average microseconds per call of fn over exactly `steps` calls (after `warmup` untimed
+    ones), rotating the copy index; HIP events on the launch stream bracket the timed region."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn(0)                       # first launch of a kernel loads its code object: not under capture
+    torch.cuda.synchronize()
+    if use_graph:
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            full = make_graph(torch, fn, copies)
+            rem_n = steps % copies
+            rem = make_graph(torch, fn, rem_n) if rem_n else None
+            for _ in range(max(1, -(-warmup // copies))):
+                full.replay()
+            torch.cuda.synchronize()
+            start.record()
+            for _ in range(steps // copies):
+                full.replay()
+            if rem is not None:
+                rem.replay()
+            stop.record()
+            torch.cuda.synchronize()
+    else:
+        for k in range(warmup):
+            fn(k % copies)
+        torch.cuda.synchronize()
+        start.record()
+        for k in range(steps):
+            fn(k % copies)
+        stop.record()
+        torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1e3 / steps
+
+
+def cpu_baseline(case, x_np, thr, budget_s=12.0):
+    """The oracle as it stands, timed on the host cores, on repeated calls for about budget_s."""
+    import oracle
+    oracle.gemv(case["q_rowmajor"], case["scales"], x_np, thr)       # warm
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        oracle.gemv(case["q_rowmajor"], case["scales"], x_np, thr)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or reps >= 2000:
+            break
+    return dt / reps * 1e6, reps, oracle.threads()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=6400)
+    ap.add_argument("--warmup", type=int, default=640)
+    ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
+    ap.add_argument("--no-sweep", action="store_true", help="headline workload only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--full", action="store_true", help="also sweep the MLP / 70B shapes")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
+              "(sharding is described in DESIGN.md, not implemented)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2511_04477_amd as spqt
+    from workloads import CONFIG_SCALE_RANGE
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    spqt.lib()
+    use_graph = not args.eager
+    K_steps, W = args.steps, args.warmup
+
+    # ---------------- headline: config 2, 4096 x 4096, 50 % -------------------------------
+    M, K = 4096, 4096
+    wl = Workload(torch, spqt, M, K, "laplace", CONFIG_SCALE_RANGE[2], 2, "q", 0.5)
+    ok, max_err = wl.check_copy0()
+    if not ok:
+        print(f"bench.py: parity check against the oracle FAILED (max err {max_err})", file=sys.stderr)
+        sys.exit(1)
+    us_step = time_sequence(torch, wl.step, wl.copies, K_steps, W, use_graph)
+    us_gemv = time_sequence(torch, wl.gemv_only, wl.copies, K_steps, W, use_graph)
+    us_gather = time_sequence(torch, wl.gather_only, wl.copies, K_steps, W, use_graph)
+    us_dense = time_sequence(torch, wl.dense_only, wl.copies, K_steps, W, use_graph)
+    us_step_eager = time_sequence(torch, wl.step, wl.copies, min(K_steps, 2000), min(W, 200), False)
+
+    achieved = wl.mean_kept_bytes / (us_gemv * 1e-6) / 1e9
+    out = {
+        "metric": "us per GEMV (spqt_gather + sparse int4 GEMV), 50% activation sparsity, batch 1",
+        "value": round(us_step, 3),
+        "unit": "us/GEMV",
+        "n_gpus": 1, "steps": K_steps, "warmup": W,
+        "ms_per_step": round(us_step * 1e-3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int4 weights x fp16 activations, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: 4096x4096 int4 group-128, x~Laplace(0,1) fp16, threshold=50% quantile, batch 1",
+                   "M": M, "K": K, "sparsity": 0.5, "copies_rotated": wl.copies,
+                   "rotated_MB": round(wl.copies * spqt.spqt_packed_bytes(M, K) / 1e6, 1),
+                   "launch": "hipgraph replay" if use_graph else "stream launches",
+                   "mean_n_ns": float(np.mean(wl.n_ns))},
+        "effective_GBps_kept_bytes": round(wl.mean_kept_bytes / (us_step * 1e-6) / 1e9, 1),
+        "us_gemv_only": round(us_gemv, 3), "us_gather_only": round(us_gather, 3),
+        "us_dense_gemv": round(us_dense, 3), "speedup_vs_dense": round(us_dense / us_gemv, 3),
+        "us_step_stream_launches": round(us_step_eager, 3),
+        "oracle_max_abs_err": max_err,
+        "roofline": {"bound": "hbm", "kernel": "spqt_gemv_kernel<sparse>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "bytes_per_launch": wl.mean_kept_bytes, "us_per_launch": round(us_gemv, 3),
+                     "traffic": None},
+    }
+
+    # ---------------- sweeps ---------------------------------------------------------------
+    sweep = []
+    if not args.no_sweep:
+        shapes = [(2, "q", 4096, 4096, "laplace", [0.0, 0.25, 0.4, 0.65])]
+        shapes.append((5, "gate", 28672, 8192, "laplace", [0.5]))
+        if args.full:
+            shapes += [(3, "gate", 11008, 4096, "laplace", [0.4, 0.5]),
+                       (3, "down", 4096, 11008, "silu_product", [0.4, 0.5]),
+                       (4, "gate", 14336, 4096, "laplace", [0.5]),
+                       (4, "down", 4096, 14336, "laplace", [0.5]),
+                       (5, "gate", 28672, 8192, "laplace", [0.3, 0.7]),
+                       (5, "down", 8192, 28672, "laplace", [0.3, 0.5, 0.7])]
+        for config, tensor, m, k, dist, sps in shapes:
+            for s in sps:
+                w = wl if (m, k, s) == (M, K, 0.5) else Workload(torch, spqt, m, k, dist, CONFIG_SCALE_RANGE[config], config, tensor, s)
+                steps = max(w.copies * 4, min(K_steps, 1600))
+                t_g = time_sequence(torch, w.gemv_only, w.copies, steps, w.copies, use_graph)
+                t_d = time_sequence(torch, w.dense_only, w.copies, steps, w.copies, use_graph)
+                t_s = time_sequence(torch, w.step, w.copies, steps, w.copies, use_graph)
+                gb = w.mean_kept_bytes / (t_g * 1e-6) / 1e9
+                sweep.append({"config": config, "tensor": tensor, "M": m, "K": k, "sparsity": s,
+                              "kept_frac": round(float(np.mean(w.n_ns)) / k, 4),
+                              "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3),
+                              "GBps_kept": round(gb, 1), "frac_of_8TBps": round(gb / HBM_PEAK_GBPS, 4),
+                              "dense_GBps": round(w.dense_bytes / (t_d * 1e-6) / 1e9, 1),
+                              "speedup_vs_dense": round(t_d / t_g, 3)})
+                del w
+                torch.cuda.empty_cache()
+        out["sweep"] = sweep
+
+    # ---------------- CPU oracle baseline --------------------------------------------------
+    if not args.no_cpu:
+        us_cpu, reps, cores = cpu_baseline(wl.case0, wl.x_np[0:1], wl.thr[0])
+        out["cpu_baseline"] = {"value": round(us_cpu, 1), "unit": "us/GEMV", "cores": cores, "kind": "oracle",
+                               "sample": f"{reps} repeated oracle GEMVs (mask + dequantize + dot, fp64) on copy 0 of the same 4096x4096 50% workload"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -15,19 +15,22 @@
 //   - a wavefront step is one 16-byte load per lane = 8 kept columns x 128 bytes: lane
 //     (cg, seg) = (lane/8, lane%8) reads bytes [16 seg, 16 seg+16) of column cg of the step,
 //     i.e. 32 consecutive rows of one column, and keeps 32 fp32 accumulators.
-//   - the slice is consumed in passes of up to 128 columns that belong to ONE quantization
-//     group (idx is ascending, so a group is a contiguous run of the list).  Per pass the
-//     wave stages (byte offset, x) of its columns in LDS, so every lane fetches the pair for
-//     its column with one broadcast LDS read per step.
+//   - the slice is consumed in passes of up to 64 columns that belong to ONE quantization
+//     group (idx is ascending, so a group is a contiguous run of the list).  Lane l of a pass
+//     owns list entry pos+l: it computes the column's byte offset and fetches its x, and both
+//     are staged in LDS so that every lane can pick up the pair of the column it reads in a
+//     step.  The index entries of the next pass are requested before the weights of this one.
 //   - int4 -> float costs no conversion instruction: a stored code n in 0..15 masked in
 //     place at bit 0..3 (or 4..7) of a 16-bit half IS the fp16 subnormal n*2^-24 (or
 //     16n*2^-24), which v_fma_mix_f32 multiplies by a pre-scaled x*2^24 (x*2^20) into the fp32
-//     accumulator - exact products, fp32 accumulation.  The offset-binary bias (stored =
-//     q + 8) is removed by starting each pass's accumulators at -8 * sum of the lane's x.
-//   - the group scale is applied once per (row, pass): y_acc += scale * acc.
-//   - reduction: 8 column-lanes and WAVES wavefronts through LDS, then the S workgroups of a
-//     block-row through a workspace; the last one to arrive adds the partials in fixed order
-//     and writes y.  No floating-point atomics, so results are reproducible.
+//     accumulator - exact products, fp32 accumulation.
+//   - per group: the 8 column-lanes are folded with a transposing butterfly (permlane32/16
+//     swaps + one DPP rotate), leaving each lane 4 rows; the offset-binary bias (stored =
+//     q + 8) is removed there as -8 * (sum of the group's kept x), and the fp16 group scale is
+//     applied once per (row, group): y_acc += scale * (sum - bias).
+//   - WAVES wavefronts are combined through LDS, the S workgroups of a block-row through a
+//     workspace: the last one to arrive adds the partials in fixed order and writes y.  No
+//     floating-point atomics, so results are reproducible.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -42,7 +45,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kPassCols = 128;                 // most columns one pass stages (one group)
+constexpr int kPassCols = 64;                  // most columns one pass covers (8 steps)
 constexpr float kTwo24 = 16777216.0f;          // 2^24: undoes the fp16 subnormal exponent
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
@@ -74,14 +77,54 @@ __device__ __forceinline__ void fma_codes(uint32_t w, float xlo, float xhi, floa
     acc[7] = __builtin_fmaf((float)d.y, xhi, acc[7]);
 }
 
+// a and b are two accumulators of every lane.  Returns, in lanes 0..31, a summed over the
+// lane pair (l, l+32) and, in lanes 32..63, b summed over the same pair.
+__device__ __forceinline__ float fold32(float a, float b) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(as_u32(a), as_u32(b), false, false);
+    const uint32_t r0 = r.x, r1 = r.y;
+    return as_float(r0) + as_float(r1);
+}
+// Same for the lane pair (l, l^16): lanes with bit 4 clear get a's sum, the others b's.
+__device__ __forceinline__ float fold16(float a, float b) {
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(as_u32(a), as_u32(b), false, false);
+    const uint32_t r0 = r.x, r1 = r.y;
+    return as_float(r0) + as_float(r1);
+}
+// Value of lane l^8 (rotate by 8 inside each row of 16 lanes).
+__device__ __forceinline__ float from_xor8(float v) {
+    return as_float(__builtin_amdgcn_update_dpp(0u, as_u32(v), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+}
+
+// Fold the 32 accumulators of the 8 lanes that read the same rows (lanes seg, seg+8, ...,
+// seg+56).  Lane (cg, seg) ends with the complete sums of rows 32 seg + 4 cg + j, j = 0..3.
+__device__ __forceinline__ void fold_columns(const float *acc, bool bit3, float *out4) {
+    float v16[16], v8[8];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v16[i] = fold32(acc[i], acc[i + 16]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v8[i] = fold16(v16[i], v16[i + 8]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float keep = bit3 ? v8[i + 4] : v8[i];
+        const float send = bit3 ? v8[i] : v8[i + 4];
+        out4[i] = keep + from_xor8(send);
+    }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m);
+    return v;
+}
+
 template <int WAVES, bool DENSE>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    float *partials, int32_t *counters, int K, int NG, int S) {
-    // Per wave: 8 KB.  During the main loop its first 1 KB stages (offset, x) pairs; after
-    // the loop the whole 8 KB receives the wave's 64 x 32 partial sums.
-    __shared__ __attribute__((aligned(16))) float lds[WAVES][8 * kTileRows];
+    float *partials, int32_t *counters, int K, int NG, int S, int T) {
+    __shared__ uint32_t stage_off[WAVES][kPassCols];   // byte offset of each column of the pass
+    __shared__ float stage_x[WAVES][kPassCols];        // its x, pre-scaled by 2^24
+    __shared__ __attribute__((aligned(16))) float red[WAVES][kTileRows];
     __shared__ int is_last;
 
     const int tid = threadIdx.x;
@@ -89,8 +132,15 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cg = lane >> 3;      // column of the step this lane reads
     const int seg = lane & 7;      // 32-row segment of the tile this lane reads
-    const int t = blockIdx.x / S;  // block-row
-    const int s = blockIdx.x - t * S;
+    const bool bit3 = (lane & 8) != 0;
+    // Workgroups are handed to the 8 XCDs round-robin by index.  Keep all S workgroups of a
+    // block-row on ONE XCD (same index mod 8): their arrival counter then stays in that XCD's
+    // L2 instead of bouncing between dies.  Only a matter of speed, never of correctness.
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;          // position among this XCD's workgroups
+    const int t = xcd + 8 * (slot / S);        // block-row
+    const int s = slot % S;
+    if (t >= T) return;
 
     // Even split of the index list over the S*WAVES wavefronts of this block-row.
     const int n_ns = DENSE ? K : __builtin_amdgcn_readfirstlane(*count);
@@ -99,138 +149,148 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     int pos = (int)(((int64_t)n_ns * part) / parts);
     const int end = (int)(((int64_t)n_ns * (part + 1)) / parts);
 
-    u32x2 *stage = reinterpret_cast<u32x2 *>(lds[wave]);
+    uint32_t *my_off = stage_off[wave];
+    float *my_x = stage_x[wave];
     const uint8_t *row_base = packed + (size_t)t * NG * kChunkBytes;
 
-    float yacc[32];
+    // list entry pos + lane (-1 past the slice): the column this lane stages in the pass
+    auto fetch_k = [&](int p) -> int {
+        const int e = p + lane;
+        if (e >= end) return -1;
+        return DENSE ? e : idx[e];
+    };
+
+    float yacc[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // rows 32 seg + 4 cg + j, scaled and summed over groups
+    float acc[32];                               // current group, this lane's columns, unscaled
 #pragma unroll
-    for (int i = 0; i < 32; ++i) yacc[i] = 0.0f;
+    for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
+    float xsum = 0.0f;                           // current group: x (pre-scaled) of the columns this lane staged
+    u32x2 sc = {0u, 0u};                         // current group: fp16 scales of this lane's 4 rows
+    int g_cur = -1;
 
+    // fold the finished group into yacc
+    auto flush = [&]() {
+        float r4[4];
+        fold_columns(acc, bit3, r4);
+        const float bias = wave_sum(xsum) * (-8.0f / kTwo24);
+        const uint32_t s01 = sc.x, s23 = sc.y;
+        const f16x2 h01 = as_f16x2(s01), h23 = as_f16x2(s23);
+        yacc[0] = __builtin_fmaf((float)h01.x, r4[0] + bias, yacc[0]);
+        yacc[1] = __builtin_fmaf((float)h01.y, r4[1] + bias, yacc[1]);
+        yacc[2] = __builtin_fmaf((float)h23.x, r4[2] + bias, yacc[2]);
+        yacc[3] = __builtin_fmaf((float)h23.y, r4[3] + bias, yacc[3]);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
+        xsum = 0.0f;
+    };
+
+    int k = fetch_k(pos);
     while (pos < end) {
-        // ---- stage up to 128 kept columns that share the group of idx[pos] ---------------
-        const int e0 = pos + lane, e1 = pos + 64 + lane;
-        int k0 = -1, k1 = -1;
-        if (e0 < end) k0 = DENSE ? e0 : idx[e0];
-        if (e1 < end) k1 = DENSE ? e1 : idx[e1];
-        const int g = __builtin_amdgcn_readfirstlane(k0) >> 7;
-        const bool in0 = (k0 >> 7) == g, in1 = (k1 >> 7) == g;
-        const int n = __builtin_amdgcn_readfirstlane(__popcll(__ballot(in0)) + __popcll(__ballot(in1)));
+        // ---- the pass: the run of list entries from pos that share the group of idx[pos] ----
+        const int g = __builtin_amdgcn_readfirstlane(k) >> 7;
+        const bool in = (k >> 7) == g;
+        const int n = __builtin_amdgcn_readfirstlane((int)__popcll(__ballot(in)));
+        const int k_next = fetch_k(pos + n);                 // next pass's entries: request early
 
-        float x0 = 0.0f, x1 = 0.0f;
-        if (in0) x0 = half_bits_to_float(x[k0]) * kTwo24;
-        if (in1) x1 = half_bits_to_float(x[k1]) * kTwo24;
-        u32x2 s0v = {in0 ? (uint32_t)(k0 & (kGroup - 1)) * kColBytes : 0u, as_u32(x0)};
-        u32x2 s1v = {in1 ? (uint32_t)(k1 & (kGroup - 1)) * kColBytes : 0u, as_u32(x1)};
-        stage[lane] = s0v;
-        stage[64 + lane] = s1v;
-
-        // Sum of the (pre-scaled) x of the columns this lane will visit: columns 8u + cg.
-        float z = x0 + x1;
-        z += __shfl_xor(z, 8);
-        z += __shfl_xor(z, 16);
-        z += __shfl_xor(z, 32);           // lane l now holds the sum over columns = l mod 8
-        z = __shfl(z, cg);
-        const float bias = z * (-8.0f / kTwo24);
+        const uint32_t koff = in ? (uint32_t)(k & (kGroup - 1)) * kColBytes : 0u;
+        uint32_t xraw = 0u;
+        if (in) xraw = x[k];
+        my_off[lane] = koff;
 
         const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;
-        // this lane's 32 scales (rows 32 seg .. 32 seg + 31), 64 bytes
-        u32x4 sc[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            sc[i] = *reinterpret_cast<const u32x4 *>(chunk + seg * 64 + i * 16);
-
-        float acc[32];
-#pragma unroll
-        for (int i = 0; i < 32; ++i) acc[i] = bias;
-
         const uint8_t *cols = chunk + kScaleBytes + seg * 16;
-        __builtin_amdgcn_wave_barrier();   // staging writes above, reads below: same wave, LDS is in order
+        __builtin_amdgcn_wave_barrier();
 
-        for (int c0 = 0; c0 < n; c0 += 64) {
-            u32x4 w[8];
-            float xl[8];
+        // ---- request this pass's weights: one 16-byte load per lane and step ---------------
+        u32x4 w[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                w[u] = u32x4{0u, 0u, 0u, 0u};
-                xl[u] = 0.0f;
-                if (c0 + u * 8 < n) {                     // wave-uniform: skip empty steps
-                    const int e = c0 + u * 8 + cg;
-                    const u32x2 ox = stage[e];
-                    xl[u] = as_float(ox.y);
-                    if (e < n)
-                        w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(cols + ox.x));
-                }
+        for (int u = 0; u < 8; ++u) {
+            w[u] = u32x4{0u, 0u, 0u, 0u};
+            if (u * 8 < n) {                                   // wave-uniform: skip empty steps
+                const int e = u * 8 + cg;
+                const uint32_t o = my_off[e];
+                if (e < n) w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(cols + o));
             }
+        }
+
+        // ---- group change: fold the finished group while the loads are in flight -----------
+        if (g != g_cur) {
+            if (g_cur >= 0) flush();
+            g_cur = g;
+            sc = *reinterpret_cast<const u32x2 *>(chunk + seg * 64 + cg * 8);
+        }
+
+        const float xs = half_bits_to_float(xraw) * kTwo24;   // 0 for lanes outside the pass
+        xsum += xs;
+        my_x[lane] = xs;
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- multiply-accumulate ------------------------------------------------------------
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (c0 + u * 8 < n) {
-                    const float xh = xl[u] * 0.0625f;
-                    fma_codes(w[u].x, xl[u], xh, acc + 0);
-                    fma_codes(w[u].y, xl[u], xh, acc + 8);
-                    fma_codes(w[u].z, xl[u], xh, acc + 16);
-                    fma_codes(w[u].w, xl[u], xh, acc + 24);
-                }
+        for (int u = 0; u < 8; ++u) {
+            if (u * 8 < n) {
+                const float xl = my_x[u * 8 + cg];
+                const float xh = xl * 0.0625f;
+                fma_codes(w[u].x, xl, xh, acc + 0);
+                fma_codes(w[u].y, xl, xh, acc + 8);
+                fma_codes(w[u].z, xl, xh, acc + 16);
+                fma_codes(w[u].w, xl, xh, acc + 24);
             }
         }
         __builtin_amdgcn_wave_barrier();
-
-        // ---- apply the group scale once per row ------------------------------------------
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const f16x2 h = as_f16x2(sc[i][d]);
-                const int r = i * 8 + d * 2;
-                yacc[r] = __builtin_fmaf((float)h.x, acc[r], yacc[r]);
-                yacc[r + 1] = __builtin_fmaf((float)h.y, acc[r + 1], yacc[r + 1]);
-            }
-        }
         pos += n;
+        k = k_next;
     }
+    if (g_cur >= 0) flush();
 
-    // ---- reduce: 8 column-lanes x WAVES wavefronts, through LDS -------------------------
-    // float index inside a wave's region: ((cg*8 + q)*8 + seg)*4 + j  <->  row 32 seg + 4 q + j
-    __builtin_amdgcn_wave_barrier();
-    f32x4 *mine = reinterpret_cast<f32x4 *>(lds[wave]);
-#pragma unroll
-    for (int q = 0; q < 8; ++q)
-        mine[(cg * 8 + q) * 8 + seg] = f32x4{yacc[4 * q], yacc[4 * q + 1], yacc[4 * q + 2], yacc[4 * q + 3]};
+    // ---- combine the WAVES wavefronts through LDS ------------------------------------------
+    reinterpret_cast<f32x4 *>(red[wave])[8 * seg + cg] = f32x4{yacc[0], yacc[1], yacc[2], yacc[3]};
     __syncthreads();
 
-    // element e of the 256-entry tile vector in "LDS order"; its output row:
-    auto row_of = [](int e) { return ((e >> 2) & 7) * 32 + (e >> 5) * 4 + (e & 3); };
-
-    float *my_partial = partials + ((size_t)blockIdx.x) * kTileRows;
-    for (int e = tid; e < kTileRows; e += WAVES * 64) {
+    float *my_partial = partials + ((size_t)t * S + s) * kTileRows;
+    for (int r = tid; r < kTileRows; r += WAVES * 64) {
         float sum = 0.0f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) sum += lds[w][c * kTileRows + e];
+        for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2][r];
         if (S == 1)
-            y[(size_t)t * kTileRows + row_of(e)] = sum;
+            y[(size_t)t * kTileRows + r] = sum;
         else
-            __hip_atomic_store(my_partial + e, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(my_partial + r, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (S == 1) return;
 
-    // ---- combine the S workgroups of this block-row: last arrival adds in fixed order ----
-    __threadfence();
+    // ---- combine the S workgroups of this block-row: last arrival adds in fixed order ------
+    // The partials are written and read with device-scope atomic accesses (they go through to
+    // the device-coherent level instead of staying in one XCD's L2), so the only ordering
+    // needed is "my stores have completed before my arrival is counted" and "the count is read
+    // before the partials are": a wait on the memory counters plus the workgroup barrier, not a
+    // cache-wide write-back and invalidate.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0) {
-        const int prev = __hip_atomic_fetch_add(counters + t, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        const int prev = __hip_atomic_fetch_add(counters + t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (prev == S - 1);
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const float *tile_partials = partials + (size_t)t * S * kTileRows;
-    for (int e = tid; e < kTileRows; e += WAVES * 64) {
+    for (int r = tid; r < kTileRows; r += WAVES * 64) {
+        // request the partials in batches so their latencies overlap; add in index order
         float sum = 0.0f;
-        for (int k = 0; k < S; ++k)
-            sum += __hip_atomic_load(tile_partials + (size_t)k * kTileRows + e, __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT);
-        y[(size_t)t * kTileRows + row_of(e)] = sum;
+        for (int p0 = 0; p0 < S; p0 += 16) {
+            float v[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                v[j] = 0.0f;
+                if (p0 + j < S)
+                    v[j] = __hip_atomic_load(tile_partials + (size_t)(p0 + j) * kTileRows + r,
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sum += v[j];
+        }
+        y[(size_t)t * kTileRows + r] = sum;
     }
     if (tid == 0) __hip_atomic_store(counters + t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -243,13 +303,13 @@ __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
 template <int WAVES>
 hipError_t launch(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                   const int32_t *idx, const int32_t *count, float *y, float *partials,
-                  int32_t *counters, int K, int NG, int S) {
+                  int32_t *counters, int K, int NG, int S, int T) {
     if (dense)
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, counters, K, NG, S);
+                           packed, x, idx, count, y, partials, counters, K, NG, S, T);
     else
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, counters, K, NG, S);
+                           packed, x, idx, count, y, partials, counters, K, NG, S, T);
     return hipGetLastError();
 }
 
@@ -328,7 +388,7 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
     }
 
     const int T = (int)(M / kTileRows), NG = (int)(K / kGroup);
-    const int grid = T * c.splits;
+    const int grid = 8 * ((T + 7) / 8) * c.splits;
     const bool dense = idx_dev == nullptr;
     hipStream_t st = (hipStream_t)stream;
     // batch > 1: one pass per row over the shared (union) index list; each row uses its own
@@ -338,9 +398,9 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
         float *yb = y_dev + (size_t)b * M;
         hipError_t err;
         switch (c.waves) {
-            case 1: err = launch<1>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits); break;
-            case 2: err = launch<2>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits); break;
-            default: err = launch<4>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits); break;
+            case 1: err = launch<1>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits, T); break;
+            case 2: err = launch<2>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits, T); break;
+            default: err = launch<4>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits, T); break;
         }
         if (err != hipSuccess) return SPQT_EHIP;
     }

@@ -10,6 +10,10 @@ from .synth import (  # noqa: F401
     GROUP,
     TILE_ROWS,
     CONFIG_SHAPES,
+    CONFIG_SCALE_RANGE,
+    KIND_WEIGHTS,
+    KIND_X,
+    KIND_CALIB,
     seed_for,
     make_weights,
     make_x,
