@@ -58,62 +58,96 @@ __device__ __forceinline__ float as_float(uint32_t bits) { return __builtin_bit_
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t bits) { return __builtin_bit_cast(f16x2, bits); }
 
-// Eight codes of one dword: acc[i] += n_i * x for nibble i (row 8d+i of the lane's 32 rows).
+// Eight codes of one dword: acc[i] (+)= n_i * x for nibble i (row 8d+i of the lane's 32 rows).
 // xlo = x * 2^24 pairs with nibbles sitting at bits 0..3 of a half, xhi = x * 2^20 with
-// nibbles at bits 4..7 (value 16 n * 2^-24).
+// nibbles at bits 4..7 (value 16 n * 2^-24).  INIT overwrites the accumulators (first step of
+// a group) instead of adding to them.
+template <bool INIT>
 __device__ __forceinline__ void fma_codes(uint32_t w, float xlo, float xhi, float *acc) {
     const uint32_t w8 = w >> 8;
     const f16x2 a = as_f16x2(w & 0x000F000Fu);    // nibbles 0, 4
     const f16x2 b = as_f16x2(w & 0x00F000F0u);    // nibbles 1, 5
     const f16x2 c = as_f16x2(w8 & 0x000F000Fu);   // nibbles 2, 6
     const f16x2 d = as_f16x2(w8 & 0x00F000F0u);   // nibbles 3, 7
-    acc[0] = __builtin_fmaf((float)a.x, xlo, acc[0]);
-    acc[4] = __builtin_fmaf((float)a.y, xlo, acc[4]);
-    acc[1] = __builtin_fmaf((float)b.x, xhi, acc[1]);
-    acc[5] = __builtin_fmaf((float)b.y, xhi, acc[5]);
-    acc[2] = __builtin_fmaf((float)c.x, xlo, acc[2]);
-    acc[6] = __builtin_fmaf((float)c.y, xlo, acc[6]);
-    acc[3] = __builtin_fmaf((float)d.x, xhi, acc[3]);
-    acc[7] = __builtin_fmaf((float)d.y, xhi, acc[7]);
+    acc[0] = __builtin_fmaf((float)a.x, xlo, INIT ? 0.0f : acc[0]);
+    acc[4] = __builtin_fmaf((float)a.y, xlo, INIT ? 0.0f : acc[4]);
+    acc[1] = __builtin_fmaf((float)b.x, xhi, INIT ? 0.0f : acc[1]);
+    acc[5] = __builtin_fmaf((float)b.y, xhi, INIT ? 0.0f : acc[5]);
+    acc[2] = __builtin_fmaf((float)c.x, xlo, INIT ? 0.0f : acc[2]);
+    acc[6] = __builtin_fmaf((float)c.y, xlo, INIT ? 0.0f : acc[6]);
+    acc[3] = __builtin_fmaf((float)d.x, xhi, INIT ? 0.0f : acc[3]);
+    acc[7] = __builtin_fmaf((float)d.y, xhi, INIT ? 0.0f : acc[7]);
+}
+
+template <bool INIT>
+__device__ __forceinline__ void fma_step(u32x4 w, float xl, float *acc) {
+    const float xh = xl * 0.0625f;
+    fma_codes<INIT>(w.x, xl, xh, acc + 0);
+    fma_codes<INIT>(w.y, xl, xh, acc + 8);
+    fma_codes<INIT>(w.z, xl, xh, acc + 16);
+    fma_codes<INIT>(w.w, xl, xh, acc + 24);
 }
 
 // a and b are two accumulators of every lane.  Returns, in lanes 0..31, a summed over the
-// lane pair (l, l+32) and, in lanes 32..63, b summed over the same pair.
-__device__ __forceinline__ float fold32(float a, float b) {
-    const u32x2 r = __builtin_amdgcn_permlane32_swap(as_u32(a), as_u32(b), false, false);
-    const uint32_t r0 = r.x, r1 = r.y;
-    return as_float(r0) + as_float(r1);
+// lane pair (l, l+32) and, in lanes 32..63, b summed over the same pair.  The swap works in
+// place on both registers (written as asm so that no copies are made; the two wait states it
+// needs after a VALU write of its operands are provided here); a and b are clobbered.
+__device__ __forceinline__ float fold32(float &a, float &b) {
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
 }
 // Same for the lane pair (l, l^16): lanes with bit 4 clear get a's sum, the others b's.
-__device__ __forceinline__ float fold16(float a, float b) {
-    const u32x2 r = __builtin_amdgcn_permlane16_swap(as_u32(a), as_u32(b), false, false);
-    const uint32_t r0 = r.x, r1 = r.y;
-    return as_float(r0) + as_float(r1);
+__device__ __forceinline__ float fold16(float &a, float &b) {
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
 }
 // Value of lane l^8 (rotate by 8 inside each row of 16 lanes).
 __device__ __forceinline__ float from_xor8(float v) {
     return as_float(__builtin_amdgcn_update_dpp(0u, as_u32(v), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
 }
 
-// Fold the 32 accumulators of the 8 lanes that read the same rows (lanes seg, seg+8, ...,
-// seg+56).  Lane (cg, seg) ends with the complete sums of rows 32 seg + 4 cg + j, j = 0..3.
-__device__ __forceinline__ void fold_columns(const float *acc, bool bit3, float *out4) {
-    float v16[16], v8[8];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) v16[i] = fold32(acc[i], acc[i + 16]);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v8[i] = fold16(v16[i], v16[i + 8]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float keep = bit3 ? v8[i + 4] : v8[i];
-        const float send = bit3 ? v8[i] : v8[i + 4];
-        out4[i] = keep + from_xor8(send);
-    }
+// For lane pairs (l, l^8), inside every row of 16 lanes: lanes with bit 3 clear receive a
+// summed over the pair, lanes with bit 3 set receive b summed over the pair.  Two DPP adds
+// that each write only half of the row (bank masks), in place in b's register.  The leading
+// wait states cover a VALU write of a or b just before.
+__device__ __forceinline__ void fold8_into_b(float a, float &b) {
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3"
+        : "+v"(b)
+        : "v"(a));
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
+// Fold the 32 accumulators of the 8 lanes that read the same rows (lanes seg, seg+8, ...,
+// seg+56), halving the number of live values at each of the three levels.  Lane (cg, seg)
+// ends with the complete sums of rows 32 seg + 4 rev(cg) + j, j = 0..3, where rev reverses
+// the three bits of cg (level 1 splits on lane bit 3, level 2 on bit 4, level 3 on bit 5).
+__device__ __forceinline__ void fold_columns(float *acc, float *out4) {
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m);
+    for (int i = 0; i < 16; ++i) fold8_into_b(acc[i], acc[i + 16]);     // -> acc[16..31]
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = fold16(acc[16 + i], acc[24 + i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out4[i] = fold32(acc[i], acc[4 + i]);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return as_float(__builtin_amdgcn_update_dpp(0u, as_u32(v), CTRL, 0xf, 0xf, false));
+}
+
+// Sum over the 64 lanes, returned in every lane: xor-butterfly inside rows of 16 with DPP
+// (quad permutes, half-row and row mirrors), then across rows with the permlane swaps.
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+    v += dpp_move<0x141>(v);   // row_half_mirror: the other quad of the 8
+    v += dpp_move<0x140>(v);   // row_mirror: the other half of the row
+    float t = v;
+    v = fold16(v, t);
+    t = v;
+    v = fold32(v, t);
     return v;
 }
 
@@ -122,8 +156,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
     float *partials, int32_t *counters, int K, int NG, int S, int T) {
-    __shared__ uint32_t stage_off[WAVES][kPassCols];   // byte offset of each column of the pass
-    __shared__ float stage_x[WAVES][kPassCols];        // its x, pre-scaled by 2^24
+    // Two staging slots per wave (the pass being multiplied and the pass being fetched).
+    __shared__ uint32_t stage_off[WAVES][2][kPassCols];   // byte offset of each column of the pass
+    __shared__ float stage_x[WAVES][2][kPassCols];        // its x, pre-scaled by 2^24
     __shared__ __attribute__((aligned(16))) float red[WAVES][kTileRows];
     __shared__ int is_last;
 
@@ -132,7 +167,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cg = lane >> 3;      // column of the step this lane reads
     const int seg = lane & 7;      // 32-row segment of the tile this lane reads
-    const bool bit3 = (lane & 8) != 0;
+    const int cgr = ((cg & 1) << 2) | (cg & 2) | (cg >> 2);   // cg with its three bits reversed
+    const uint32_t seg16 = (uint32_t)seg * 16u;              // this lane's bytes inside a column run
+    const uint32_t sc_off = (uint32_t)(seg * 64 + cgr * 8);  // this lane's 4 scales inside a chunk
     // Workgroups are handed to the 8 XCDs round-robin by index.  Keep all S workgroups of a
     // block-row on ONE XCD (same index mod 8): their arrival counter then stays in that XCD's
     // L2 instead of bouncing between dies.  Only a matter of speed, never of correctness.
@@ -149,102 +186,119 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     int pos = (int)(((int64_t)n_ns * part) / parts);
     const int end = (int)(((int64_t)n_ns * (part + 1)) / parts);
 
-    uint32_t *my_off = stage_off[wave];
-    float *my_x = stage_x[wave];
     const uint8_t *row_base = packed + (size_t)t * NG * kChunkBytes;
 
-    // list entry pos + lane (-1 past the slice): the column this lane stages in the pass
-    auto fetch_k = [&](int p) -> int {
-        const int e = p + lane;
-        if (e >= end) return -1;
-        return DENSE ? e : idx[e];
-    };
+    float yacc[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // rows 32 seg + 4 rev(cg) + j, scaled and summed over groups
 
-    float yacc[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // rows 32 seg + 4 cg + j, scaled and summed over groups
-    float acc[32];                               // current group, this lane's columns, unscaled
-#pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-    float xsum = 0.0f;                           // current group: x (pre-scaled) of the columns this lane staged
-    u32x2 sc = {0u, 0u};                         // current group: fp16 scales of this lane's 4 rows
-    int g_cur = -1;
+    if (pos < end) {
+        // List entry p + lane, or -1 past the slice.  The load itself is never predicated
+        // (the index is clamped): every pass issues the same number of memory operations, so
+        // the multiply stage can wait for exactly its own loads while the next pass's fly.
+        auto fetch_k = [&](int p) -> int {
+            const int e = p + lane;
+            if (DENSE) return e < end ? e : -1;
+            const int v = idx[e < n_ns ? e : n_ns - 1];
+            return e < end ? v : -1;
+        };
 
-    // fold the finished group into yacc
-    auto flush = [&]() {
-        float r4[4];
-        fold_columns(acc, bit3, r4);
-        const float bias = wave_sum(xsum) * (-8.0f / kTwo24);
-        const uint32_t s01 = sc.x, s23 = sc.y;
-        const f16x2 h01 = as_f16x2(s01), h23 = as_f16x2(s23);
-        yacc[0] = __builtin_fmaf((float)h01.x, r4[0] + bias, yacc[0]);
-        yacc[1] = __builtin_fmaf((float)h01.y, r4[1] + bias, yacc[1]);
-        yacc[2] = __builtin_fmaf((float)h23.x, r4[2] + bias, yacc[2]);
-        yacc[3] = __builtin_fmaf((float)h23.y, r4[3] + bias, yacc[3]);
+        float acc[32];                  // current group, this lane's columns, unscaled
 #pragma unroll
         for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-        xsum = 0.0f;
-    };
+        float xsum = 0.0f;              // current group: pre-scaled x of the columns this lane staged
 
-    int k = fetch_k(pos);
-    while (pos < end) {
-        // ---- the pass: the run of list entries from pos that share the group of idx[pos] ----
-        const int g = __builtin_amdgcn_readfirstlane(k) >> 7;
-        const bool in = (k >> 7) == g;
-        const int n = __builtin_amdgcn_readfirstlane((int)__popcll(__ballot(in)));
-        const int k_next = fetch_k(pos + n);                 // next pass's entries: request early
-
-        const uint32_t koff = in ? (uint32_t)(k & (kGroup - 1)) * kColBytes : 0u;
-        uint32_t xraw = 0u;
-        if (in) xraw = x[k];
-        my_off[lane] = koff;
-
-        const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;
-        const uint8_t *cols = chunk + kScaleBytes + seg * 16;
-        __builtin_amdgcn_wave_barrier();
-
-        // ---- request this pass's weights: one 16-byte load per lane and step ---------------
-        u32x4 w[8];
+        // FETCH stage of the pass that starts at list position p (kk = fetch_k(p)): delimit the
+        // pass (the run of entries that share the group of idx[p], at most 64), request the
+        // NEXT pass's entries, this pass's x, its weights (8 steps, always) and its scales.
+        // Past the end of the slice (p >= end) it degenerates to n = 0 with harmless re-reads.
+        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, int &g_out, uint32_t &xraw_out,
+                         u32x2 &sc_out, int &k_after) {
+            const bool any = p < end;
+            const int g = any ? (__builtin_amdgcn_readfirstlane(kk) >> 7) : 0;
+            const bool in = any && ((kk >> 7) == g);
+            const int n = __builtin_amdgcn_readfirstlane((int)__popcll(__ballot(in)));
+            k_after = fetch_k(p + n);
+            // Lanes outside the pass point at the pass's first column and later carry x = 0:
+            // they re-read a line that is being fetched anyway.
+            const uint32_t koff_in = (uint32_t)(kk & (kGroup - 1)) * kColBytes;
+            const uint32_t koff_first = any ? (uint32_t)__builtin_amdgcn_readfirstlane((int)koff_in) : 0u;
+            xraw_out = x[in ? kk : 0];
+            stage_off[wave][slot][lane] = in ? koff_in : koff_first;
+            const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;   // wave-uniform base
+            __builtin_amdgcn_wave_barrier();
+            uint32_t off[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            w[u] = u32x4{0u, 0u, 0u, 0u};
-            if (u * 8 < n) {                                   // wave-uniform: skip empty steps
-                const int e = u * 8 + cg;
-                const uint32_t o = my_off[e];
-                if (e < n) w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(cols + o));
-            }
-        }
-
-        // ---- group change: fold the finished group while the loads are in flight -----------
-        if (g != g_cur) {
-            if (g_cur >= 0) flush();
-            g_cur = g;
-            sc = *reinterpret_cast<const u32x2 *>(chunk + seg * 64 + cg * 8);
-        }
-
-        const float xs = half_bits_to_float(xraw) * kTwo24;   // 0 for lanes outside the pass
-        xsum += xs;
-        my_x[lane] = xs;
-        __builtin_amdgcn_wave_barrier();
-
-        // ---- multiply-accumulate ------------------------------------------------------------
+            for (int u = 0; u < 8; ++u) off[u] = stage_off[wave][slot][u * 8 + cg] + seg16;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            if (u * 8 < n) {
-                const float xl = my_x[u * 8 + cg];
-                const float xh = xl * 0.0625f;
-                fma_codes(w[u].x, xl, xh, acc + 0);
-                fma_codes(w[u].y, xl, xh, acc + 8);
-                fma_codes(w[u].z, xl, xh, acc + 16);
-                fma_codes(w[u].w, xl, xh, acc + 24);
+            for (int u = 0; u < 8; ++u)
+                w[u] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(chunk + kScaleBytes + (size_t)off[u]));
+            sc_out = *reinterpret_cast<const u32x2 *>(chunk + (size_t)sc_off);
+            n_out = n;
+            g_out = g;
+        };
+
+        // MULTIPLY stage of a fetched pass.
+        auto multiply = [&](int n, uint32_t xraw, int slot, const u32x4(&w)[8]) {
+            const float xs = lane < n ? half_bits_to_float(xraw) * kTwo24 : 0.0f;
+            xsum += xs;
+            stage_x[wave][slot][lane] = xs;
+            __builtin_amdgcn_wave_barrier();
+            float xl[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) xl[u] = stage_x[wave][slot][u * 8 + cg];
+            fma_step<false>(w[0], xl[0], acc);
+#pragma unroll
+            for (int u = 1; u < 8; ++u)
+                if (u * 8 < n) fma_step<false>(w[u], xl[u], acc);
+            __builtin_amdgcn_wave_barrier();
+        };
+
+        // Fold the finished group (whose scales are `sc`) into yacc.
+        auto flush = [&](u32x2 sc) {
+            float r4[4];
+            fold_columns(acc, r4);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
+            const float bias = wave_sum(xsum) * (-8.0f / kTwo24);
+            const uint32_t s01 = sc.x, s23 = sc.y;
+            const f16x2 h01 = as_f16x2(s01), h23 = as_f16x2(s23);
+            yacc[0] = __builtin_fmaf((float)h01.x, r4[0] + bias, yacc[0]);
+            yacc[1] = __builtin_fmaf((float)h01.y, r4[1] + bias, yacc[1]);
+            yacc[2] = __builtin_fmaf((float)h23.x, r4[2] + bias, yacc[2]);
+            yacc[3] = __builtin_fmaf((float)h23.y, r4[3] + bias, yacc[3]);
+            xsum = 0.0f;
+        };
+
+        // Two-stage software pipeline over the passes, buffers A and B alternating.
+        u32x4 wA[8], wB[8];
+        u32x2 scA, scB;
+        uint32_t xrA, xrB;
+        int nA, nB, gA, gB, kA, kB;
+        kA = fetch_k(pos);
+        fetch(kA, pos, 0, wA, nA, gA, xrA, scA, kB);
+        for (;;) {
+            const int posB = pos + nA;
+            fetch(kB, posB, 1, wB, nB, gB, xrB, scB, kA);
+            multiply(nA, xrA, 0, wA);
+            if (posB >= end) {
+                flush(scA);
+                break;
             }
+            if (gB != gA) flush(scA);
+            const int posA = posB + nB;
+            fetch(kA, posA, 0, wA, nA, gA, xrA, scA, kB);
+            multiply(nB, xrB, 1, wB);
+            if (posA >= end) {
+                flush(scB);
+                break;
+            }
+            if (gA != gB) flush(scB);
+            pos = posA;
         }
-        __builtin_amdgcn_wave_barrier();
-        pos += n;
-        k = k_next;
     }
-    if (g_cur >= 0) flush();
 
     // ---- combine the WAVES wavefronts through LDS ------------------------------------------
-    reinterpret_cast<f32x4 *>(red[wave])[8 * seg + cg] = f32x4{yacc[0], yacc[1], yacc[2], yacc[3]};
+    reinterpret_cast<f32x4 *>(red[wave])[8 * seg + cgr] = f32x4{yacc[0], yacc[1], yacc[2], yacc[3]};
     __syncthreads();
 
     float *my_partial = partials + ((size_t)t * S + s) * kTileRows;
