@@ -23,6 +23,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
+# HBM bytes per sparse-GEMV launch on the headline workload, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE scaled by a plain copy kernel of known size (profiles/spqt_gemv_sparse_4096x4096_s50.md).
+MEASURED_TRAFFIC_BYTES = {(4096, 4096, 0.5): 5126991}
 INFINITY_CACHE_BYTES = 256 << 20
 ROTATE_BYTES = 3 * INFINITY_CACHE_BYTES   # rotate over at least this many bytes of weights
 
@@ -152,6 +155,50 @@ def time_sequence(torch, fn, copies, steps, warmup, use_graph=True):
     return start.elapsed_time(stop) * 1e3 / steps
 
 
+class Calib:
+    """ctypes face of libspqt_calib.so: plain streaming read / copy / empty launch, used to put the
+    GEMV numbers next to what a trivial kernel reaches on the same box."""
+
+    def __init__(self, torch):
+        import ctypes
+        self.torch = torch
+        path = os.path.join(ROOT, "paper_2511_04477_amd", "libspqt_calib.so")
+        L = ctypes.CDLL(path)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.spqt_calib_read.argtypes = [vp, sz, vp, i32, i32, vp]
+        L.spqt_calib_copy.argtypes = [vp, vp, sz, i32, vp]
+        L.spqt_calib_empty.argtypes = [vp]
+        self.L = L
+        self.sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+
+    def stream(self):
+        return self.torch.cuda.current_stream().cuda_stream
+
+    def empty(self, _i=0):
+        self.L.spqt_calib_empty(self.stream())
+
+    def read(self, buf, offset, nbytes, blocks=0, unroll=4):
+        self.L.spqt_calib_read(buf.data_ptr() + offset, nbytes, self.sink.data_ptr(), blocks, unroll, self.stream())
+
+    def copy(self, dst, src, nbytes):
+        self.L.spqt_calib_copy(dst.data_ptr(), src.data_ptr(), nbytes, 0, self.stream())
+
+
+def calibrate(torch, nbytes_like):
+    """(empty-launch us, us of a plain cold streaming read of ~nbytes_like bytes, GB/s of a 1 GiB read)."""
+    cal = Calib(torch)
+    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 256)
+    t_empty = time_sequence(torch, cal.empty, 100, 2000, 200, True)
+    size = max(1 << 20, (int(nbytes_like) + 65535) // 65536 * 65536)
+    k = (1 << 30) // size
+    blocks = max(64, min(4096, size // 16 // 256 // 2))
+    t_small = time_sequence(torch, lambda i: cal.read(big, (i % k) * size, size, blocks, 2), k, 2 * k, k, True)
+    t_big = time_sequence(torch, lambda i: cal.read(big, 0, 1 << 30, 8192, 4), 2, 6, 2, True)
+    del big
+    torch.cuda.empty_cache()
+    return t_empty, t_small, size, (1 << 30) / (t_big * 1e-6) / 1e9
+
+
 def cpu_baseline(case, x_np, thr, budget_s=12.0):
     """The oracle as it stands, timed on the host cores, on repeated calls for about budget_s."""
     import oracle
@@ -176,6 +223,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--full", action="store_true", help="also sweep the MLP / 70B shapes")
+    ap.add_argument("--pmc-pass", action="store_true",
+                    help="for hardware-counter runs: launch only a 64 MiB calibration copy (x8) and the "
+                         "headline sparse GEMV once per weight copy, eagerly, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
@@ -199,6 +249,18 @@ def main():
     if not ok:
         print(f"bench.py: parity check against the oracle FAILED (max err {max_err})", file=sys.stderr)
         sys.exit(1)
+    if args.pmc_pass:
+        cal = Calib(torch)
+        a = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 256)
+        b = torch.empty_like(a)
+        for _ in range(8):
+            cal.copy(b, a, 64 << 20)
+        for i in range(wl.copies):
+            wl.gemv_only(i)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_pass": True, "copy_bytes": 64 << 20, "gemv_launches": wl.copies,
+                          "kept_bytes_per_launch": wl.mean_kept_bytes, "y_bytes_per_launch": 4 * M}))
+        return
     us_step = time_sequence(torch, wl.step, wl.copies, K_steps, W, use_graph)
     us_gemv = time_sequence(torch, wl.gemv_only, wl.copies, K_steps, W, use_graph)
     us_gather = time_sequence(torch, wl.gather_only, wl.copies, K_steps, W, use_graph)
@@ -230,8 +292,15 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "spqt_gemv_kernel<sparse>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "bytes_per_launch": wl.mean_kept_bytes, "us_per_launch": round(us_gemv, 3),
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((M, K, 0.5))},
     }
+
+    # ---------------- context: what trivial kernels reach on this machine ----------------------
+    t_empty, t_read, read_bytes, big_gbps = calibrate(torch, wl.mean_kept_bytes)
+    out["context"] = {"empty_launch_us": round(t_empty, 3),
+                      "plain_read_same_bytes_us": round(t_read, 3), "plain_read_bytes": read_bytes,
+                      "plain_read_1GiB_GBps": round(big_gbps, 1),
+                      "note": "plain streaming read of the same byte count, cold, same graph-replay timing: the practical floor for one launch"}
 
     # ---------------- sweeps ---------------------------------------------------------------
     sweep = []

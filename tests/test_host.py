@@ -15,10 +15,22 @@ from workloads import make_weights
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "spqt.h")).read()
+def declared_functions(header="spqt.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(spqt_[a-z_]+)\s*\(", text)))
+
+
+def test_calibration_library_exports_every_declared_symbol():
+    L = ctypes.CDLL(os.path.join(ROOT, "paper_2511_04477_amd", "libspqt_calib.so"))
+    names = declared_functions("spqt_calib.h")
+    assert names == ["spqt_calib_copy", "spqt_calib_empty", "spqt_calib_read"]
+    for n in names:
+        assert getattr(L, n) is not None
+    # argument checks happen before any launch
+    L.spqt_calib_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    assert L.spqt_calib_read(None, 16, None, 0, 4, None) == -1
+    assert L.spqt_calib_read(16, 24, 16, 0, 4, None) == -1
 
 
 def test_library_exports_every_declared_symbol():
