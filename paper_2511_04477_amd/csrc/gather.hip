@@ -5,9 +5,11 @@
 // to the position the scan gives it, so the list is contiguous.  The paper scans 1024-entry
 // segments with a Blelloch scan and orders the segments through a global atomic counter,
 // which makes the order depend on arrival.  Here the list must be ascending and
-// reproducible, and x is at most a few tens of KB, so ONE 1024-lane workgroup does the
-// whole vector with wave64 primitives: ballot + mbcnt give each lane its rank inside a
-// 512-entry wave step, and sixteen wave totals are combined through LDS.  No atomics.
+// reproducible, so there are no atomics: workgroup b owns the 4096-entry segment b of x,
+// ranks its kept entries with wave64 primitives (ballot + mbcnt inside a 512-entry wave
+// step, eight wave totals through LDS), and obtains its base offset by simply counting
+// the kept entries of all earlier segments itself (x is at most 128 KB and sits in L2 after
+// the first touch; counting needs no ballots, only popcounts).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -15,11 +17,11 @@
 
 namespace {
 
-constexpr int kWaves = 16;
+constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kPerLane = 8;                        // one 16-byte load of fp16 per lane
-constexpr int kStep = 64 * kPerLane;               // entries one wave covers per step
-constexpr int kMaxSteps = SPQT_GATHER_MAX_K / (kWaves * kStep);   // 8
+constexpr int kStep = 64 * kPerLane;               // entries one wave covers
+constexpr int kSegment = kWaves * kStep;           // entries one workgroup ranks: 4096
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -33,80 +35,78 @@ __device__ __forceinline__ uint32_t keep_bits(u32x4 v, float thr) {
     uint32_t m = 0;
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-        float lo = half_bits_to_float(v[d] & 0xFFFFu);
-        float hi = half_bits_to_float(v[d] >> 16);
+        const uint32_t word = v[d];
+        const float lo = half_bits_to_float(word & 0xFFFFu);
+        const float hi = half_bits_to_float(word >> 16);
         m |= (uint32_t)(!(__builtin_fabsf(lo) < thr)) << (2 * d);
         m |= (uint32_t)(!(__builtin_fabsf(hi) < thr)) << (2 * d + 1);
     }
     return m;
 }
 
+// Keep mask of the eight entries starting at `first` (all rows of the batch OR-ed), or 0 past K.
+template <int BATCH>
+__device__ __forceinline__ uint32_t mask_at(const uint16_t *__restrict__ x, int K, int first, float thr) {
+    u32x4 v[BATCH];
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) v[b] = *reinterpret_cast<const u32x4 *>(x + (size_t)b * K + first);
+    uint32_t m = 0;
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) m |= keep_bits(v[b], thr);
+    return m;
+}
+
+template <int BATCH>
 __global__ __launch_bounds__(kThreads) void spqt_gather_kernel(const uint16_t *__restrict__ x, int K,
-                                                               int batch, float thr,
-                                                               int32_t *__restrict__ idx,
+                                                               float thr, int32_t *__restrict__ idx,
                                                                int32_t *__restrict__ count) {
     __shared__ int wave_total[kWaves];
+    __shared__ int wave_before[kWaves];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    const int seg = blockIdx.x;
+    const int lane_first = wave * kStep + lane * kPerLane;   // inside a segment
 
-    // Wave w owns the contiguous span [w*span, (w+1)*span), walked in steps of 512 entries;
-    // lane l of a step owns entries 8l..8l+7 of it, so ranks follow (step, lane, bit) order.
-    const int steps = (K + kWaves * kStep - 1) / (kWaves * kStep);
-    const int span = steps * kStep;
+    // This workgroup's own segment: lane l of wave w owns entries 8l..8l+7 of wave step w, so
+    // ranks follow (wave, lane, bit) order = ascending index.
+    const int first = seg * kSegment + lane_first;
+    // K % 8 == 0, so a lane's eight entries are all inside x or all past its end
+    const uint32_t m = first < K ? mask_at<BATCH>(x, K, first, thr) : 0u;
 
-    uint32_t bits[kMaxSteps];      // keep mask of this lane's 8 entries, per step
-    int lane_rank[kMaxSteps];      // kept entries of this wave before this lane's, per step
-    int total = 0;                 // kept entries of this wave so far
-
+    // Kept entries of all earlier segments, counted by this workgroup itself.
+    // (Earlier segments are complete - only the last one can be ragged - so these loads need no
+    // bounds test and can all be in flight together.)
+    int before = 0;
+#pragma unroll 4
+    for (int p = 0; p < seg; ++p) before += __popc(mask_at<BATCH>(x, K, p * kSegment + lane_first, thr));
 #pragma unroll
-    for (int s = 0; s < kMaxSteps; ++s) {
-        bits[s] = 0;
-        lane_rank[s] = 0;
-        if (s < steps) {
-            const int first = wave * span + s * kStep + lane * kPerLane;
-            uint32_t m = 0;
-            if (first < K) {       // K % 8 == 0, so a lane's eight entries are all in or all out
-                for (int b = 0; b < batch; ++b) {
-                    u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)b * K + first);
-                    m |= keep_bits(v, thr);
-                }
-            }
-            bits[s] = m;
-            int before = total;
+    for (int s = 1; s < 64; s <<= 1) before += __shfl_xor(before, s);
+
+    int rank = 0, total = 0;
 #pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                uint64_t ballot = __ballot((m >> j) & 1u);
-                before += __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32),
-                                                    __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
-                total += __popcll(ballot);
-            }
-            lane_rank[s] = before;
-        }
+    for (int j = 0; j < kPerLane; ++j) {
+        const uint64_t ballot = __ballot((m >> j) & 1u);
+        rank += __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+        total += __popcll(ballot);
     }
-
-    if (lane == 0) wave_total[wave] = total;
+    if (lane == 0) {
+        wave_total[wave] = total;
+        wave_before[wave] = before;
+    }
     __syncthreads();
     int base = 0, all = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-        int t = wave_total[w];
-        base += (w < wave) ? t : 0;
-        all += t;
+        const int t = wave_total[w];
+        base += wave_before[w] + ((w < wave) ? t : 0);
+        all += wave_before[w] + t;
     }
-    if (threadIdx.x == 0) *count = all;
+    if (seg == (int)gridDim.x - 1 && threadIdx.x == 0) *count = all;
 
+    int pos = base + rank;
 #pragma unroll
-    for (int s = 0; s < kMaxSteps; ++s) {
-        if (s < steps) {
-            uint32_t m = bits[s];
-            const int first = wave * span + s * kStep + lane * kPerLane;
-            int pos = base + lane_rank[s];
-#pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                if ((m >> j) & 1u) idx[pos++] = first + j;
-            }
-        }
-    }
+    for (int j = 0; j < kPerLane; ++j)
+        if ((m >> j) & 1u) idx[pos++] = first + j;
 }
 
 }  // namespace
@@ -118,7 +118,15 @@ extern "C" int spqt_gather(const void *x_dev, int64_t K, int batch, float thresh
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
     if (threshold != threshold) return SPQT_EINVAL;   // NaN threshold has no meaning
     if ((uintptr_t)x_dev % 16 != 0 || (uintptr_t)idx_out_dev % 4 != 0) return SPQT_EALIGN;
-    hipLaunchKernelGGL(spqt_gather_kernel, dim3(1), dim3(kThreads), 0, (hipStream_t)stream,
-                       (const uint16_t *)x_dev, (int)K, batch, threshold, idx_out_dev, count_out_dev);
+    const int segments = (int)((K + kSegment - 1) / kSegment);
+    const dim3 grid(segments), block(kThreads);
+    hipStream_t st = (hipStream_t)stream;
+    const uint16_t *x = (const uint16_t *)x_dev;
+    switch (batch) {
+        case 1: hipLaunchKernelGGL(spqt_gather_kernel<1>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
+        case 2: hipLaunchKernelGGL(spqt_gather_kernel<2>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
+        case 3: hipLaunchKernelGGL(spqt_gather_kernel<3>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
+        default: hipLaunchKernelGGL(spqt_gather_kernel<4>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
+    }
     return hipGetLastError() == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }

@@ -47,6 +47,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPassCols = 64;                  // most columns one pass covers (8 steps)
 constexpr float kTwo24 = 16777216.0f;          // 2^24: undoes the fp16 subnormal exponent
+constexpr int kMaxPolls = 1 << 18;             // bound on the reducer's wait for one batch of partials
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
@@ -88,48 +89,66 @@ __device__ __forceinline__ void fma_step(u32x4 w, float xl, float *acc) {
     fma_codes<INIT>(w.w, xl, xh, acc + 24);
 }
 
-// a and b are two accumulators of every lane.  Returns, in lanes 0..31, a summed over the
-// lane pair (l, l+32) and, in lanes 32..63, b summed over the same pair.  The swap works in
-// place on both registers (written as asm so that no copies are made; the two wait states it
-// needs after a VALU write of its operands are provided here); a and b are clobbered.
-__device__ __forceinline__ float fold32(float &a, float &b) {
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-    return a + b;
+// The three levels of the column fold are written as asm blocks: the lane swaps work in place
+// on both of their registers (no copies), and the wait states a swap or DPP read needs after a
+// VALU write of its operand are paid once per block instead of once per instruction.
+
+// Level 1, lane pairs (l, l^8) inside every row of 16 lanes: afterwards lanes with bit 3 clear
+// hold a summed over the pair, lanes with bit 3 set hold b summed over the pair - in b's
+// register.  Two bank-masked DPP adds per (a, b).
+#define SPQT_FOLD8(B, A)                                                              \
+    "v_add_f32_dpp " B ", " B ", " B " row_ror:8 row_mask:0xf bank_mask:0xc\n\t"      \
+    "v_add_f32_dpp " B ", " A ", " A " row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+__device__ __forceinline__ void fold8_x8(const float *a, float *b) {
+    asm volatile("s_nop 1\n\t" SPQT_FOLD8("%0", "%8") SPQT_FOLD8("%1", "%9") SPQT_FOLD8("%2", "%10")
+                     SPQT_FOLD8("%3", "%11") SPQT_FOLD8("%4", "%12") SPQT_FOLD8("%5", "%13")
+                         SPQT_FOLD8("%6", "%14") SPQT_FOLD8("%7", "%15")
+                 : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+                 : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]));
 }
-// Same for the lane pair (l, l^16): lanes with bit 4 clear get a's sum, the others b's.
-__device__ __forceinline__ float fold16(float &a, float &b) {
+
+// Level 2, lane pairs (l, l^16): v_permlane16_swap exchanges the odd rows of its first operand
+// with the even rows of its second, so a + b afterwards is, in lanes with bit 4 clear, the old a
+// summed over the pair and, in the others, the old b summed over the pair.
+__device__ __forceinline__ void swap16_x8(float *a, float *b) {
+    asm volatile("s_nop 1\n\t"
+                 "v_permlane16_swap_b32 %0, %8\n\tv_permlane16_swap_b32 %1, %9\n\t"
+                 "v_permlane16_swap_b32 %2, %10\n\tv_permlane16_swap_b32 %3, %11\n\t"
+                 "v_permlane16_swap_b32 %4, %12\n\tv_permlane16_swap_b32 %5, %13\n\t"
+                 "v_permlane16_swap_b32 %6, %14\n\tv_permlane16_swap_b32 %7, %15"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
+                   "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7]));
+}
+// Level 3, lane pairs (l, l^32), same idea with the two halves of the wave.
+__device__ __forceinline__ void swap32_x4(float *a, float *b) {
+    asm volatile("s_nop 1\n\t"
+                 "v_permlane32_swap_b32 %0, %4\n\tv_permlane32_swap_b32 %1, %5\n\t"
+                 "v_permlane32_swap_b32 %2, %6\n\tv_permlane32_swap_b32 %3, %7"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]));
+}
+__device__ __forceinline__ float fold16(float a, float b) {
     asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
     return a + b;
 }
-// Value of lane l^8 (rotate by 8 inside each row of 16 lanes).
-__device__ __forceinline__ float from_xor8(float v) {
-    return as_float(__builtin_amdgcn_update_dpp(0u, as_u32(v), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
-}
-
-// For lane pairs (l, l^8), inside every row of 16 lanes: lanes with bit 3 clear receive a
-// summed over the pair, lanes with bit 3 set receive b summed over the pair.  Two DPP adds
-// that each write only half of the row (bank masks), in place in b's register.  The leading
-// wait states cover a VALU write of a or b just before.
-__device__ __forceinline__ void fold8_into_b(float a, float &b) {
-    asm volatile(
-        "s_nop 1\n\t"
-        "v_add_f32_dpp %0, %0, %0 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
-        "v_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3"
-        : "+v"(b)
-        : "v"(a));
+__device__ __forceinline__ float fold32(float a, float b) {
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
 }
 
 // Fold the 32 accumulators of the 8 lanes that read the same rows (lanes seg, seg+8, ...,
 // seg+56), halving the number of live values at each of the three levels.  Lane (cg, seg)
 // ends with the complete sums of rows 32 seg + 4 rev(cg) + j, j = 0..3, where rev reverses
 // the three bits of cg (level 1 splits on lane bit 3, level 2 on bit 4, level 3 on bit 5).
+// acc is clobbered.
 __device__ __forceinline__ void fold_columns(float *acc, float *out4) {
+    fold8_x8(acc + 0, acc + 16);      // pairs (i, i+16), i = 0..7   -> acc[16..23]
+    fold8_x8(acc + 8, acc + 24);      // pairs (i, i+16), i = 8..15  -> acc[24..31]
+    swap16_x8(acc + 16, acc + 24);    // pairs (16+i, 24+i)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) fold8_into_b(acc[i], acc[i + 16]);     // -> acc[16..31]
+    for (int i = 0; i < 8; ++i) acc[i] = acc[16 + i] + acc[24 + i];
+    swap32_x4(acc + 0, acc + 4);      // pairs (i, 4+i)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = fold16(acc[16 + i], acc[24 + i]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) out4[i] = fold32(acc[i], acc[4 + i]);
+    for (int i = 0; i < 4; ++i) out4[i] = acc[i] + acc[4 + i];
 }
 
 template <int CTRL>
@@ -144,10 +163,8 @@ __device__ __forceinline__ float wave_sum(float v) {
     v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
     v += dpp_move<0x141>(v);   // row_half_mirror: the other quad of the 8
     v += dpp_move<0x140>(v);   // row_mirror: the other half of the row
-    float t = v;
-    v = fold16(v, t);
-    t = v;
-    v = fold32(v, t);
+    v = fold16(v, v);
+    v = fold32(v, v);
     return v;
 }
 
@@ -155,12 +172,11 @@ template <int WAVES, bool DENSE>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    float *partials, int32_t *counters, int K, int NG, int S, int T) {
+    void *partials, int32_t *epochs, int K, int NG, int S, int T) {
     // Two staging slots per wave (the pass being multiplied and the pass being fetched).
     __shared__ uint32_t stage_off[WAVES][2][kPassCols];   // byte offset of each column of the pass
     __shared__ float stage_x[WAVES][2][kPassCols];        // its x, pre-scaled by 2^24
     __shared__ __attribute__((aligned(16))) float red[WAVES][kTileRows];
-    __shared__ int is_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -178,6 +194,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const int t = xcd + 8 * (slot / S);        // block-row
     const int s = slot % S;
     if (t >= T) return;
+    // This call's tag for the cross-workgroup exchange (requested now, used at the very end).
+    int tag = 0;
+    if (S > 1) tag = __hip_atomic_load(epochs + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
 
     // Even split of the index list over the S*WAVES wavefronts of this block-row.
     const int n_ns = DENSE ? K : __builtin_amdgcn_readfirstlane(*count);
@@ -205,6 +224,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
 #pragma unroll
         for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
         float xsum = 0.0f;              // current group: pre-scaled x of the columns this lane staged
+        bool fresh = true;              // the next step is the first of its group: it overwrites acc
 
         // FETCH stage of the pass that starts at list position p (kk = fetch_k(p)): delimit the
         // pass (the run of entries that share the group of idx[p], at most 64), request the
@@ -246,7 +266,13 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             float xl[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) xl[u] = stage_x[wave][slot][u * 8 + cg];
-            fma_step<false>(w[0], xl[0], acc);
+            if (fresh) {
+                asm volatile("" ::);   // not speculatable: stays a wave-uniform branch, not 32 selects
+                fma_step<true>(w[0], xl[0], acc);
+            } else {
+                fma_step<false>(w[0], xl[0], acc);
+            }
+            fresh = false;
 #pragma unroll
             for (int u = 1; u < 8; ++u)
                 if (u * 8 < n) fma_step<false>(w[u], xl[u], acc);
@@ -257,8 +283,6 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         auto flush = [&](u32x2 sc) {
             float r4[4];
             fold_columns(acc, r4);
-#pragma unroll
-            for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
             const float bias = wave_sum(xsum) * (-8.0f / kTwo24);
             const uint32_t s01 = sc.x, s23 = sc.y;
             const f16x2 h01 = as_f16x2(s01), h23 = as_f16x2(s23);
@@ -267,6 +291,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             yacc[2] = __builtin_fmaf((float)h23.x, r4[2] + bias, yacc[2]);
             yacc[3] = __builtin_fmaf((float)h23.y, r4[3] + bias, yacc[3]);
             xsum = 0.0f;
+            fresh = true;
         };
 
         // Two-stage software pipeline over the passes, buffers A and B alternating.
@@ -276,6 +301,11 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         int nA, nB, gA, gB, kA, kB;
         kA = fetch_k(pos);
         fetch(kA, pos, 0, wA, nA, gA, xrA, scA, kB);
+        if (pos + nA >= end) {
+            // the whole slice is one pass (small matrices): nothing to overlap with
+            multiply(nA, xrA, 0, wA);
+            flush(scA);
+        } else
         for (;;) {
             const int posB = pos + nA;
             fetch(kB, posB, 1, wB, nB, gB, xrB, scB, kA);
@@ -301,52 +331,59 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     reinterpret_cast<f32x4 *>(red[wave])[8 * seg + cgr] = f32x4{yacc[0], yacc[1], yacc[2], yacc[3]};
     __syncthreads();
 
-    float *my_partial = partials + ((size_t)t * S + s) * kTileRows;
+    // ---- combine the S workgroups of this block-row ----------------------------------------
+    // Every workgroup but the last (s == S-1) publishes its 256 partial sums as 64-bit words
+    // {value, tag} with device-scope stores and is done: no wait, no counter.  The last one adds
+    // the others' words in index order, polling a word until its tag equals this call's tag,
+    // then its own sums, and writes y.  The tag is the block-row's epoch + 1; the epoch lives in
+    // the workspace, is read by everybody at kernel start and advanced by the reducer at the
+    // end, so words left over from earlier calls never match.  A 64-bit store is a single
+    // access: value and tag arrive together.  The reducer has the highest index of its block-row
+    // and workgroups are dispatched in index order, so everything it waits for is running or
+    // finished; the wait is bounded anyway and a give-up poisons y with NaN instead of hanging.
+    unsigned long long *slots =
+        reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kTileRows;
     for (int r = tid; r < kTileRows; r += WAVES * 64) {
         float sum = 0.0f;
 #pragma unroll
         for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2][r];
-        if (S == 1)
+        if (S == 1) {
             y[(size_t)t * kTileRows + r] = sum;
-        else
-            __hip_atomic_store(my_partial + r, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (S == 1) return;
-
-    // ---- combine the S workgroups of this block-row: last arrival adds in fixed order ------
-    // The partials are written and read with device-scope atomic accesses (they go through to
-    // the device-coherent level instead of staying in one XCD's L2), so the only ordering
-    // needed is "my stores have completed before my arrival is counted" and "the count is read
-    // before the partials are": a wait on the memory counters plus the workgroup barrier, not a
-    // cache-wide write-back and invalidate.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    if (tid == 0) {
-        const int prev = __hip_atomic_fetch_add(counters + t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (prev == S - 1);
-    }
-    __syncthreads();
-    if (!is_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const float *tile_partials = partials + (size_t)t * S * kTileRows;
-    for (int r = tid; r < kTileRows; r += WAVES * 64) {
-        // request the partials in batches so their latencies overlap; add in index order
-        float sum = 0.0f;
-        for (int p0 = 0; p0 < S; p0 += 16) {
-            float v[16];
+        } else if (s != S - 1) {
+            const unsigned long long word = ((unsigned long long)(uint32_t)tag << 32) | as_u32(sum);
+            __hip_atomic_store(slots + (size_t)s * kTileRows + r, word, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            float total = 0.0f;
+            bool gave_up = false;
+            for (int p0 = 0; p0 < S - 1; p0 += 16) {
+                unsigned long long v[16];
+                int polls = 0;
+                bool all_here;
+                do {
+                    // 16 unconditional loads back to back (clamped index), then one check
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                v[j] = 0.0f;
-                if (p0 + j < S)
-                    v[j] = __hip_atomic_load(tile_partials + (size_t)(p0 + j) * kTileRows + r,
-                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int j = 0; j < 16; ++j) {
+                        const int p = p0 + j < S - 1 ? p0 + j : S - 2;
+                        v[j] = __hip_atomic_load(slots + (size_t)p * kTileRows + r, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    uint32_t missing = 0u;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[j] >> 32) ^ (uint32_t)tag;
+                    all_here = missing == 0u;
+                } while (!all_here && ++polls < kMaxPolls);
+                gave_up = gave_up || !all_here;
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (p0 + j < S - 1) total += as_float((uint32_t)v[j]);
             }
-#pragma unroll
-            for (int j = 0; j < 16; ++j) sum += v[j];
+            total += sum;
+            y[(size_t)t * kTileRows + r] = gave_up ? __builtin_nanf("") : total;
         }
-        y[(size_t)t * kTileRows + r] = sum;
     }
-    if (tid == 0) __hip_atomic_store(counters + t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (S > 1 && s == S - 1 && tid == 0)
+        __hip_atomic_store(epochs + t, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
@@ -356,14 +393,14 @@ __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
 
 template <int WAVES>
 hipError_t launch(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                  const int32_t *idx, const int32_t *count, float *y, float *partials,
-                  int32_t *counters, int K, int NG, int S, int T) {
+                  const int32_t *idx, const int32_t *count, float *y, void *partials,
+                  int32_t *epochs, int K, int NG, int S, int T) {
     if (dense)
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, counters, K, NG, S, T);
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T);
     else
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, counters, K, NG, S, T);
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T);
     return hipGetLastError();
 }
 
@@ -373,17 +410,16 @@ extern "C" int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out
     if (!out_bytes) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    *out_bytes = counter_bytes(M) + (size_t)M * SPQT_MAX_SPLITS * sizeof(float);
+    *out_bytes = counter_bytes(M) + (size_t)M * SPQT_MAX_SPLITS * 2 * sizeof(float);
     return SPQT_OK;
 }
 
 extern "C" int spqt_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream) {
     if (!workspace_dev || workspace_bytes < 256) return SPQT_EINVAL;
     if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-    // Only the counters need a defined start value; zero the counter area of the largest
-    // shape this workspace could serve (it is a few KB at most) - simply all leading words
-    // up to 64 KB or the buffer's end.
-    size_t words = (workspace_bytes < 65536 ? workspace_bytes : 65536) / 4;
+    // Epochs start at zero and no stale {value, tag} word may survive from an earlier use of
+    // this memory: clear all of it.
+    size_t words = workspace_bytes / 4;
     hipLaunchKernelGGL(spqt_fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, (uint32_t *)workspace_dev, words);
     return hipGetLastError() == hipSuccess ? SPQT_OK : SPQT_EHIP;
@@ -393,17 +429,17 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
     if (!out) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    (void)sparse;
     const int64_t T = M / kTileRows, NG = K / kGroup;
     int waves = 4;
-    // Aim for ~2048 wavefronts in flight, but keep at least one quantization group of
-    // dense work per wavefront.
-    int64_t S = (2048 + T * waves - 1) / (T * waves);
-    int64_t cap = NG / waves;
-    if (cap < 1) cap = 1;
-    if (S > cap) S = cap;
-    if (S > SPQT_MAX_SPLITS) S = SPQT_MAX_SPLITS;
-    if (S < 1) S = 1;
+    // Measured on MI355X over the benchmark shapes (sweep of S at 50 % sparsity and dense):
+    // the fastest launch has about 512 (sparse) / 1024 (dense) workgroups of 4 wavefronts in
+    // total, S a power of two and at most 16 - beyond that the fixed cost per wavefront
+    // (prologue loads, pipeline fill, final fold, exchange of partial sums) outweighs the
+    // extra parallelism.  Keep at least a quarter of a quantization group per wavefront.
+    const int64_t target = sparse ? 512 : 1024;
+    int64_t S = 1;
+    while (S * 2 <= 16 && S * 2 * T <= target) S *= 2;
+    while (S > 1 && S * waves > 4 * NG) S /= 2;
     out->splits = (int)S;
     out->waves = waves;
     return SPQT_OK;
@@ -431,14 +467,14 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
 
     size_t need = 0;
     spqt_workspace_bytes(M, K, batch, &need);
-    float *partials = nullptr;
-    int32_t *counters = nullptr;
+    void *partials = nullptr;
+    int32_t *epochs = nullptr;
     if (c.splits > 1) {
         if (!workspace_dev) return SPQT_EINVAL;
         if (workspace_bytes < need) return SPQT_ESIZE;
         if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-        counters = (int32_t *)workspace_dev;
-        partials = (float *)((uint8_t *)workspace_dev + counter_bytes(M));
+        epochs = (int32_t *)workspace_dev;
+        partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
 
     const int T = (int)(M / kTileRows), NG = (int)(K / kGroup);
@@ -452,9 +488,9 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
         float *yb = y_dev + (size_t)b * M;
         hipError_t err;
         switch (c.waves) {
-            case 1: err = launch<1>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits, T); break;
-            case 2: err = launch<2>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits, T); break;
-            default: err = launch<4>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, counters, (int)K, NG, c.splits, T); break;
+            case 1: err = launch<1>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, epochs, (int)K, NG, c.splits, T); break;
+            case 2: err = launch<2>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, epochs, (int)K, NG, c.splits, T); break;
+            default: err = launch<4>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, epochs, (int)K, NG, c.splits, T); break;
         }
         if (err != hipSuccess) return SPQT_EHIP;
     }
