@@ -41,11 +41,12 @@ class Workload:
     """Rotating set of packed weight copies + per-copy activations, thresholds and index lists
     for one (M, K) shape at one sparsity."""
 
-    def __init__(self, torch, spqt, M, K, dist, scale_range, config, tensor, sparsity, copies=None):
+    def __init__(self, torch, spqt, M, K, dist, scale_range, config, tensor, sparsity, copies=None, batch=1):
         import numpy as np
         from workloads import make_case, make_x, quantile_threshold, seed_for, KIND_X
         self.torch, self.spqt, self.M, self.K = torch, spqt, M, K
         self.sparsity = sparsity
+        self.batch = batch
         dev = torch.device("cuda:0")
         pbytes = spqt.spqt_packed_bytes(M, K)
         self.copies = copies or max(2, -(-ROTATE_BYTES // pbytes))
@@ -65,16 +66,16 @@ class Workload:
             self.packed.append(buf.reshape(-1))
         xs, thr = [], []
         for layer in range(self.copies):
-            x = make_x(K, dist, seed_for(config, layer, tensor, KIND_X))
-            xs.append(x[0])
+            x = make_x(K, dist, seed_for(config, layer, tensor, KIND_X), batch)
+            xs.append(x[0] if batch == 1 else x)
             thr.append(quantile_threshold(x, sparsity))
         self.x_np = np.stack(xs)
         self.thr = thr
         self.x = torch.from_numpy(self.x_np).to(dev)
         self.idx = torch.zeros((self.copies, K), dtype=torch.int32, device=dev)
         self.cnt = torch.zeros((self.copies, 1), dtype=torch.int32, device=dev)
-        self.y = torch.zeros((self.copies, M), dtype=torch.float32, device=dev)
-        self.ws = spqt.new_workspace(M, K)
+        self.y = torch.zeros((self.copies, M) if batch == 1 else (self.copies, batch, M), dtype=torch.float32, device=dev)
+        self.ws = spqt.new_workspace(M, K, batch)
         for i in range(self.copies):
             spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
         torch.cuda.synchronize()
@@ -305,24 +306,27 @@ def main():
     # ---------------- sweeps ---------------------------------------------------------------
     sweep = []
     if not args.no_sweep:
-        shapes = [(2, "q", 4096, 4096, "laplace", [0.0, 0.25, 0.4, 0.65])]
-        shapes.append((5, "gate", 28672, 8192, "laplace", [0.5]))
+        shapes = [(2, "q", 4096, 4096, "laplace", [0.0, 0.25, 0.4, 0.65], 1)]
+        shapes.append((5, "gate", 28672, 8192, "laplace", [0.5], 1))
         if args.full:
-            shapes += [(3, "gate", 11008, 4096, "laplace", [0.4, 0.5]),
-                       (3, "down", 4096, 11008, "silu_product", [0.4, 0.5]),
-                       (4, "gate", 14336, 4096, "laplace", [0.5]),
-                       (4, "down", 4096, 14336, "laplace", [0.5]),
-                       (5, "gate", 28672, 8192, "laplace", [0.3, 0.7]),
-                       (5, "down", 8192, 28672, "laplace", [0.3, 0.5, 0.7])]
-        for config, tensor, m, k, dist, sps in shapes:
+            shapes += [(3, "gate", 11008, 4096, "laplace", [0.4, 0.5], 1),
+                       (3, "down", 4096, 11008, "silu_product", [0.4, 0.5], 1),
+                       (4, "k", 1024, 4096, "laplace", [0.5], 1),
+                       (4, "gate", 14336, 4096, "laplace", [0.5], 1),
+                       (4, "down", 4096, 14336, "laplace", [0.5], 1),
+                       (5, "gate", 28672, 8192, "laplace", [0.3, 0.7], 1),
+                       (5, "down", 8192, 28672, "laplace", [0.3, 0.5, 0.7], 1),
+                       (5, "gate", 28672, 8192, "laplace", [0.3, 0.5, 0.7], 4),
+                       (5, "down", 8192, 28672, "laplace", [0.5], 4)]
+        for config, tensor, m, k, dist, sps, batch in shapes:
             for s in sps:
-                w = wl if (m, k, s) == (M, K, 0.5) else Workload(torch, spqt, m, k, dist, CONFIG_SCALE_RANGE[config], config, tensor, s)
+                w = wl if (m, k, s, batch) == (M, K, 0.5, 1) else Workload(torch, spqt, m, k, dist, CONFIG_SCALE_RANGE[config], config, tensor, s, batch=batch)
                 steps = max(w.copies * 4, min(K_steps, 1600))
                 t_g = time_sequence(torch, w.gemv_only, w.copies, steps, w.copies, use_graph)
                 t_d = time_sequence(torch, w.dense_only, w.copies, steps, w.copies, use_graph)
                 t_s = time_sequence(torch, w.step, w.copies, steps, w.copies, use_graph)
                 gb = w.mean_kept_bytes / (t_g * 1e-6) / 1e9
-                sweep.append({"config": config, "tensor": tensor, "M": m, "K": k, "sparsity": s,
+                sweep.append({"config": config, "tensor": tensor, "M": m, "K": k, "batch": batch, "sparsity_per_row": s,
                               "kept_frac": round(float(np.mean(w.n_ns)) / k, 4),
                               "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3),
                               "GBps_kept": round(gb, 1), "frac_of_8TBps": round(gb / HBM_PEAK_GBPS, 4),

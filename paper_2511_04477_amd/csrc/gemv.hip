@@ -168,15 +168,18 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-template <int WAVES, bool DENSE>
+// BATCH activation rows share one pass over the weights: the index list is the union of the
+// rows' kept columns, every dequantized code is multiplied by each row's own x, and each row
+// has its own accumulators, bias sum and output.
+template <int WAVES, bool DENSE, int BATCH>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    void *partials, int32_t *epochs, int K, int NG, int S, int T) {
+    void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
     // Two staging slots per wave (the pass being multiplied and the pass being fetched).
-    __shared__ uint32_t stage_off[WAVES][2][kPassCols];   // byte offset of each column of the pass
-    __shared__ float stage_x[WAVES][2][kPassCols];        // its x, pre-scaled by 2^24
-    __shared__ __attribute__((aligned(16))) float red[WAVES][kTileRows];
+    __shared__ uint32_t stage_off[WAVES][2][kPassCols];      // byte offset of each column of the pass
+    __shared__ float stage_x[WAVES][2][BATCH][kPassCols];    // its x per batch row, pre-scaled by 2^24
+    __shared__ __attribute__((aligned(16))) float red[WAVES][BATCH][kTileRows];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -207,7 +210,11 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
 
     const uint8_t *row_base = packed + (size_t)t * NG * kChunkBytes;
 
-    float yacc[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // rows 32 seg + 4 rev(cg) + j, scaled and summed over groups
+    float yacc[BATCH][4];   // rows 32 seg + 4 rev(cg) + j, scaled and summed over groups
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) yacc[b][j] = 0.0f;
 
     if (pos < end) {
         // List entry p + lane, or -1 past the slice.  The load itself is never predicated
@@ -220,18 +227,22 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             return e < end ? v : -1;
         };
 
-        float acc[32];                  // current group, this lane's columns, unscaled
+        float acc[BATCH][32];           // current group, this lane's columns, unscaled
+        float xsum[BATCH];              // current group: pre-scaled x of the columns this lane staged
 #pragma unroll
-        for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-        float xsum = 0.0f;              // current group: pre-scaled x of the columns this lane staged
+        for (int b = 0; b < BATCH; ++b) {
+            xsum[b] = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) acc[b][i] = 0.0f;
+        }
         bool fresh = true;              // the next step is the first of its group: it overwrites acc
 
         // FETCH stage of the pass that starts at list position p (kk = fetch_k(p)): delimit the
         // pass (the run of entries that share the group of idx[p], at most 64), request the
         // NEXT pass's entries, this pass's x, its weights (8 steps, always) and its scales.
         // Past the end of the slice (p >= end) it degenerates to n = 0 with harmless re-reads.
-        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, int &g_out, uint32_t &xraw_out,
-                         u32x2 &sc_out, int &k_after) {
+        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, int &g_out,
+                         uint32_t(&xraw_out)[BATCH], u32x2 &sc_out, int &k_after) {
             const bool any = p < end;
             const int g = any ? (__builtin_amdgcn_readfirstlane(kk) >> 7) : 0;
             const bool in = any && ((kk >> 7) == g);
@@ -241,7 +252,8 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             // they re-read a line that is being fetched anyway.
             const uint32_t koff_in = (uint32_t)(kk & (kGroup - 1)) * kColBytes;
             const uint32_t koff_first = any ? (uint32_t)__builtin_amdgcn_readfirstlane((int)koff_in) : 0u;
-            xraw_out = x[in ? kk : 0];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) xraw_out[b] = x[(size_t)b * K + (in ? kk : 0)];
             stage_off[wave][slot][lane] = in ? koff_in : koff_first;
             const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;   // wave-uniform base
             __builtin_amdgcn_wave_barrier();
@@ -258,50 +270,90 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         };
 
         // MULTIPLY stage of a fetched pass.
-        auto multiply = [&](int n, uint32_t xraw, int slot, const u32x4(&w)[8]) {
-            const float xs = lane < n ? half_bits_to_float(xraw) * kTwo24 : 0.0f;
-            xsum += xs;
-            stage_x[wave][slot][lane] = xs;
-            __builtin_amdgcn_wave_barrier();
-            float xl[8];
+        auto multiply = [&](int n, const uint32_t(&xraw)[BATCH], int slot, const u32x4(&w)[8]) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) xl[u] = stage_x[wave][slot][u * 8 + cg];
-            if (fresh) {
-                asm volatile("" ::);   // not speculatable: stays a wave-uniform branch, not 32 selects
-                fma_step<true>(w[0], xl[0], acc);
+            for (int b = 0; b < BATCH; ++b) {
+                const float xs = lane < n ? half_bits_to_float(xraw[b]) * kTwo24 : 0.0f;
+                xsum[b] += xs;
+                stage_x[wave][slot][b][lane] = xs;
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (BATCH == 1) {
+                float xl[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) xl[u] = stage_x[wave][slot][0][u * 8 + cg];
+                if (fresh) {
+                    asm volatile("" ::);   // not speculatable: stays a wave-uniform branch, not 32 selects
+                    fma_step<true>(w[0], xl[0], acc[0]);
+                } else {
+                    fma_step<false>(w[0], xl[0], acc[0]);
+                }
+#pragma unroll
+                for (int u = 1; u < 8; ++u)
+                    if (u * 8 < n) fma_step<false>(w[u], xl[u], acc[0]);
             } else {
-                fma_step<false>(w[0], xl[0], acc);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (u * 8 < n) {
+                        float xl[BATCH];
+#pragma unroll
+                        for (int b = 0; b < BATCH; ++b) xl[b] = stage_x[wave][slot][b][u * 8 + cg];
+                        if (u == 0 && fresh) {
+                            asm volatile("" ::);
+#pragma unroll
+                            for (int b = 0; b < BATCH; ++b) fma_step<true>(w[u], xl[b], acc[b]);
+                        } else {
+#pragma unroll
+                            for (int b = 0; b < BATCH; ++b) fma_step<false>(w[u], xl[b], acc[b]);
+                        }
+                    }
+                }
             }
             fresh = false;
-#pragma unroll
-            for (int u = 1; u < 8; ++u)
-                if (u * 8 < n) fma_step<false>(w[u], xl[u], acc);
             __builtin_amdgcn_wave_barrier();
         };
 
         // Fold the finished group (whose scales are `sc`) into yacc.
         auto flush = [&](u32x2 sc) {
-            float r4[4];
-            fold_columns(acc, r4);
-            const float bias = wave_sum(xsum) * (-8.0f / kTwo24);
             const uint32_t s01 = sc.x, s23 = sc.y;
             const f16x2 h01 = as_f16x2(s01), h23 = as_f16x2(s23);
-            yacc[0] = __builtin_fmaf((float)h01.x, r4[0] + bias, yacc[0]);
-            yacc[1] = __builtin_fmaf((float)h01.y, r4[1] + bias, yacc[1]);
-            yacc[2] = __builtin_fmaf((float)h23.x, r4[2] + bias, yacc[2]);
-            yacc[3] = __builtin_fmaf((float)h23.y, r4[3] + bias, yacc[3]);
-            xsum = 0.0f;
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                float r4[4];
+                fold_columns(acc[b], r4);
+                const float bias = wave_sum(xsum[b]) * (-8.0f / kTwo24);
+                yacc[b][0] = __builtin_fmaf((float)h01.x, r4[0] + bias, yacc[b][0]);
+                yacc[b][1] = __builtin_fmaf((float)h01.y, r4[1] + bias, yacc[b][1]);
+                yacc[b][2] = __builtin_fmaf((float)h23.x, r4[2] + bias, yacc[b][2]);
+                yacc[b][3] = __builtin_fmaf((float)h23.y, r4[3] + bias, yacc[b][3]);
+                xsum[b] = 0.0f;
+            }
             fresh = true;
         };
 
         // Two-stage software pipeline over the passes, buffers A and B alternating.
         u32x4 wA[8], wB[8];
         u32x2 scA, scB;
-        uint32_t xrA, xrB;
+        uint32_t xrA[BATCH], xrB[BATCH];
         int nA, nB, gA, gB, kA, kB;
         kA = fetch_k(pos);
         fetch(kA, pos, 0, wA, nA, gA, xrA, scA, kB);
-        if (pos + nA >= end) {
+        if (BATCH > 1) {
+            // Several activation rows: the multiply stage dominates (BATCH fused multiply-adds per
+            // code) and the accumulators take most of the register file, so passes are simply
+            // fetched and multiplied one after the other with one weight buffer.
+            for (;;) {
+                multiply(nA, xrA, 0, wA);
+                pos += nA;
+                if (pos >= end) break;
+                const int g_prev = gA;
+                const u32x2 sc_prev = scA;
+                fetch(kB, pos, 0, wA, nA, gA, xrA, scA, kA);
+                kB = kA;
+                if (gA != g_prev) flush(sc_prev);
+            }
+            flush(scA);
+        } else if (pos + nA >= end) {
             // the whole slice is one pass (small matrices): nothing to overlap with
             multiply(nA, xrA, 0, wA);
             flush(scA);
@@ -328,7 +380,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     }
 
     // ---- combine the WAVES wavefronts through LDS ------------------------------------------
-    reinterpret_cast<f32x4 *>(red[wave])[8 * seg + cgr] = f32x4{yacc[0], yacc[1], yacc[2], yacc[3]};
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b)
+        reinterpret_cast<f32x4 *>(red[wave][b])[8 * seg + cgr] = f32x4{yacc[b][0], yacc[b][1], yacc[b][2], yacc[b][3]};
     __syncthreads();
 
     // ---- combine the S workgroups of this block-row ----------------------------------------
@@ -341,17 +395,18 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     // access: value and tag arrive together.  The reducer has the highest index of its block-row
     // and workgroups are dispatched in index order, so everything it waits for is running or
     // finished; the wait is bounded anyway and a give-up poisons y with NaN instead of hanging.
-    unsigned long long *slots =
-        reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kTileRows;
-    for (int r = tid; r < kTileRows; r += WAVES * 64) {
+    constexpr int kOut = BATCH * kTileRows;      // values one workgroup contributes: [BATCH][256]
+    unsigned long long *slots = reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kOut;
+    for (int r = tid; r < kOut; r += WAVES * 64) {
         float sum = 0.0f;
 #pragma unroll
-        for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2][r];
+        for (int w2 = 0; w2 < WAVES; ++w2) sum += (&red[w2][0][0])[r];
+        float *y_out = y + (size_t)(r / kTileRows) * M + (size_t)t * kTileRows + (r % kTileRows);
         if (S == 1) {
-            y[(size_t)t * kTileRows + r] = sum;
+            *y_out = sum;
         } else if (s != S - 1) {
             const unsigned long long word = ((unsigned long long)(uint32_t)tag << 32) | as_u32(sum);
-            __hip_atomic_store(slots + (size_t)s * kTileRows + r, word, __ATOMIC_RELAXED,
+            __hip_atomic_store(slots + (size_t)s * kOut + r, word, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         } else {
             float total = 0.0f;
@@ -365,7 +420,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
                         const int p = p0 + j < S - 1 ? p0 + j : S - 2;
-                        v[j] = __hip_atomic_load(slots + (size_t)p * kTileRows + r, __ATOMIC_RELAXED,
+                        v[j] = __hip_atomic_load(slots + (size_t)p * kOut + r, __ATOMIC_RELAXED,
                                                  __HIP_MEMORY_SCOPE_AGENT);
                     }
                     uint32_t missing = 0u;
@@ -379,7 +434,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                     if (p0 + j < S - 1) total += as_float((uint32_t)v[j]);
             }
             total += sum;
-            y[(size_t)t * kTileRows + r] = gave_up ? __builtin_nanf("") : total;
+            *y_out = gave_up ? __builtin_nanf("") : total;
         }
     }
     if (S > 1 && s == S - 1 && tid == 0)
@@ -391,17 +446,29 @@ __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
     if (i < n_words) p[i] = 0u;
 }
 
-template <int WAVES>
+template <int WAVES, int BATCH>
 hipError_t launch(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                   const int32_t *idx, const int32_t *count, float *y, void *partials,
-                  int32_t *epochs, int K, int NG, int S, int T) {
+                  int32_t *epochs, int K, int NG, int S, int T, int M) {
     if (dense)
-        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T);
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true, BATCH>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
     else
-        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T);
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, BATCH>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
     return hipGetLastError();
+}
+
+template <int WAVES>
+hipError_t launch_batch(int batch, bool dense, int grid, hipStream_t stream, const uint8_t *packed,
+                        const uint16_t *x, const int32_t *idx, const int32_t *count, float *y,
+                        void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
+    switch (batch) {
+        case 1: return launch<WAVES, 1>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
+        case 2: return launch<WAVES, 2>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
+        case 3: return launch<WAVES, 3>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
+        default: return launch<WAVES, 4>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
+    }
 }
 
 }  // namespace
@@ -410,7 +477,7 @@ extern "C" int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out
     if (!out_bytes) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    *out_bytes = counter_bytes(M) + (size_t)M * SPQT_MAX_SPLITS * 2 * sizeof(float);
+    *out_bytes = counter_bytes(M) + (size_t)M * SPQT_MAX_SPLITS * 2 * sizeof(float) * (size_t)batch;
     return SPQT_OK;
 }
 
@@ -436,7 +503,9 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
     // total, S a power of two and at most 16 - beyond that the fixed cost per wavefront
     // (prologue loads, pipeline fill, final fold, exchange of partial sums) outweighs the
     // extra parallelism.  Keep at least a quarter of a quantization group per wavefront.
-    const int64_t target = sparse ? 512 : 1024;
+    // Four activation rows need so many accumulator registers that only one wavefront fits per
+    // SIMD: keep the whole grid resident at once (256 workgroups of 4 wavefronts).
+    const int64_t target = batch == 4 ? 256 : (sparse ? 512 : 1024);
     int64_t S = 1;
     while (S * 2 <= 16 && S * 2 * T <= target) S *= 2;
     while (S > 1 && S * waves > 4 * NG) S /= 2;
@@ -481,19 +550,15 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
     const int grid = 8 * ((T + 7) / 8) * c.splits;
     const bool dense = idx_dev == nullptr;
     hipStream_t st = (hipStream_t)stream;
-    // batch > 1: one pass per row over the shared (union) index list; each row uses its own
-    // x values.  Launches on one stream run in order, so they can share the workspace.
-    for (int b = 0; b < batch; ++b) {
-        const uint16_t *xb = (const uint16_t *)x_dev + (size_t)b * K;
-        float *yb = y_dev + (size_t)b * M;
-        hipError_t err;
-        switch (c.waves) {
-            case 1: err = launch<1>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, epochs, (int)K, NG, c.splits, T); break;
-            case 2: err = launch<2>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, epochs, (int)K, NG, c.splits, T); break;
-            default: err = launch<4>(dense, grid, st, (const uint8_t *)packed_dev, xb, idx_dev, count_dev, yb, partials, epochs, (int)K, NG, c.splits, T); break;
-        }
-        if (err != hipSuccess) return SPQT_EHIP;
+    hipError_t err;
+    const uint8_t *pk = (const uint8_t *)packed_dev;
+    const uint16_t *xp = (const uint16_t *)x_dev;
+    switch (c.waves) {
+        case 1: err = launch_batch<1>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        case 2: err = launch_batch<2>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        default: err = launch_batch<4>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
     }
+    if (err != hipSuccess) return SPQT_EHIP;
     return SPQT_OK;
 }
 

@@ -230,6 +230,22 @@ def test_batch4_union(gpu):
     assert all(np.array_equal(y4[b], y1[0]) for b in range(4))
 
 
+@pytest.mark.parametrize("batch", [2, 3, 4])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (3, 4), (8, 2)])
+def test_batch_rows_share_one_pass(gpu, batch, splits, waves):
+    """Several activation rows over the union index list, multi-group slices and several
+    workgroups per block-row; also the dense kernel and per-row consistency with batch 1."""
+    M, K = 1024, 2048
+    w = make_weights(M, K, 81)
+    x = make_x(K, "laplace", 82 + batch, batch=batch)
+    thr = quantile_threshold(x, 0.6)
+    say(f"batch={batch} splits={splits} waves={waves}")
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    assert_close(gpu_gemv(gpu, w, x, thr, splits=splits, waves=waves), ref, "batch sparse")
+    ref0 = oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0)
+    assert_close(gpu_gemv(gpu, w, x, 0.0, dense=True, splits=splits, waves=waves), ref0, "batch dense")
+
+
 def test_hip_graph_replay_matches_eager(gpu):
     """gather + GEMV captured in one HIP graph and replayed, with eager work and
     synchronizations between the replays: every replay must reproduce the eager result."""
