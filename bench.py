@@ -94,6 +94,9 @@ class Workload:
     def gather_only(self, i):
         self.spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
 
+    def fused(self, i):
+        self.spqt.spqt_gemv_fused(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws)
+
     def dense_only(self, i):
         self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], None, None, self.y[i], self.ws)
 
@@ -267,6 +270,16 @@ def main():
     us_gather = time_sequence(torch, wl.gather_only, wl.copies, K_steps, W, use_graph)
     us_dense = time_sequence(torch, wl.dense_only, wl.copies, K_steps, W, use_graph)
     us_step_eager = time_sequence(torch, wl.step, wl.copies, min(K_steps, 2000), min(W, 200), False)
+    # one-launch variant (threshold + compaction inside the GEMV kernel); checked against the oracle too
+    wl.fused(0)
+    torch.cuda.synchronize()
+    import oracle as _oracle
+    _ref = _oracle.gemv(wl.case0["q_rowmajor"], wl.case0["scales"], wl.x_np[0:1], wl.thr[0])[0]
+    _err = np.abs(wl.y[0].cpu().numpy().astype(np.float64) - _ref)
+    if not bool(np.all(_err <= 1e-2 + 2e-3 * np.abs(_ref))):
+        print("bench.py: fused path parity check FAILED", file=sys.stderr)
+        sys.exit(1)
+    us_fused = time_sequence(torch, wl.fused, wl.copies, K_steps, W, use_graph)
 
     achieved = wl.mean_kept_bytes / (us_gemv * 1e-6) / 1e9
     out = {
@@ -289,6 +302,8 @@ def main():
         "us_gemv_only": round(us_gemv, 3), "us_gather_only": round(us_gather, 3),
         "us_dense_gemv": round(us_dense, 3), "speedup_vs_dense": round(us_dense / us_gemv, 3),
         "us_step_stream_launches": round(us_step_eager, 3),
+        "us_fused_step": round(us_fused, 3),
+        "fused_effective_GBps_kept_bytes": round(wl.mean_kept_bytes / (us_fused * 1e-6) / 1e9, 1),
         "oracle_max_abs_err": max_err,
         "roofline": {"bound": "hbm", "kernel": "spqt_gemv_kernel<sparse>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
@@ -325,10 +340,11 @@ def main():
                 t_g = time_sequence(torch, w.gemv_only, w.copies, steps, w.copies, use_graph)
                 t_d = time_sequence(torch, w.dense_only, w.copies, steps, w.copies, use_graph)
                 t_s = time_sequence(torch, w.step, w.copies, steps, w.copies, use_graph)
+                t_f = time_sequence(torch, w.fused, w.copies, steps, w.copies, use_graph) if batch == 1 else None
                 gb = w.mean_kept_bytes / (t_g * 1e-6) / 1e9
                 sweep.append({"config": config, "tensor": tensor, "M": m, "K": k, "batch": batch, "sparsity_per_row": s,
                               "kept_frac": round(float(np.mean(w.n_ns)) / k, 4),
-                              "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3),
+                              "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3), "us_fused": None if t_f is None else round(t_f, 3),
                               "GBps_kept": round(gb, 1), "frac_of_8TBps": round(gb / HBM_PEAK_GBPS, 4),
                               "dense_GBps": round(w.dense_bytes / (t_d * 1e-6) / 1e9, 1),
                               "speedup_vs_dense": round(t_d / t_g, 3)})

@@ -138,6 +138,20 @@ int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const 
                  void *workspace_dev, size_t workspace_bytes, void *stream,
                  const spqt_launch_cfg *cfg);
 
+/* DEVICE, async.  Gather and GEMV in ONE launch, batch 1: the kernel applies the sparsity test of
+ * Section 2 (sparse iff |x_i| < threshold, compared in fp32) to x itself, compacts the kept
+ * columns of each 64-column stretch with a wavefront ballot, and multiplies - no index list
+ * is written and n_ns is never materialised.  Same y as spqt_gather followed by spqt_gemv (the
+ * summation order differs, so the last bits may).  Because the index list does not exist, the
+ * work of a block-row is split into equal COLUMN ranges instead of equal shares of the list
+ * (Section 4.2.3): balanced when the kept columns are spread evenly, as with iid activations.
+ * This is the combination the paper's threshold sharing aims at (Section 5: fewer index
+ * collections per layer), taken to one collection per GEMV at no extra launch.
+ * Arguments as for spqt_gemv; cfg may be NULL. */
+int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+                    float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                    void *stream, const spqt_launch_cfg *cfg);
+
 /* The launch shape spqt_gemv would pick for this shape (host only, no device access). */
 int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spqt_launch_cfg *out);
 

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     spqt_default_cfg,
     spqt_gather,
     spqt_gemv,
+    spqt_gemv_fused,
     spqt_pack,
     spqt_packed_bytes,
     spqt_status_str,

@@ -23,7 +23,8 @@ MAX_SPLITS = 64
 
 EXPORTS = [
     "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",
-    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gemv", "spqt_gemv_ex", "spqt_default_cfg",
+    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gemv", "spqt_gemv_ex", "spqt_gemv_fused",
+    "spqt_default_cfg",
 ]
 
 
@@ -59,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.spqt_gemv.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         L.spqt_gemv_ex.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp,
                                    c.POINTER(LaunchCfg)]
+        L.spqt_gemv_fused.argtypes = [vp, i64, i64, i32, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_default_cfg.argtypes = [i64, i64, i32, i32, c.POINTER(LaunchCfg)]
         for name in EXPORTS[1:]:
             getattr(L, name).restype = i32
@@ -192,3 +194,20 @@ def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, 
     else:
         rc = lib().spqt_gemv(pp, M, K, group, xp, batch, ip, cp, yp, wp, wbytes, _stream_ptr(stream))
     _check(rc)
+
+
+def spqt_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, stream=None,
+                    group: int = GROUP, splits: int = 0, waves: int = 0) -> None:
+    """Threshold + compaction + GEMV in one launch (batch 1): x fp16[K], y fp32[M]."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp = _dev(y, torch.float32, "y")
+    if x.numel() != K or y.numel() != M or packed.numel() < spqt_packed_bytes(M, K, group):
+        raise SpqtError("spqt_gemv_fused: x / y / packed sizes do not match M, K (batch 1 only)")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    cfg = LaunchCfg(int(splits), int(waves))
+    _check(lib().spqt_gemv_fused(pp, M, K, group, xp, float(threshold), yp, wp, wbytes,
+                                 _stream_ptr(stream), ctypes.byref(cfg)))

@@ -171,11 +171,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 // BATCH activation rows share one pass over the weights: the index list is the union of the
 // rows' kept columns, every dequantized code is multiplied by each row's own x, and each row
 // has its own accumulators, bias sum and output.
-template <int WAVES, bool DENSE, int BATCH>
+//
+// FUSED: the kernel thresholds x itself instead of reading an index list.  The slice of a
+// wavefront is then a static range of 64-column units (K/64 units split evenly over the S*WAVES
+// wavefronts of the block-row); each unit is one pass: lane l tests column 64u + l, a ballot
+// gives the kept set, mbcnt the rank of every kept column, and the (offset, x) pairs are written
+// to the staging slot in rank order - the same compacted form the index-list path stages.
+template <int WAVES, bool DENSE, int BATCH, bool FUSED>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
+    void *partials, int32_t *epochs, int K, int NG, int S, int T, int M, float thr) {
     // Two staging slots per wave (the pass being multiplied and the pass being fetched).
     __shared__ uint32_t stage_off[WAVES][2][kPassCols];      // byte offset of each column of the pass
     __shared__ float stage_x[WAVES][2][BATCH][kPassCols];    // its x per batch row, pre-scaled by 2^24
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     if (S > 1) tag = __hip_atomic_load(epochs + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
 
     // Even split of the index list over the S*WAVES wavefronts of this block-row.
-    const int n_ns = DENSE ? K : __builtin_amdgcn_readfirstlane(*count);
+    const int n_ns = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));
     const int parts = S * WAVES;
     const int part = s * WAVES + wave;
     int pos = (int)(((int64_t)n_ns * part) / parts);
@@ -271,11 +277,15 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
 
         // MULTIPLY stage of a fetched pass.
         auto multiply = [&](int n, const uint32_t(&xraw)[BATCH], int slot, const u32x4(&w)[8]) {
+            if (FUSED) {    // the fused fetch stage has already staged x; xraw carries this lane's share
+                xsum[0] += as_float(xraw[0]);
+            } else {
 #pragma unroll
-            for (int b = 0; b < BATCH; ++b) {
-                const float xs = lane < n ? half_bits_to_float(xraw[b]) * kTwo24 : 0.0f;
-                xsum[b] += xs;
-                stage_x[wave][slot][b][lane] = xs;
+                for (int b = 0; b < BATCH; ++b) {
+                    const float xs = lane < n ? half_bits_to_float(xraw[b]) * kTwo24 : 0.0f;
+                    xsum[b] += xs;
+                    stage_x[wave][slot][b][lane] = xs;
+                }
             }
             __builtin_amdgcn_wave_barrier();
             if (BATCH == 1) {
@@ -315,6 +325,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
 
         // Fold the finished group (whose scales are `sc`) into yacc.
         auto flush = [&](u32x2 sc) {
+            if (FUSED && fresh) return;   // no kept column in this group's share: nothing accumulated
             const uint32_t s01 = sc.x, s23 = sc.y;
             const f16x2 h01 = as_f16x2(s01), h23 = as_f16x2(s23);
 #pragma unroll
@@ -336,6 +347,68 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         u32x2 scA, scB;
         uint32_t xrA[BATCH], xrB[BATCH];
         int nA, nB, gA, gB, kA, kB;
+        if (FUSED) {
+            // FETCH stage of unit u (xr = this lane's x[64u + lane], requested one stage earlier):
+            // threshold, rank, stage, request the next unit's x, the weights and the scales.
+            auto fetch_unit = [&](uint32_t xr, int u, int slot, u32x4(&w)[8], int &n_out, int &g_out,
+                                  u32x2 &sc_out, uint32_t &xr_next, uint32_t &xs_bits) {
+                const bool any = u < end;
+                const int g = any ? (u >> 1) : 0;
+                const float xf = half_bits_to_float(xr);
+                const bool keep = any && !(__builtin_fabsf(xf) < thr);
+                const uint64_t mask = __ballot(keep);
+                const int n = __builtin_amdgcn_readfirstlane((int)__popcll(mask));
+                const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                {   // next unit's x (index clamped: the value is unused past the slice)
+                    const int c = (u + 1) * kPassCols + lane;
+                    xr_next = x[c < K ? c : K - 1];
+                }
+                // kept columns go to entries 0..n-1 in ascending order; the other lanes fill entries
+                // n..63 with the pass's first kept column and x = 0
+                const int first_lane = n ? (int)__builtin_ctzll(mask) : 0;
+                const uint32_t koff_first = (uint32_t)(((u & 1) * kPassCols + first_lane) * kColBytes);
+                const uint32_t koff_own = (uint32_t)(((u & 1) * kPassCols + lane) * kColBytes);
+                const int entry = keep ? rank : n + lane - rank;
+                const float xs = keep ? xf * kTwo24 : 0.0f;
+                xs_bits = as_u32(xs);   // added to the group's bias sum when the unit is multiplied
+                stage_off[wave][slot][entry] = keep ? koff_own : koff_first;
+                stage_x[wave][slot][0][entry] = xs;
+                const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;   // wave-uniform base
+                __builtin_amdgcn_wave_barrier();
+                uint32_t off[8];
+#pragma unroll
+                for (int v = 0; v < 8; ++v) off[v] = stage_off[wave][slot][v * 8 + cg] + seg16;
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    w[v] = __builtin_nontemporal_load(
+                        reinterpret_cast<const u32x4 *>(chunk + kScaleBytes + (size_t)off[v]));
+                sc_out = *reinterpret_cast<const u32x2 *>(chunk + (size_t)sc_off);
+                n_out = n;
+                g_out = g;
+            };
+            uint32_t xa = x[pos * kPassCols + lane], xb;
+            fetch_unit(xa, pos, 0, wA, nA, gA, scA, xb, xrA[0]);
+            for (;;) {
+                const int uB = pos + 1;
+                fetch_unit(xb, uB, 1, wB, nB, gB, scB, xa, xrB[0]);
+                if (nA > 0) multiply(nA, xrA, 0, wA);
+                if (uB >= end) {
+                    flush(scA);
+                    break;
+                }
+                if (gB != gA) flush(scA);
+                const int uA = uB + 1;
+                fetch_unit(xa, uA, 0, wA, nA, gA, scA, xb, xrA[0]);
+                if (nB > 0) multiply(nB, xrB, 1, wB);
+                if (uA >= end) {
+                    flush(scB);
+                    break;
+                }
+                if (gA != gB) flush(scB);
+                pos = uA;
+            }
+        } else {
         kA = fetch_k(pos);
         fetch(kA, pos, 0, wA, nA, gA, xrA, scA, kB);
         if (BATCH > 1) {
@@ -376,6 +449,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             }
             if (gA != gB) flush(scB);
             pos = posA;
+        }
         }
     }
 
@@ -451,11 +525,20 @@ hipError_t launch(bool dense, int grid, hipStream_t stream, const uint8_t *packe
                   const int32_t *idx, const int32_t *count, float *y, void *partials,
                   int32_t *epochs, int K, int NG, int S, int T, int M) {
     if (dense)
-        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true, BATCH>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true, BATCH, false>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, 0.0f);
     else
-        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, BATCH>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, BATCH, false>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, 0.0f);
+    return hipGetLastError();
+}
+
+template <int WAVES>
+hipError_t launch_fused(int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x, float thr,
+                        float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
+    hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                       packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K, NG,
+                       S, T, M, thr);
     return hipGetLastError();
 }
 
@@ -560,6 +643,47 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
     }
     if (err != hipSuccess) return SPQT_EHIP;
     return SPQT_OK;
+}
+
+extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+                               float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                               void *stream, const spqt_launch_cfg *cfg) {
+    if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
+    if (threshold != threshold) return SPQT_EINVAL;
+    if (int rc = check_shape(M, K, group)) return rc;
+    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
+        return SPQT_EALIGN;
+    spqt_launch_cfg c;
+    if (int rc = spqt_default_cfg(M, K, 1, 1, &c)) return rc;
+    if (cfg) {
+        if (cfg->splits) c.splits = cfg->splits;
+        if (cfg->waves) c.waves = cfg->waves;
+    }
+    if (c.splits < 1 || c.splits > SPQT_MAX_SPLITS) return SPQT_EINVAL;
+    if (c.waves != 1 && c.waves != 2 && c.waves != 4) return SPQT_EINVAL;
+    size_t need = 0;
+    spqt_workspace_bytes(M, K, 1, &need);
+    void *partials = nullptr;
+    int32_t *epochs = nullptr;
+    if (c.splits > 1) {
+        if (!workspace_dev) return SPQT_EINVAL;
+        if (workspace_bytes < need) return SPQT_ESIZE;
+        if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
+        epochs = (int32_t *)workspace_dev;
+        partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
+    }
+    const int T = (int)(M / kTileRows), NG = (int)(K / kGroup);
+    const int grid = 8 * ((T + 7) / 8) * c.splits;
+    hipStream_t st = (hipStream_t)stream;
+    const uint8_t *pk = (const uint8_t *)packed_dev;
+    const uint16_t *xp = (const uint16_t *)x_dev;
+    hipError_t err;
+    switch (c.waves) {
+        case 1: err = launch_fused<1>(grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        case 2: err = launch_fused<2>(grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        default: err = launch_fused<4>(grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+    }
+    return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }
 
 extern "C" int spqt_gemv(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,

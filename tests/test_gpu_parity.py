@@ -246,6 +246,64 @@ def test_batch_rows_share_one_pass(gpu, batch, splits, waves):
     assert_close(gpu_gemv(gpu, w, x, 0.0, dense=True, splits=splits, waves=waves), ref0, "batch dense")
 
 
+def gpu_gemv_fused(gpu, w, x_np, thr, splits=0, waves=0, packed=None):
+    torch, spqt, dev = gpu
+    M, K = w["q_rowmajor"].shape[0], w["q_rowmajor"].shape[1] * 2
+    if packed is None:
+        packed = torch.from_numpy(spqt.spqt_pack(w["q_rowmajor"], w["scales"])).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)[0]
+    y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K)
+    spqt.spqt_gemv_fused(packed, M, K, x, thr, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()[None, :]
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 1024), (1024, 4096), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (2, 4), (7, 2), (16, 4), (64, 1)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_fused_gather_gemv(gpu, M, K, splits, waves, sparsity):
+    """The one-launch path (threshold + in-wave compaction + GEMV) against the oracle."""
+    w = make_weights(M, K, 7100 + M + K)
+    x = make_x(K, "laplace", 7101 + M + K)
+    thr = quantile_threshold(x, sparsity)
+    say(f"fused M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    assert_close(gpu_gemv_fused(gpu, w, x, thr, splits=splits, waves=waves), ref, "fused")
+
+
+def test_fused_clustered_ties_and_exact(gpu):
+    M, K = 1024, 2048
+    w = make_weights(M, K, 61)
+    x = make_x(K, "laplace", 62)
+    x[0, 0:512] = 0            # empty groups and empty 64-column units
+    x[0, 640:768] = 0
+    x[0, 700] = 3.0            # a group with one kept column
+    x[0, 1024:1152] = 2.0      # a full group
+    x[0, 1500] = 0.75          # a tie with the threshold is kept
+    thr = 0.75
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    for splits, waves in [(0, 0), (1, 1), (5, 4), (16, 2)]:
+        assert_close(gpu_gemv_fused(gpu, w, x, thr, splits=splits, waves=waves), ref, f"fused clustered {splits}x{waves}")
+    # exact-arithmetic inputs: bit-for-bit
+    rng = np.random.default_rng(5)
+    w["scales"] = (2.0 ** rng.integers(-6, -2, size=(M, K // 128))).astype(np.float16)
+    xi = rng.integers(-4, 5, size=(1, K)).astype(np.float16)
+    for thr in (0.0, 2.0, 3.0):
+        ref = oracle.gemv(w["q_rowmajor"], w["scales"], xi, thr)
+        assert np.array_equal(gpu_gemv_fused(gpu, w, xi, thr).astype(np.float64), ref), thr
+
+
+def test_fused_full_size_headline(gpu):
+    torch, spqt, dev = gpu
+    case = make_case(2, "q", want_q=False)
+    packed = torch.from_numpy(spqt.spqt_pack(case["q_rowmajor"], case["scales"])).to(dev)
+    for s in (0.0, 0.25, 0.5, 0.65):
+        thr = quantile_threshold(case["x"], s)
+        ref = oracle.gemv(case["q_rowmajor"], case["scales"], case["x"], thr)
+        assert_close(gpu_gemv_fused(gpu, case, case["x"], thr, packed=packed), ref, f"fused cfg2 s={s}")
+
+
 def test_hip_graph_replay_matches_eager(gpu):
     """gather + GEMV captured in one HIP graph and replayed, with eager work and
     synchronizations between the replays: every replay must reproduce the eager result."""
