@@ -203,6 +203,142 @@ def calibrate(torch, nbytes_like):
     return t_empty, t_small, size, (1 << 30) / (t_big * 1e-6) / 1e9
 
 
+def layer_sequence(torch, spqt, config, layers, sparsity, use_graph=True, reps=5):
+    """Decoder-layer GEMV sequence (configs 3 and 4): every projection of every layer has its own
+    independently seeded weights and a threshold calibrated offline (separate 64*K draw) for the
+    requested sparsity; activations are per input site (attention input, o input, MLP input,
+    down input).  One HIP graph holds the whole multi-layer pass.  Returns per-mode timings."""
+    import numpy as np
+    from workloads import (CONFIG_SHAPES, CONFIG_SCALE_RANGE, KIND_CALIB, KIND_X, calibrated_threshold,
+                           make_x, seed_for)
+    dev = torch.device("cuda:0")
+    shapes = CONFIG_SHAPES[config]
+    lo, hi = CONFIG_SCALE_RANGE[config]
+    site_of = {"q": "attn", "k": "attn", "v": "attn", "o": "o", "gate": "mlp", "up": "mlp", "down": "down"}
+    thr = {name: calibrated_threshold(K, dist, sparsity, seed_for(config, 0, name, KIND_CALIB))
+           for name, M, K, dist in shapes}
+    L = []          # per layer: list of (name, M, K, packed, x, thr, idx, cnt, y, site)
+    kept_bytes_total, dense_bytes_total, n_gemv = 0.0, 0.0, 0
+    ws = {}
+    for layer in range(layers):
+        xs = {}
+        items = []
+        for name, M, K, dist in shapes:
+            site = site_of[name]
+            if site not in xs:
+                xv = make_x(K, dist, seed_for(config, layer, name, KIND_X))
+                xs[site] = torch.from_numpy(xv[0]).to(dev)
+            g = torch.Generator(device=dev)
+            g.manual_seed(seed_for(config, layer, name))
+            T, NG = M // 256, K // 128
+            buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NG, 256), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
+            buf[:, :512] = sc.view(torch.uint8)
+            if (M, K) not in ws:
+                ws[(M, K)] = spqt.new_workspace(M, K)
+            idx = torch.zeros(K, dtype=torch.int32, device=dev)
+            cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+            y = torch.zeros(M, dtype=torch.float32, device=dev)
+            items.append((name, M, K, buf.reshape(-1), xs[site], thr[name], idx, cnt, y, site))
+        L.append(items)
+    # Projections that read the same activations, packed as ONE matrix: block-rows are the
+    # storage unit of the layout, so concatenating packed buffers along M is concatenating bytes.
+    # {q,k,v} and {gate,up} then share one threshold, as in the paper's customized mode (Section 5).
+    merged = []
+    for items in L:
+        groups, order = {}, []
+        for it in items:
+            if it[9] not in groups:
+                groups[it[9]] = []
+                order.append(it[9])
+            groups[it[9]].append(it)
+        mitems = []
+        for site in order:
+            g_items = groups[site]
+            Mtot = sum(it[1] for it in g_items)
+            K = g_items[0][2]
+            pk = torch.cat([it[3] for it in g_items]) if len(g_items) > 1 else g_items[0][3]
+            if (Mtot, K) not in ws:
+                ws[(Mtot, K)] = spqt.new_workspace(Mtot, K)
+            y = torch.zeros(Mtot, dtype=torch.float32, device=dev)
+            mitems.append((Mtot, K, pk, g_items[0][4], g_items[0][5], g_items[0][6], g_items[0][7], y))
+        merged.append(mitems)
+
+    # achieved kept counts (one eager pass)
+    for items in L:
+        for name, M, K, pk, x, t, idx, cnt, y, site in items:
+            spqt.spqt_gather(x, t, idx, cnt)
+    torch.cuda.synchronize()
+    for items in L:
+        for name, M, K, pk, x, t, idx, cnt, y, site in items:
+            kept_bytes_total += kept_bytes(M, K, int(cnt.item()))
+            dense_bytes_total += kept_bytes(M, K, K)
+            n_gemv += 1
+
+    def run(mode):
+        if mode.startswith("merged"):
+            for mitems in merged:
+                for Mtot, K, pk, x, t, idx, cnt, y in mitems:
+                    if mode == "merged_fused":
+                        spqt.spqt_gemv_fused(pk, Mtot, K, x, t, y, ws[(Mtot, K)])
+                    elif mode == "merged_dense":
+                        spqt.spqt_gemv(pk, Mtot, K, x, None, None, y, ws[(Mtot, K)])
+                    else:
+                        spqt.spqt_gather(x, t, idx, cnt)
+                        spqt.spqt_gemv(pk, Mtot, K, x, idx, cnt, y, ws[(Mtot, K)])
+            return
+        for items in L:
+            done_sites = {}
+            for name, M, K, pk, x, t, idx, cnt, y, site in items:
+                w = ws[(M, K)]
+                if mode == "dense":
+                    spqt.spqt_gemv(pk, M, K, x, None, None, y, w)
+                elif mode == "fused":
+                    spqt.spqt_gemv_fused(pk, M, K, x, t, y, w)
+                elif mode == "strict":          # one gather per projection
+                    spqt.spqt_gather(x, t, idx, cnt)
+                    spqt.spqt_gemv(pk, M, K, x, idx, cnt, y, w)
+                else:                           # "shared": one gather per input site (threshold sharing)
+                    if site not in done_sites:
+                        spqt.spqt_gather(x, t, idx, cnt)
+                        done_sites[site] = (idx, cnt)
+                    si, sc_ = done_sites[site]
+                    spqt.spqt_gemv(pk, M, K, x, si, sc_, y, w)
+
+    out = {"config": config, "layers": layers, "gemvs_per_layer": len(shapes), "sparsity_target": sparsity,
+           "packed_MB": round(dense_bytes_total / 1e6, 1), "kept_MB": round(kept_bytes_total / 1e6, 1)}
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for mode in ("strict", "shared", "fused", "merged_gather_gemv", "merged_fused", "dense", "merged_dense"):
+        run(mode)
+        torch.cuda.synchronize()
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            if use_graph:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    run(mode)
+                fn = g.replay
+            else:
+                fn = lambda: run(mode)
+            fn()
+            torch.cuda.synchronize()
+            start.record()
+            for _ in range(reps):
+                fn()
+            stop.record()
+            torch.cuda.synchronize()
+        us_pass = start.elapsed_time(stop) * 1e3 / reps
+        nbytes = dense_bytes_total if mode.endswith("dense") else kept_bytes_total
+        out[mode] = {"us_per_layer": round(us_pass / layers, 2), "us_per_gemv": round(us_pass / n_gemv, 3),
+                     "GBps": round(nbytes / (us_pass * 1e-6) / 1e9, 1)}
+    out["speedup_strict_vs_dense"] = round(out["dense"]["us_per_layer"] / out["strict"]["us_per_layer"], 3)
+    out["speedup_fused_vs_dense"] = round(out["dense"]["us_per_layer"] / out["fused"]["us_per_layer"], 3)
+    out["speedup_merged_fused_vs_merged_dense"] = round(out["merged_dense"]["us_per_layer"] / out["merged_fused"]["us_per_layer"], 3)
+    out["launches_per_layer"] = {"strict": 2 * len(shapes), "shared": len(shapes) + len(merged[0]), "fused": len(shapes),
+                                 "merged_gather_gemv": 2 * len(merged[0]), "merged_fused": len(merged[0]), "dense": len(shapes), "merged_dense": len(merged[0])}
+    return out
+
+
 def cpu_baseline(case, x_np, thr, budget_s=12.0):
     """The oracle as it stands, timed on the host cores, on repeated calls for about budget_s."""
     import oracle
@@ -351,6 +487,12 @@ def main():
                 del w
                 torch.cuda.empty_cache()
         out["sweep"] = sweep
+        if args.full:
+            # decoder-layer sequences: Llama-2-7B MLP over 16 layers (config 3), Llama-3-8B full layer
+            # over 32 layers (config 4); spqt_gather time included
+            out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),
+                                      layer_sequence(torch, spqt, 3, 16, 0.5, use_graph),
+                                      layer_sequence(torch, spqt, 4, 32, 0.5, use_graph)]
 
     # ---------------- CPU oracle baseline --------------------------------------------------
     if not args.no_cpu:
