@@ -18,6 +18,10 @@ extern "C" {
  * sink_dev (one uint32) is written only if the XOR of everything read has an unlikely value. */
 int spqt_calib_read(const void *src_dev, size_t bytes, uint32_t *sink_dev, int blocks, int unroll,
                     void *stream);
+/* Same read, but each wavefront owns one contiguous slice of the buffer and walks it 1 KB at a
+ * time, `unroll` (2, 4, 8, 16) loads in flight - the order a GEMV wavefront reads its columns in. */
+int spqt_calib_read_blocked(const void *src_dev, size_t bytes, uint32_t *sink_dev, int blocks, int unroll,
+                            void *stream);
 /* Copies `bytes` (multiple of 16) from src to dst: reads bytes, writes bytes. */
 int spqt_calib_copy(void *dst_dev, const void *src_dev, size_t bytes, int blocks, void *stream);
 /* Launches one empty workgroup. */

@@ -27,6 +27,29 @@ __global__ __launch_bounds__(256) void read_kernel(const u32x4 *__restrict__ src
     if (x == 0x9E3779B9u) *sink = x;
 }
 
+// Same bytes, but every wavefront owns one contiguous slice and walks it 1 KB at a time (the
+// access order of a GEMV wavefront that owns a contiguous range of columns).
+template <int UNROLL>
+__global__ __launch_bounds__(256) void read_blocked_kernel(const u32x4 *__restrict__ src, size_t n16,
+                                                           uint32_t *sink) {
+    const size_t waves = (size_t)gridDim.x * 4;
+    const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t per = (n16 / 64 + waves - 1) / waves * 64;      // 16-byte units per wave, multiple of 64
+    size_t i = wave * per + (threadIdx.x & 63);
+    const size_t stop = (wave + 1) * per < n16 ? (wave + 1) * per : n16;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + (UNROLL - 1) * 64 < stop; i += UNROLL * 64) {
+        u32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 64);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) acc ^= v[u];
+    }
+    for (; i < stop; i += 64) acc ^= __builtin_nontemporal_load(src + i);
+    const uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (x == 0x9E3779B9u) *sink = x;
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
                                                    size_t n16) {
     const size_t stride = (size_t)gridDim.x * 256;
@@ -50,6 +73,23 @@ extern "C" int spqt_calib_read(const void *src_dev, size_t bytes, uint32_t *sink
         case 4: hipLaunchKernelGGL(read_kernel<4>, dim3(blocks), dim3(256), 0, st, src, n16, sink_dev); break;
         case 8: hipLaunchKernelGGL(read_kernel<8>, dim3(blocks), dim3(256), 0, st, src, n16, sink_dev); break;
         case 16: hipLaunchKernelGGL(read_kernel<16>, dim3(blocks), dim3(256), 0, st, src, n16, sink_dev); break;
+        default: return -1;
+    }
+    return hipGetLastError() == hipSuccess ? 0 : -5;
+}
+
+extern "C" int spqt_calib_read_blocked(const void *src_dev, size_t bytes, uint32_t *sink_dev, int blocks,
+                                       int unroll, void *stream) {
+    if (!src_dev || !sink_dev || bytes == 0 || bytes % 16 || (uintptr_t)src_dev % 16) return -1;
+    const size_t n16 = bytes / 16;
+    if (blocks <= 0) blocks = 512;
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4 *src = (const u32x4 *)src_dev;
+    switch (unroll) {
+        case 2: hipLaunchKernelGGL(read_blocked_kernel<2>, dim3(blocks), dim3(256), 0, st, src, n16, sink_dev); break;
+        case 4: hipLaunchKernelGGL(read_blocked_kernel<4>, dim3(blocks), dim3(256), 0, st, src, n16, sink_dev); break;
+        case 8: hipLaunchKernelGGL(read_blocked_kernel<8>, dim3(blocks), dim3(256), 0, st, src, n16, sink_dev); break;
+        case 16: hipLaunchKernelGGL(read_blocked_kernel<16>, dim3(blocks), dim3(256), 0, st, src, n16, sink_dev); break;
         default: return -1;
     }
     return hipGetLastError() == hipSuccess ? 0 : -5;
