@@ -24,13 +24,17 @@
 //     place at bit 0..3 (or 4..7) of a 16-bit half IS the fp16 subnormal n*2^-24 (or
 //     16n*2^-24), which v_fma_mix_f32 multiplies by a pre-scaled x*2^24 (x*2^20) into the fp32
 //     accumulator - exact products, fp32 accumulation.
-//   - per group: the 8 column-lanes are folded with a transposing butterfly (permlane32/16
-//     swaps + one DPP rotate), leaving each lane 4 rows; the offset-binary bias (stored =
-//     q + 8) is removed there as -8 * (sum of the group's kept x), and the fp16 group scale is
-//     applied once per (row, group): y_acc += scale * (sum - bias).
+//   - per pass: the 8 column-lanes are folded with a transposing butterfly (bank-masked DPP
+//     adds, then permlane16/32 swaps), leaving each lane 4 rows that are added to the group's
+//     running sums.  Folding every pass instead of once per group keeps the 32 accumulators
+//     local to the multiply stage (nothing wide is carried around the loop), which is worth
+//     more in registers and copies than the ~56 instructions an extra fold costs.
+//   - per group: the offset-binary bias (stored = q + 8) is removed as -8 * (sum of the
+//     group's kept x), and the fp16 group scale is applied once per (row, group):
+//     y_acc += scale * (sum - bias).
 //   - WAVES wavefronts are combined through LDS, the S workgroups of a block-row through a
-//     workspace: the last one to arrive adds the partials in fixed order and writes y.  No
-//     floating-point atomics, so results are reproducible.
+//     workspace of tagged words: the workgroup with the highest index adds the others' partial
+//     sums in fixed order and writes y.  No floating-point atomics, so results are reproducible.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -62,7 +66,7 @@ __device__ __forceinline__ f16x2 as_f16x2(uint32_t bits) { return __builtin_bit_
 // Eight codes of one dword: acc[i] (+)= n_i * x for nibble i (row 8d+i of the lane's 32 rows).
 // xlo = x * 2^24 pairs with nibbles sitting at bits 0..3 of a half, xhi = x * 2^20 with
 // nibbles at bits 4..7 (value 16 n * 2^-24).  INIT overwrites the accumulators (first step of
-// a group) instead of adding to them.
+// a pass) instead of adding to them.
 template <bool INIT>
 __device__ __forceinline__ void fma_codes(uint32_t w, float xlo, float xhi, float *acc) {
     const uint32_t w8 = w >> 8;
@@ -233,15 +237,15 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             return e < end ? v : -1;
         };
 
-        float acc[BATCH][32];           // current group, this lane's columns, unscaled
+        float gacc[BATCH][4];           // current group, rows 32 seg + 4 rev(cg) + j, unscaled
         float xsum[BATCH];              // current group: pre-scaled x of the columns this lane staged
 #pragma unroll
         for (int b = 0; b < BATCH; ++b) {
             xsum[b] = 0.0f;
 #pragma unroll
-            for (int i = 0; i < 32; ++i) acc[b][i] = 0.0f;
+            for (int j = 0; j < 4; ++j) gacc[b][j] = 0.0f;
         }
-        bool fresh = true;              // the next step is the first of its group: it overwrites acc
+        bool fresh = true;              // nothing accumulated for the current group yet
 
         // FETCH stage of the pass that starts at list position p (kk = fetch_k(p)): delimit the
         // pass (the run of entries that share the group of idx[p], at most 64), request the
@@ -288,36 +292,38 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                 }
             }
             __builtin_amdgcn_wave_barrier();
+            // The pass's products live only inside this stage: the first step overwrites the 32
+            // accumulators, the others add to them, and the fold at the end leaves 4 sums per lane.
+            float acc[BATCH][32];
             if (BATCH == 1) {
                 float xl[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) xl[u] = stage_x[wave][slot][0][u * 8 + cg];
-                if (fresh) {
-                    asm volatile("" ::);   // not speculatable: stays a wave-uniform branch, not 32 selects
-                    fma_step<true>(w[0], xl[0], acc[0]);
-                } else {
-                    fma_step<false>(w[0], xl[0], acc[0]);
-                }
+                fma_step<true>(w[0], xl[0], acc[0]);
 #pragma unroll
                 for (int u = 1; u < 8; ++u)
                     if (u * 8 < n) fma_step<false>(w[u], xl[u], acc[0]);
             } else {
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    if (u * 8 < n) {
+                    if (u == 0 || u * 8 < n) {
                         float xl[BATCH];
 #pragma unroll
                         for (int b = 0; b < BATCH; ++b) xl[b] = stage_x[wave][slot][b][u * 8 + cg];
-                        if (u == 0 && fresh) {
-                            asm volatile("" ::);
 #pragma unroll
-                            for (int b = 0; b < BATCH; ++b) fma_step<true>(w[u], xl[b], acc[b]);
-                        } else {
-#pragma unroll
-                            for (int b = 0; b < BATCH; ++b) fma_step<false>(w[u], xl[b], acc[b]);
+                        for (int b = 0; b < BATCH; ++b) {
+                            if (u == 0) fma_step<true>(w[u], xl[b], acc[b]);
+                            else fma_step<false>(w[u], xl[b], acc[b]);
                         }
                     }
                 }
+            }
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                float r4[4];
+                fold_columns(acc[b], r4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gacc[b][j] += r4[j];
             }
             fresh = false;
             __builtin_amdgcn_wave_barrier();
@@ -330,14 +336,14 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             const f16x2 h01 = as_f16x2(s01), h23 = as_f16x2(s23);
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
-                float r4[4];
-                fold_columns(acc[b], r4);
                 const float bias = wave_sum(xsum[b]) * (-8.0f / kTwo24);
-                yacc[b][0] = __builtin_fmaf((float)h01.x, r4[0] + bias, yacc[b][0]);
-                yacc[b][1] = __builtin_fmaf((float)h01.y, r4[1] + bias, yacc[b][1]);
-                yacc[b][2] = __builtin_fmaf((float)h23.x, r4[2] + bias, yacc[b][2]);
-                yacc[b][3] = __builtin_fmaf((float)h23.y, r4[3] + bias, yacc[b][3]);
+                yacc[b][0] = __builtin_fmaf((float)h01.x, gacc[b][0] + bias, yacc[b][0]);
+                yacc[b][1] = __builtin_fmaf((float)h01.y, gacc[b][1] + bias, yacc[b][1]);
+                yacc[b][2] = __builtin_fmaf((float)h23.x, gacc[b][2] + bias, yacc[b][2]);
+                yacc[b][3] = __builtin_fmaf((float)h23.y, gacc[b][3] + bias, yacc[b][3]);
                 xsum[b] = 0.0f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gacc[b][j] = 0.0f;
             }
             fresh = true;
         };
