@@ -65,6 +65,7 @@ class Workload:
             buf[:, :512] = sc.view(torch.uint8)
             self.packed.append(buf.reshape(-1))
         xs, thr = [], []
+        self.dist = dist
         for layer in range(self.copies):
             x = make_x(K, dist, seed_for(config, layer, tensor, KIND_X), batch)
             xs.append(x[0] if batch == 1 else x)
@@ -96,6 +97,10 @@ class Workload:
 
     def fused(self, i):
         self.spqt.spqt_gemv_fused(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws)
+
+    def fused_no_compaction(self, i):
+        self.spqt.spqt_gemv_fused(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws,
+                                  flags=self.spqt.CFG_NO_COMPACTION)
 
     def dense_only(self, i):
         self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], None, None, self.y[i], self.ws)
@@ -201,6 +206,73 @@ def calibrate(torch, nbytes_like):
     del big
     torch.cuda.empty_cache()
     return t_empty, t_small, size, (1 << 30) / (t_big * 1e-6) / 1e9
+
+
+def ablations(torch, spqt, use_graph):
+    """Section 6.3's question on this hardware, on the 70B gate shape at 50 %: what do the index
+    list's even split (Section 4.2.3) and the compaction buy?  Two activation patterns: iid
+    Laplace (kept columns spread evenly) and a clustered one (7 of 8 kept columns in the first
+    half of K), three kernels: list-balanced (spqt_gather + spqt_gemv), static column ranges
+    with in-kernel test and compaction (spqt_gemv_fused), the same without compaction."""
+    import numpy as np
+    from workloads import CONFIG_SCALE_RANGE
+    M, K, s = 28672, 8192, 0.5
+    rows = []
+    for dist in ("laplace", "laplace_clustered"):
+        w = Workload(torch, spqt, M, K, dist, CONFIG_SCALE_RANGE[5], 5, "gate", s)
+        # copy 0 against the oracle in every mode (the clustered pattern is not covered elsewhere at this size)
+        import oracle
+        ref = oracle.gemv(w.case0["q_rowmajor"], w.case0["scales"], w.x_np[0:1], w.thr[0])[0]
+        for fn in (w.step, w.fused, w.fused_no_compaction):
+            w.y[0].fill_(float("nan"))
+            fn(0)
+            torch.cuda.synchronize()
+            err = np.abs(w.y[0].cpu().numpy().astype(np.float64) - ref)
+            if not bool(np.all(err <= 1e-2 + 2e-3 * np.abs(ref))):
+                print(f"bench.py: ablation parity check FAILED ({dist}, {fn.__name__})", file=sys.stderr)
+                sys.exit(1)
+        steps = w.copies * 40
+        t = {name: time_sequence(torch, fn, w.copies, steps, w.copies, use_graph)
+             for name, fn in (("list_balanced_gemv", w.gemv_only), ("gather_plus_list_balanced_gemv", w.step),
+                              ("static_ranges_compacted", w.fused),
+                              ("static_ranges_no_compaction", w.fused_no_compaction), ("dense", w.dense_only))}
+        rows.append({"M": M, "K": K, "sparsity": s, "activations": dist,
+                     "kept_frac": round(float(np.mean(w.n_ns)) / K, 4),
+                     "us": {k: round(v, 3) for k, v in t.items()},
+                     "speedup_vs_dense": {k: round(t["dense"] / v, 3) for k, v in t.items() if k != "dense"}})
+        del w
+        torch.cuda.empty_cache()
+    return rows
+
+
+def dense_shape_sweep(torch, spqt, use_graph):
+    """The dense zigzag kernel on the 15 shapes of the paper's dense micro-benchmark
+    (Section 6.4: m in {2048, 4096, 8192} x k in {1024 ... 16384}); random packed bytes."""
+    dev = torch.device("cuda:0")
+    rows = []
+    for M in (2048, 4096, 8192):
+        for K in (1024, 2048, 4096, 8192, 16384):
+            pbytes = spqt.spqt_packed_bytes(M, K)
+            copies = max(2, -(-ROTATE_BYTES // pbytes))
+            g = torch.Generator(device=dev)
+            g.manual_seed(1000 * M + K)
+            T, NG = M // 256, K // 128
+            packed = []
+            for _ in range(copies):
+                buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+                sc = (torch.rand((T * NG, 256), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
+                buf[:, :512] = sc.view(torch.uint8)
+                packed.append(buf.reshape(-1))
+            x = torch.randn(K, device=dev, generator=g).to(torch.float16)
+            y = torch.empty(M, dtype=torch.float32, device=dev)
+            ws = spqt.new_workspace(M, K)
+            fn = lambda i: spqt.spqt_gemv(packed[i], M, K, x, None, None, y, ws)
+            us = time_sequence(torch, fn, copies, copies * 4, copies, use_graph)
+            rows.append({"M": M, "K": K, "us_dense": round(us, 3), "GBps": round(pbytes / (us * 1e-6) / 1e9, 1),
+                         "GFLOPS": round(2.0 * M * K / (us * 1e-6) / 1e9, 1)})
+            del packed
+            torch.cuda.empty_cache()
+    return rows
 
 
 def layer_sequence(torch, spqt, config, layers, sparsity, use_graph=True, reps=5):
@@ -490,6 +562,8 @@ def main():
         if args.full:
             # decoder-layer sequences: Llama-2-7B MLP over 16 layers (config 3), Llama-3-8B full layer
             # over 32 layers (config 4); spqt_gather time included
+            out["ablations"] = ablations(torch, spqt, use_graph)
+            out["dense_shape_sweep"] = dense_shape_sweep(torch, spqt, use_graph)
             out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),
                                       layer_sequence(torch, spqt, 3, 16, 0.5, use_graph),
                                       layer_sequence(torch, spqt, 4, 32, 0.5, use_graph)]

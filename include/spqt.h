@@ -70,15 +70,18 @@ const char *spqt_status_str(int status);
 /* Size in bytes of the packed form of an M x K matrix (layout above). */
 int spqt_packed_bytes(int64_t M, int64_t K, int group, size_t *out_bytes);
 
-/* Size in bytes of the device workspace spqt_gemv needs for this shape (partial sums of
- * the workgroups that share a block-row, plus one arrival counter per block-row).  The
- * workspace must be prepared ONCE with spqt_workspace_init before its first use; every
- * spqt_gemv call leaves it ready for the next one.  Two calls that may overlap in time
- * (different streams) need two workspaces. */
+/* Size in bytes of the device workspace spqt_gemv needs for this shape: one epoch counter
+ * per block-row plus, for each of up to SPQT_MAX_SPLITS workgroups that may share a
+ * block-row, 256 x batch 64-bit words {partial sum, tag} through which they hand their
+ * partial sums to the workgroup that writes y.  The workspace must be prepared ONCE with
+ * spqt_workspace_init before its first use; every call leaves it ready for the next one
+ * (the tag of a call is its block-row's epoch + 1, so words of earlier calls never match).
+ * Two calls that may overlap in time (different streams) need two workspaces; calls on one
+ * stream, or replays of one graph, may share one. */
 int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out_bytes);
 
-/* DEVICE, async.  Zeroes the arrival counters of a workspace (a small fill kernel, so it
- * is safe under graph capture). */
+/* DEVICE, async.  Clears the whole workspace (epochs and tagged words) with a small fill
+ * kernel, so it is safe under graph capture. */
 int spqt_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /* HOST, offline, once per matrix (Section 3.2: one-time conversion; Section 4.1.2: the
@@ -113,7 +116,14 @@ int spqt_gather(const void *x_dev, int64_t K, int batch, float threshold, int32_
 typedef struct {
     int splits; /* workgroups per block-row, 1..SPQT_MAX_SPLITS */
     int waves;  /* wavefronts per workgroup: 1, 2 or 4 */
+    int flags;  /* 0, or SPQT_CFG_* bits */
 } spqt_launch_cfg;
+
+/* spqt_gemv_fused only - an ablation in the spirit of Section 6.3's "no load balancing"
+ * variant: the sparsity test runs inside the kernel on static column ranges and a dropped
+ * column is NOT compacted away - it keeps its slot in the wavefront's step with x = 0.
+ * Skipping then saves memory traffic but no issue slots.  Same results as the default. */
+#define SPQT_CFG_NO_COMPACTION 1
 
 /* DEVICE, async.  y[b][m] = sum over the listed columns k of scale[m][k/128] * q[m][k] *
  * x[b][k], fp32 accumulation (Section 4.2.2 for the dense kernel, Section 4.2.3 for the
@@ -127,7 +137,10 @@ typedef struct {
  *   y_dev          fp32[batch][M], fully overwritten (zeros when n_ns == 0).
  *   workspace_dev  >= spqt_workspace_bytes(M, K, batch) bytes, prepared by
  *                  spqt_workspace_init (else SPQT_ESIZE / SPQT_EINVAL).
- * Deterministic: partial sums are combined in a fixed order, no floating-point atomics. */
+ * Deterministic: partial sums are combined in a fixed order, no floating-point atomics.
+ * The workgroup that combines a block-row waits for the others' partial sums; the wait is
+ * bounded, and if it ever gave up (it cannot while the device makes progress) the affected
+ * outputs are NaN rather than silently wrong. */
 int spqt_gemv(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
               int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
               void *workspace_dev, size_t workspace_bytes, void *stream);

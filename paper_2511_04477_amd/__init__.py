@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     GROUP,
     CHUNK_BYTES,
     MAX_SPLITS,
+    CFG_NO_COMPACTION,
     lib,
     new_workspace,
     spqt_default_cfg,

@@ -20,6 +20,7 @@ TILE_ROWS = 256
 GROUP = 128
 CHUNK_BYTES = 16896
 MAX_SPLITS = 64
+CFG_NO_COMPACTION = 1
 
 EXPORTS = [
     "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",
@@ -33,7 +34,7 @@ class SpqtError(RuntimeError):
 
 
 class LaunchCfg(ctypes.Structure):
-    _fields_ = [("splits", ctypes.c_int), ("waves", ctypes.c_int)]
+    _fields_ = [("splits", ctypes.c_int), ("waves", ctypes.c_int), ("flags", ctypes.c_int)]
 
 
 _lib = None
@@ -188,7 +189,7 @@ def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, 
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
     if splits or waves:
-        cfg = LaunchCfg(int(splits), int(waves))
+        cfg = LaunchCfg(int(splits), int(waves), 0)
         rc = lib().spqt_gemv_ex(pp, M, K, group, xp, batch, ip, cp, yp, wp, wbytes,
                                 _stream_ptr(stream), ctypes.byref(cfg))
     else:
@@ -197,7 +198,7 @@ def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, 
 
 
 def spqt_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, stream=None,
-                    group: int = GROUP, splits: int = 0, waves: int = 0) -> None:
+                    group: int = GROUP, splits: int = 0, waves: int = 0, flags: int = 0) -> None:
     """Threshold + compaction + GEMV in one launch (batch 1): x fp16[K], y fp32[M]."""
     import torch
     pp = _dev(packed, torch.uint8, "packed")
@@ -208,6 +209,6 @@ def spqt_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, s
     wp, wbytes = None, 0
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
-    cfg = LaunchCfg(int(splits), int(waves))
+    cfg = LaunchCfg(int(splits), int(waves), int(flags))
     _check(lib().spqt_gemv_fused(pp, M, K, group, xp, float(threshold), yp, wp, wbytes,
                                  _stream_ptr(stream), ctypes.byref(cfg)))

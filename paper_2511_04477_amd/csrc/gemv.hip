@@ -181,7 +181,10 @@ __device__ __forceinline__ float wave_sum(float v) {
 // wavefronts of the block-row); each unit is one pass: lane l tests column 64u + l, a ballot
 // gives the kept set, mbcnt the rank of every kept column, and the (offset, x) pairs are written
 // to the staging slot in rank order - the same compacted form the index-list path stages.
-template <int WAVES, bool DENSE, int BATCH, bool FUSED>
+// FUSED == 2 is an ablation: same test, same static ranges, but NO compaction - a dropped column
+// keeps its slot in the pass with x = 0 (and re-reads a kept column's line), so skipping saves
+// memory traffic but not one multiply step.
+template <int WAVES, bool DENSE, int BATCH, int FUSED>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint32_t seg16 = (uint32_t)seg * 16u;              // this lane's bytes inside a column run
     const uint32_t sc_off = (uint32_t)(seg * 64 + cgr * 8);  // this lane's 4 scales inside a chunk
     // Workgroups are handed to the 8 XCDs round-robin by index.  Keep all S workgroups of a
-    // block-row on ONE XCD (same index mod 8): their arrival counter then stays in that XCD's
+    // block-row on ONE XCD (same index mod 8): their epoch word and partial sums then stay in that XCD's
     // L2 instead of bouncing between dies.  Only a matter of speed, never of correctness.
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;          // position among this XCD's workgroups
@@ -375,7 +378,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                 const int first_lane = n ? (int)__builtin_ctzll(mask) : 0;
                 const uint32_t koff_first = (uint32_t)(((u & 1) * kPassCols + first_lane) * kColBytes);
                 const uint32_t koff_own = (uint32_t)(((u & 1) * kPassCols + lane) * kColBytes);
-                const int entry = keep ? rank : n + lane - rank;
+                const int entry = FUSED == 2 ? lane : (keep ? rank : n + lane - rank);
                 const float xs = keep ? xf * kTwo24 : 0.0f;
                 xs_bits = as_u32(xs);   // added to the group's bias sum when the unit is multiplied
                 stage_off[wave][slot][entry] = keep ? koff_own : koff_first;
@@ -390,7 +393,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                     w[v] = __builtin_nontemporal_load(
                         reinterpret_cast<const u32x4 *>(chunk + kScaleBytes + (size_t)off[v]));
                 sc_out = *reinterpret_cast<const u32x2 *>(chunk + (size_t)sc_off);
-                n_out = n;
+                n_out = FUSED == 2 ? (n ? kPassCols : 0) : n;
                 g_out = g;
             };
             uint32_t xa = x[pos * kPassCols + lane], xb;
@@ -531,20 +534,25 @@ hipError_t launch(bool dense, int grid, hipStream_t stream, const uint8_t *packe
                   const int32_t *idx, const int32_t *count, float *y, void *partials,
                   int32_t *epochs, int K, int NG, int S, int T, int M) {
     if (dense)
-        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true, BATCH, false>), dim3(grid), dim3(WAVES * 64), 0, stream,
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true, BATCH, 0>), dim3(grid), dim3(WAVES * 64), 0, stream,
                            packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, 0.0f);
     else
-        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, BATCH, false>), dim3(grid), dim3(WAVES * 64), 0, stream,
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, BATCH, 0>), dim3(grid), dim3(WAVES * 64), 0, stream,
                            packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, 0.0f);
     return hipGetLastError();
 }
 
 template <int WAVES>
-hipError_t launch_fused(int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x, float thr,
-                        float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
-    hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                       packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K, NG,
-                       S, T, M, thr);
+hipError_t launch_fused(bool compact, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
+                        float thr, float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
+    if (compact)
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, 1>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                           packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K,
+                           NG, S, T, M, thr);
+    else
+        hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, 2>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                           packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K,
+                           NG, S, T, M, thr);
     return hipGetLastError();
 }
 
@@ -590,16 +598,17 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
     // Measured on MI355X over the benchmark shapes (sweep of S at 50 % sparsity and dense):
     // the fastest launch has about 512 (sparse) / 1024 (dense) workgroups of 4 wavefronts in
     // total, S a power of two and at most 16 - beyond that the fixed cost per wavefront
-    // (prologue loads, pipeline fill, final fold, exchange of partial sums) outweighs the
-    // extra parallelism.  Keep at least a quarter of a quantization group per wavefront.
-    // Four activation rows need so many accumulator registers that only one wavefront fits per
-    // SIMD: keep the whole grid resident at once (256 workgroups of 4 wavefronts).
-    const int64_t target = batch == 4 ? 256 : (sparse ? 512 : 1024);
+    // (prologue loads, pipeline fill, exchange of partial sums) outweighs the extra
+    // parallelism.  Keep at least a quarter of a quantization group per wavefront.
+    // Four activation rows need enough accumulator registers that two wavefronts fit per SIMD
+    // instead of three: 512 workgroups of 4 wavefronts is then the whole chip, once.
+    const int64_t target = batch == 4 ? 512 : (sparse ? 512 : 1024);
     int64_t S = 1;
     while (S * 2 <= 16 && S * 2 * T <= target) S *= 2;
     while (S > 1 && S * waves > 4 * NG) S /= 2;
     out->splits = (int)S;
     out->waves = waves;
+    out->flags = 0;
     return SPQT_OK;
 }
 
@@ -680,14 +689,15 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
     }
     const int T = (int)(M / kTileRows), NG = (int)(K / kGroup);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
+    const bool compact = !(cfg && (cfg->flags & SPQT_CFG_NO_COMPACTION));
     hipStream_t st = (hipStream_t)stream;
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
     switch (c.waves) {
-        case 1: err = launch_fused<1>(grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
-        case 2: err = launch_fused<2>(grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
-        default: err = launch_fused<4>(grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        case 1: err = launch_fused<1>(compact, grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        case 2: err = launch_fused<2>(compact, grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        default: err = launch_fused<4>(compact, grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }

@@ -15,7 +15,7 @@ constexpr int kColBytes = kTileRows / 2;           // one column of one tile: 12
 constexpr int kChunkBytes = SPQT_CHUNK_BYTES;      // kScaleBytes + kGroup * kColBytes
 static_assert(kChunkBytes == kScaleBytes + kGroup * kColBytes, "chunk size");
 
-// Bytes reserved at the head of the workspace for the per-block-row arrival counters.
+// Bytes reserved at the head of the workspace for the per-block-row epoch counters.
 inline size_t counter_bytes(int64_t M) {
     size_t n = (size_t)(M / kTileRows) * sizeof(int32_t);
     return (n + 255) & ~(size_t)255;

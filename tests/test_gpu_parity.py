@@ -246,7 +246,7 @@ def test_batch_rows_share_one_pass(gpu, batch, splits, waves):
     assert_close(gpu_gemv(gpu, w, x, 0.0, dense=True, splits=splits, waves=waves), ref0, "batch dense")
 
 
-def gpu_gemv_fused(gpu, w, x_np, thr, splits=0, waves=0, packed=None):
+def gpu_gemv_fused(gpu, w, x_np, thr, splits=0, waves=0, packed=None, flags=0):
     torch, spqt, dev = gpu
     M, K = w["q_rowmajor"].shape[0], w["q_rowmajor"].shape[1] * 2
     if packed is None:
@@ -254,7 +254,7 @@ def gpu_gemv_fused(gpu, w, x_np, thr, splits=0, waves=0, packed=None):
     x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)[0]
     y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
     ws = spqt.new_workspace(M, K)
-    spqt.spqt_gemv_fused(packed, M, K, x, thr, y, ws, splits=splits, waves=waves)
+    spqt.spqt_gemv_fused(packed, M, K, x, thr, y, ws, splits=splits, waves=waves, flags=flags)
     torch.cuda.synchronize()
     return y.cpu().numpy()[None, :]
 
@@ -292,6 +292,22 @@ def test_fused_clustered_ties_and_exact(gpu):
     for thr in (0.0, 2.0, 3.0):
         ref = oracle.gemv(w["q_rowmajor"], w["scales"], xi, thr)
         assert np.array_equal(gpu_gemv_fused(gpu, w, xi, thr).astype(np.float64), ref), thr
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (1024, 4096), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (7, 2), (16, 4)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_fused_without_compaction(gpu, M, K, splits, waves, sparsity):
+    """The ablation mode (in-kernel test, dropped columns keep their slot with x = 0) computes
+    the same GEMV."""
+    _, spqt, _ = gpu
+    w = make_weights(M, K, 7300 + M + K)
+    x = make_x(K, "laplace_clustered", 7301 + M + K)
+    thr = quantile_threshold(x, sparsity)
+    say(f"fused-nocompact M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    got = gpu_gemv_fused(gpu, w, x, thr, splits=splits, waves=waves, flags=spqt.CFG_NO_COMPACTION)
+    assert_close(got, ref, "fused without compaction")
 
 
 def test_fused_full_size_headline(gpu):

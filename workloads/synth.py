@@ -74,6 +74,14 @@ def _draw(rng: np.random.Generator, dist: str, shape) -> np.ndarray:
         g = rng.standard_normal(shape)
         u = rng.standard_normal(shape)
         v = g / (1.0 + np.exp(-g)) * u            # SiLU(g) * u, a SwiGLU-like hidden state
+    elif dist == "laplace_clustered":
+        # Laplace with a step envelope along the last axis: the first half of the columns is
+        # scaled by 4, the second by 1/4, so at a 50 % threshold about 7 of 8 kept columns sit in
+        # the first half - a pattern that starves half the workers of a static column partition.
+        v = rng.laplace(0.0, 1.0, shape)
+        K = shape[-1]
+        v[..., : K // 2] *= 4.0
+        v[..., K // 2:] *= 0.25
     else:
         raise ValueError(f"unknown distribution {dist!r}")
     return v
