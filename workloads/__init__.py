@@ -16,6 +16,7 @@ from .synth import (  # noqa: F401
     KIND_CALIB,
     seed_for,
     make_weights,
+    make_fp_weights,
     make_x,
     quantile_threshold,
     calibrated_threshold,

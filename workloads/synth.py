@@ -65,6 +65,15 @@ def make_weights(M: int, K: int, seed: int, scale_lo: float = 0.005, scale_hi: f
     return out
 
 
+def make_fp_weights(M: int, K: int, seed: int, std: float = 0.02) -> np.ndarray:
+    """Full-precision weights for the re-quantizing (column-block) path: fp32 N(0, std^2),
+    with every 64th column scaled by 8 so that blocks see a spread of magnitudes."""
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal((M, K)) * std).astype(np.float32)
+    w[:, ::64] *= np.float32(8.0)
+    return np.ascontiguousarray(w)
+
+
 def _draw(rng: np.random.Generator, dist: str, shape) -> np.ndarray:
     if dist == "normal":
         v = rng.standard_normal(shape)
