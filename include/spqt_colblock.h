@@ -1,0 +1,73 @@
+/*
+ * libspqt - column-block variant of the zigzag layout: the quantization groups themselves
+ * run along a column, as in the paper (Section 4.1.2: one superblock is 256 consecutive
+ * rows of ONE column, split like Q4_K into eight blocks of 32 weights, Section 4.1.1;
+ * superblocks are stored row-major by superblock-row), and the model is re-quantized
+ * offline into this form (Section 5).  A skipped activation column then skips its scales
+ * too, and the GEMV needs no per-group bookkeeping: the scale of a block is folded into the
+ * activation value before the multiply.
+ *
+ * Where the paper leaves the encoding open this build keeps what it uses elsewhere:
+ * symmetric int4, fp16 scales (one per 32-row block; 4.5 bits per weight like Q4_K):
+ *
+ *     scale  s = fp16( max|w| over the block / 7 )          fp32 arithmetic, round to nearest even
+ *     code   q = clamp( rint( w / float(s) ), -8, 7 )       fp32, round half to even;
+ *            q = 0 for every weight of a block whose scale rounds to zero
+ *     value  q * float(s)
+ *
+ * Packed form ("ZZ-CB32"): T = M/256 superblock-rows, NC = K/128 chunks of 128 columns;
+ * chunk (t, c) at byte offset (t*NC + c) * 18432:
+ *     bytes [16 j + 2 b], j = 0..127, b = 0..7   fp16 scale (little endian) of rows
+ *                                                256t + 32b .. +31 of column 128c + j
+ *     bytes [2048 + 128 j + i], i = 0..127       column 128c + j: low nibble = code of row
+ *                                                256t + 2i, high nibble = row 256t + 2i + 1,
+ *                                                stored code = q + 8
+ * total = M*K/2 + M*K/16 bytes.  Conventions (status codes, HOST/DEVICE, streams, shapes
+ * M % 256 == 0 and K % 128 == 0) are those of spqt.h.
+ */
+#ifndef SPQT_COLBLOCK_H
+#define SPQT_COLBLOCK_H
+
+#include "spqt.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPQT_CB_BLOCK_ROWS 32
+#define SPQT_CB_CHUNK_BYTES 18432
+
+/* Size in bytes of the packed column-block form of an M x K matrix. */
+int spqt_cb_packed_bytes(int64_t M, int64_t K, size_t *out_bytes);
+
+/* HOST, offline, once per matrix (Section 5: the offline quantizer that emits the zigzag
+ * layout).  Quantizes fp32 weights by the rule above and writes the packed form.
+ *   w_rowmajor   float[M][K], finite values.
+ *   out_packed   caller-owned, out_bytes >= spqt_cb_packed_bytes (else SPQT_ESIZE); fully
+ *                overwritten. */
+int spqt_cb_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_packed, size_t out_bytes);
+
+/* HOST.  The values the packed form stands for: w_out[m][k] = q * float(s), float[M][K]. */
+int spqt_cb_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
+
+/* DEVICE, async.  y[m] = sum over the listed columns k of q[m][k] * s[m/32][k] * x[k], fp32
+ * accumulation, batch 1 (Section 4.2.2 / 4.2.3: same block-row parallelism and even split
+ * of the index list as spqt_gemv).
+ *   packed_dev     device copy of spqt_cb_quantize's output, 128-byte aligned.
+ *   x_dev          fp16[K].
+ *   idx_dev        int32 kept-column list from spqt_gather (ascending), or NULL for the
+ *                  dense kernel, which visits every column and reads neither idx nor count.
+ *   count_dev      int32[1] n_ns on the device (ignored when idx_dev == NULL).
+ *   y_dev          fp32[M], fully overwritten.
+ *   workspace_dev  as for spqt_gemv: >= spqt_workspace_bytes(M, K, 1), prepared once by
+ *                  spqt_workspace_init.
+ *   cfg            launch shape or NULL (flags must be 0).
+ * Deterministic; same bounded wait and NaN-on-give-up behaviour as spqt_gemv. */
+int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+                 const int32_t *count_dev, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                 void *stream, const spqt_launch_cfg *cfg);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPQT_COLBLOCK_H */

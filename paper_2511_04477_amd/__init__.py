@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     LaunchCfg,
     LIB_PATH,
     EXPORTS,
+    CB_EXPORTS,
+    CB_CHUNK_BYTES,
     TILE_ROWS,
     GROUP,
     CHUNK_BYTES,
@@ -25,4 +27,8 @@ from .binding import (  # noqa: F401
     spqt_unpack,
     spqt_workspace_bytes,
     spqt_workspace_init,
+    spqt_cb_packed_bytes,
+    spqt_cb_quantize,
+    spqt_cb_dequantize,
+    spqt_cb_gemv,
 )

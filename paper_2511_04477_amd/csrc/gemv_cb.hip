@@ -1,0 +1,237 @@
+// spqt_cb_gemv: batch-1 GEMV over the column-block variant of the zigzag layout, reading only
+// the kept columns.
+//
+// Paper Section 4.1.2: the quantization groups run along a column (a superblock is 256
+// consecutive rows of one column, in blocks of 32), so a skipped activation entry skips whole
+// superblocks together with their scales; Section 4.2.2: one superblock row = 256 outputs is
+// shared by n1 threadgroups x n2 simdgroups that keep partial sums locally and combine them
+// once; Section 4.2.3: the compacted index list is split evenly over them.
+//
+// Mapping onto gfx950 (wave64), same skeleton as gemv.hip:
+//   - lane (cg, seg) = (lane/8, lane%8) of a step reads bytes [16 seg, 16 seg + 16) of column cg
+//     of the step: the 32 rows of ONE quantization block.  The block's scale is therefore a
+//     per-lane scalar, and it is folded into the activation before the multiply:
+//     acc[row] += n * (x * s * 2^24) with the stored code n taken as an fp16 subnormal.
+//   - a pass is simply the next (up to) 64 entries of the wavefront's slice of the index list:
+//     there is no group structure to respect, no per-group fold, no flush.  The lane that owns
+//     entry l loads x and the 8 scales of its column (one 16-byte load) and stages the 8
+//     products in LDS; a lane picks up the product of its own (column, block) per step.
+//   - the 32 accumulators run through the whole slice; the 8 column-lanes are folded once at
+//     the end, and the offset-binary bias (stored = q + 8) is removed there as -8 * (sum of
+//     x * s of the lane's block over the slice).
+//   - two-stage software pipeline, unpredicated clamped loads, reduction through LDS and the
+//     tagged-word workspace exactly as in gemv.hip.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemv_common.hpp"
+#include "spqt_colblock.h"
+
+namespace {
+
+using namespace spqt;
+
+constexpr int kCbScaleBytes = kGroup * 16;                 // 128 columns x 8 fp16 scales
+constexpr int kCbChunkBytes = SPQT_CB_CHUNK_BYTES;
+static_assert(kCbChunkBytes == kCbScaleBytes + kGroup * kColBytes, "chunk size");
+
+// Sum over the 8 lanes that read the same 32 rows (lanes seg, seg + 8, ..., seg + 56).
+__device__ __forceinline__ float sum_over_columns(float v) {
+    v += dpp_move<0x128>(v);   // row_ror:8 - the lane 8 further inside the row of 16
+    v = fold16(v, v);
+    v = fold32(v, v);
+    return v;
+}
+
+template <int WAVES, bool DENSE>
+__global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
+    const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
+    void *partials, int32_t *epochs, int K, int NC, int S, int T, int M) {
+    __shared__ uint32_t stage_off[WAVES][2][kPassCols];                            // byte offset of each column
+    __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][2][kPassCols][8];  // x * scale * 2^24 per block
+    __shared__ __attribute__((aligned(16))) float red[WAVES][kTileRows];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cg = lane >> 3;
+    const int seg = lane & 7;
+    const int cgr = ((cg & 1) << 2) | (cg & 2) | (cg >> 2);
+    const uint32_t seg16 = (uint32_t)seg * 16u;
+    // all S workgroups of a block-row on one XCD (workgroups go to the 8 XCDs round-robin)
+    const int xcd = blockIdx.x & 7;
+    const int slot_id = blockIdx.x >> 3;
+    const int t = xcd + 8 * (slot_id / S);
+    const int s = slot_id % S;
+    if (t >= T) return;
+    int tag = 0;
+    if (S > 1) tag = __hip_atomic_load(epochs + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+
+    const int n_ns = DENSE ? K : __builtin_amdgcn_readfirstlane(*count);
+    const int parts = S * WAVES;
+    const int part = s * WAVES + wave;
+    int pos = (int)(((int64_t)n_ns * part) / parts);
+    const int end = (int)(((int64_t)n_ns * (part + 1)) / parts);
+
+    const uint8_t *row_base = packed + (size_t)t * NC * kCbChunkBytes;
+
+    float acc[32];      // this lane's 32 rows, summed over its columns of the whole slice
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
+    float bsum = 0.0f;  // sum of the staged products this lane multiplied with (its block)
+
+    if (pos < end) {
+        auto fetch_k = [&](int p) -> int {
+            const int e = p + lane;
+            if (DENSE) return e < end ? e : 0;
+            return idx[e < end ? e : end - 1];
+        };
+
+        // FETCH stage of the pass at list position p (kk = its entries): request the next pass's
+        // entries, this pass's x, scales and weights.  Lanes past the pass point at its first
+        // column and later carry x = 0; past the end of the slice the stage degenerates to n = 0
+        // with harmless re-reads.
+        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, uint32_t &xraw_out,
+                         u32x4 &sv_out, int &k_after) {
+            const int left = end - p;
+            const int n = left < 0 ? 0 : (left < kPassCols ? left : kPassCols);
+            k_after = fetch_k(p + kPassCols);
+            const int k_first = n ? __builtin_amdgcn_readfirstlane(kk) : 0;
+            const int kc = lane < n ? kk : k_first;
+            const uint32_t chunk_off = (uint32_t)(kc >> 7) * (uint32_t)kCbChunkBytes;
+            const uint32_t col = (uint32_t)(kc & (kGroup - 1));
+            xraw_out = x[kc];
+            sv_out = *reinterpret_cast<const u32x4 *>(row_base + (size_t)(chunk_off + col * 16u));
+            stage_off[wave][slot][lane] = chunk_off + (uint32_t)kCbScaleBytes + col * (uint32_t)kColBytes;
+            __builtin_amdgcn_wave_barrier();
+            uint32_t off[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) off[u] = stage_off[wave][slot][u * 8 + cg] + seg16;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row_base + (size_t)off[u]));
+            n_out = n;
+        };
+
+        // MULTIPLY stage of a fetched pass.
+        auto multiply = [&](int n, uint32_t xraw, u32x4 sv, int slot, const u32x4(&w)[8]) {
+            const float xf = lane < n ? half_bits_to_float(xraw) * kTwo24 : 0.0f;
+            f32x4 lo, hi;
+            lo.x = xf * half_bits_to_float(sv.x & 0xFFFFu);
+            lo.y = xf * half_bits_to_float(sv.x >> 16);
+            lo.z = xf * half_bits_to_float(sv.y & 0xFFFFu);
+            lo.w = xf * half_bits_to_float(sv.y >> 16);
+            hi.x = xf * half_bits_to_float(sv.z & 0xFFFFu);
+            hi.y = xf * half_bits_to_float(sv.z >> 16);
+            hi.z = xf * half_bits_to_float(sv.w & 0xFFFFu);
+            hi.w = xf * half_bits_to_float(sv.w >> 16);
+            f32x4 *dst = reinterpret_cast<f32x4 *>(stage_xs[wave][slot][lane]);
+            dst[0] = lo;
+            dst[1] = hi;
+            __builtin_amdgcn_wave_barrier();
+            float xl[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) xl[u] = stage_xs[wave][slot][u * 8 + cg][seg];
+            fma_step<false>(w[0], xl[0], acc);
+            bsum += xl[0];
+#pragma unroll
+            for (int u = 1; u < 8; ++u)
+                if (u * 8 < n) {
+                    fma_step<false>(w[u], xl[u], acc);
+                    bsum += xl[u];
+                }
+            __builtin_amdgcn_wave_barrier();
+        };
+
+        u32x4 wA[8], wB[8], svA, svB;
+        uint32_t xrA, xrB;
+        int nA, nB, kA, kB;
+        kA = fetch_k(pos);
+        fetch(kA, pos, 0, wA, nA, xrA, svA, kB);
+        if (pos + nA >= end) {
+            multiply(nA, xrA, svA, 0, wA);      // the whole slice is one pass
+        } else {
+            for (;;) {
+                const int posB = pos + nA;
+                fetch(kB, posB, 1, wB, nB, xrB, svB, kA);
+                multiply(nA, xrA, svA, 0, wA);
+                if (posB >= end) break;
+                const int posA = posB + nB;
+                fetch(kA, posA, 0, wA, nA, xrA, svA, kB);
+                multiply(nB, xrB, svB, 1, wB);
+                if (posA >= end) break;
+                pos = posA;
+            }
+        }
+    }
+
+    // fold the 8 column-lanes once and remove the bias.  The products are already in true units
+    // (code * 2^-24 times x * s * 2^24); the staged values the bias sums are still scaled by 2^24.
+    float r4[4];
+    fold_columns(acc, r4);
+    const float bias = sum_over_columns(bsum) * (8.0f / kTwo24);
+    reinterpret_cast<f32x4 *>(red[wave])[8 * seg + cgr] =
+        f32x4{r4[0] - bias, r4[1] - bias, r4[2] - bias, r4[3] - bias};
+    __syncthreads();
+    combine_block_row<WAVES, 1>(&red[0][0], tid, t, s, S, tag, partials, epochs, y, M);
+}
+
+template <int WAVES>
+hipError_t launch_cb(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
+                     const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                     int K, int NC, int S, int T, int M) {
+    if (dense)
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true>), dim3(grid), dim3(WAVES * 64), 0, stream, packed, x,
+                           idx, count, y, partials, epochs, K, NC, S, T, M);
+    else
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, stream, packed, x,
+                           idx, count, y, partials, epochs, K, NC, S, T, M);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
+                            const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                            void *workspace_dev, size_t workspace_bytes, void *stream,
+                            const spqt_launch_cfg *cfg) {
+    if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
+    if (idx_dev && !count_dev) return SPQT_EINVAL;
+    if (int rc = check_shape(M, K, kGroup)) return rc;
+    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
+        return SPQT_EALIGN;
+    spqt_launch_cfg c;
+    if (int rc = spqt_default_cfg(M, K, 1, idx_dev != nullptr, &c)) return rc;
+    if (cfg) {
+        if (cfg->flags) return SPQT_EINVAL;
+        if (cfg->splits) c.splits = cfg->splits;
+        if (cfg->waves) c.waves = cfg->waves;
+    }
+    if (c.splits < 1 || c.splits > SPQT_MAX_SPLITS) return SPQT_EINVAL;
+    if (c.waves != 1 && c.waves != 2 && c.waves != 4) return SPQT_EINVAL;
+    size_t need = 0;
+    spqt_workspace_bytes(M, K, 1, &need);
+    void *partials = nullptr;
+    int32_t *epochs = nullptr;
+    if (c.splits > 1) {
+        if (!workspace_dev) return SPQT_EINVAL;
+        if (workspace_bytes < need) return SPQT_ESIZE;
+        if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
+        epochs = (int32_t *)workspace_dev;
+        partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
+    }
+    const int T = (int)(M / kTileRows), NC = (int)(K / kGroup);
+    const int grid = 8 * ((T + 7) / 8) * c.splits;
+    const bool dense = idx_dev == nullptr;
+    hipStream_t st = (hipStream_t)stream;
+    const uint8_t *pk = (const uint8_t *)packed_dev;
+    const uint16_t *xp = (const uint16_t *)x_dev;
+    hipError_t err;
+    switch (c.waves) {
+        case 1: err = launch_cb<1>(dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M); break;
+        case 2: err = launch_cb<2>(dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M); break;
+        default: err = launch_cb<4>(dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M); break;
+    }
+    return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
+}

@@ -1,0 +1,205 @@
+// Device helpers shared by the GEMV kernels (gemv.hip, gemv_cb.hip): the int4 multiply step,
+// the transposing lane folds, wave sums, and the exchange of partial sums between the
+// workgroups of a block-row.  Not part of the C ABI.
+#ifndef SPQT_GEMV_COMMON_HPP
+#define SPQT_GEMV_COMMON_HPP
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spqt_internal.h"
+
+namespace spqt {
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPassCols = 64;                  // most columns one pass covers (8 steps)
+constexpr float kTwo24 = 16777216.0f;          // 2^24: undoes the fp16 subnormal exponent
+constexpr int kMaxPolls = 1 << 18;             // bound on the reducer's wait for one batch of partials
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
+}
+
+// Bit casts go through by-value parameters on purpose: __builtin_bit_cast applied directly
+// to a vector-element expression (v.y, v[i]) reads the vector's first element instead.
+__device__ __forceinline__ float as_float(uint32_t bits) { return __builtin_bit_cast(float, bits); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ f16x2 as_f16x2(uint32_t bits) { return __builtin_bit_cast(f16x2, bits); }
+
+// Eight codes of one dword: acc[i] (+)= n_i * x for nibble i (row 8d+i of the lane's 32 rows).
+// xlo = x * 2^24 pairs with nibbles sitting at bits 0..3 of a half, xhi = x * 2^20 with
+// nibbles at bits 4..7 (value 16 n * 2^-24).  INIT overwrites the accumulators (first step of
+// a pass) instead of adding to them.
+template <bool INIT>
+__device__ __forceinline__ void fma_codes(uint32_t w, float xlo, float xhi, float *acc) {
+    const uint32_t w8 = w >> 8;
+    const f16x2 a = as_f16x2(w & 0x000F000Fu);    // nibbles 0, 4
+    const f16x2 b = as_f16x2(w & 0x00F000F0u);    // nibbles 1, 5
+    const f16x2 c = as_f16x2(w8 & 0x000F000Fu);   // nibbles 2, 6
+    const f16x2 d = as_f16x2(w8 & 0x00F000F0u);   // nibbles 3, 7
+    acc[0] = __builtin_fmaf((float)a.x, xlo, INIT ? 0.0f : acc[0]);
+    acc[4] = __builtin_fmaf((float)a.y, xlo, INIT ? 0.0f : acc[4]);
+    acc[1] = __builtin_fmaf((float)b.x, xhi, INIT ? 0.0f : acc[1]);
+    acc[5] = __builtin_fmaf((float)b.y, xhi, INIT ? 0.0f : acc[5]);
+    acc[2] = __builtin_fmaf((float)c.x, xlo, INIT ? 0.0f : acc[2]);
+    acc[6] = __builtin_fmaf((float)c.y, xlo, INIT ? 0.0f : acc[6]);
+    acc[3] = __builtin_fmaf((float)d.x, xhi, INIT ? 0.0f : acc[3]);
+    acc[7] = __builtin_fmaf((float)d.y, xhi, INIT ? 0.0f : acc[7]);
+}
+
+template <bool INIT>
+__device__ __forceinline__ void fma_step(u32x4 w, float xl, float *acc) {
+    const float xh = xl * 0.0625f;
+    fma_codes<INIT>(w.x, xl, xh, acc + 0);
+    fma_codes<INIT>(w.y, xl, xh, acc + 8);
+    fma_codes<INIT>(w.z, xl, xh, acc + 16);
+    fma_codes<INIT>(w.w, xl, xh, acc + 24);
+}
+
+// The three levels of the column fold are written as asm blocks: the lane swaps work in place
+// on both of their registers (no copies), and the wait states a swap or DPP read needs after a
+// VALU write of its operand are paid once per block instead of once per instruction.
+
+// Level 1, lane pairs (l, l^8) inside every row of 16 lanes: afterwards lanes with bit 3 clear
+// hold a summed over the pair, lanes with bit 3 set hold b summed over the pair - in b's
+// register.  Two bank-masked DPP adds per (a, b).
+#define SPQT_FOLD8(B, A)                                                              \
+    "v_add_f32_dpp " B ", " B ", " B " row_ror:8 row_mask:0xf bank_mask:0xc\n\t"      \
+    "v_add_f32_dpp " B ", " A ", " A " row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+__device__ __forceinline__ void fold8_x8(const float *a, float *b) {
+    asm volatile("s_nop 1\n\t" SPQT_FOLD8("%0", "%8") SPQT_FOLD8("%1", "%9") SPQT_FOLD8("%2", "%10")
+                     SPQT_FOLD8("%3", "%11") SPQT_FOLD8("%4", "%12") SPQT_FOLD8("%5", "%13")
+                         SPQT_FOLD8("%6", "%14") SPQT_FOLD8("%7", "%15")
+                 : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+                 : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]));
+}
+
+// Level 2, lane pairs (l, l^16): v_permlane16_swap exchanges the odd rows of its first operand
+// with the even rows of its second, so a + b afterwards is, in lanes with bit 4 clear, the old a
+// summed over the pair and, in the others, the old b summed over the pair.
+__device__ __forceinline__ void swap16_x8(float *a, float *b) {
+    asm volatile("s_nop 1\n\t"
+                 "v_permlane16_swap_b32 %0, %8\n\tv_permlane16_swap_b32 %1, %9\n\t"
+                 "v_permlane16_swap_b32 %2, %10\n\tv_permlane16_swap_b32 %3, %11\n\t"
+                 "v_permlane16_swap_b32 %4, %12\n\tv_permlane16_swap_b32 %5, %13\n\t"
+                 "v_permlane16_swap_b32 %6, %14\n\tv_permlane16_swap_b32 %7, %15"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
+                   "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7]));
+}
+// Level 3, lane pairs (l, l^32), same idea with the two halves of the wave.
+__device__ __forceinline__ void swap32_x4(float *a, float *b) {
+    asm volatile("s_nop 1\n\t"
+                 "v_permlane32_swap_b32 %0, %4\n\tv_permlane32_swap_b32 %1, %5\n\t"
+                 "v_permlane32_swap_b32 %2, %6\n\tv_permlane32_swap_b32 %3, %7"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]));
+}
+__device__ __forceinline__ float fold16(float a, float b) {
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
+}
+__device__ __forceinline__ float fold32(float a, float b) {
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return a + b;
+}
+
+// Fold the 32 accumulators of the 8 lanes that read the same rows (lanes seg, seg+8, ...,
+// seg+56), halving the number of live values at each of the three levels.  Lane (cg, seg)
+// ends with the complete sums of rows 32 seg + 4 rev(cg) + j, j = 0..3, where rev reverses
+// the three bits of cg (level 1 splits on lane bit 3, level 2 on bit 4, level 3 on bit 5).
+// acc is clobbered.
+__device__ __forceinline__ void fold_columns(float *acc, float *out4) {
+    fold8_x8(acc + 0, acc + 16);      // pairs (i, i+16), i = 0..7   -> acc[16..23]
+    fold8_x8(acc + 8, acc + 24);      // pairs (i, i+16), i = 8..15  -> acc[24..31]
+    swap16_x8(acc + 16, acc + 24);    // pairs (16+i, 24+i)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = acc[16 + i] + acc[24 + i];
+    swap32_x4(acc + 0, acc + 4);      // pairs (i, 4+i)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out4[i] = acc[i] + acc[4 + i];
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return as_float(__builtin_amdgcn_update_dpp(0u, as_u32(v), CTRL, 0xf, 0xf, false));
+}
+
+// Sum over the 64 lanes, returned in every lane: xor-butterfly inside rows of 16 with DPP
+// (quad permutes, half-row and row mirrors), then across rows with the permlane swaps.
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+    v += dpp_move<0x141>(v);   // row_half_mirror: the other quad of the 8
+    v += dpp_move<0x140>(v);   // row_mirror: the other half of the row
+    v = fold16(v, v);
+    v = fold32(v, v);
+    return v;
+}
+
+// Combine the S workgroups of block-row t (paper Section 4.2.2: the partial sums of the
+// threadgroups that share a superblock row are reduced once at the end, without atomics on y).
+// `red` holds this workgroup's [WAVES][BATCH][256] partial sums in LDS (already synchronised).
+// Every workgroup but the last (s == S-1) publishes its 256 partial sums as 64-bit words
+// {value, tag} with device-scope stores and is done: no wait, no counter.  The last one adds
+// the others' words in index order, polling a word until its tag equals this call's tag,
+// then its own sums, and writes y.  The tag is the block-row's epoch + 1; the epoch lives in
+// the workspace, is read by everybody at kernel start and advanced by the reducer at the
+// end, so words left over from earlier calls never match.  A 64-bit store is a single
+// access: value and tag arrive together.  The reducer has the highest index of its block-row
+// and workgroups are dispatched in index order, so everything it waits for is running or
+// finished; the wait is bounded anyway and a give-up poisons y with NaN instead of hanging.
+template <int WAVES, int BATCH>
+__device__ __forceinline__ void combine_block_row(const float *red, int tid, int t, int s, int S, int tag,
+                                                  void *partials, int32_t *epochs, float *__restrict__ y,
+                                                  int M) {
+    constexpr int kOut = BATCH * kTileRows;      // values one workgroup contributes: [BATCH][256]
+    unsigned long long *slots = reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kOut;
+    for (int r = tid; r < kOut; r += WAVES * 64) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2 * kOut + r];
+        float *y_out = y + (size_t)(r / kTileRows) * M + (size_t)t * kTileRows + (r % kTileRows);
+        if (S == 1) {
+            *y_out = sum;
+        } else if (s != S - 1) {
+            const unsigned long long word = ((unsigned long long)(uint32_t)tag << 32) | as_u32(sum);
+            __hip_atomic_store(slots + (size_t)s * kOut + r, word, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            float total = 0.0f;
+            bool gave_up = false;
+            for (int p0 = 0; p0 < S - 1; p0 += 16) {
+                unsigned long long v[16];
+                int polls = 0;
+                bool all_here;
+                do {
+                    // 16 unconditional loads back to back (clamped index), then one check
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int p = p0 + j < S - 1 ? p0 + j : S - 2;
+                        v[j] = __hip_atomic_load(slots + (size_t)p * kOut + r, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    uint32_t missing = 0u;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[j] >> 32) ^ (uint32_t)tag;
+                    all_here = missing == 0u;
+                } while (!all_here && ++polls < kMaxPolls);
+                gave_up = gave_up || !all_here;
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (p0 + j < S - 1) total += as_float((uint32_t)v[j]);
+            }
+            total += sum;
+            *y_out = gave_up ? __builtin_nanf("") : total;
+        }
+    }
+    if (S > 1 && s == S - 1 && tid == 0)
+        __hip_atomic_store(epochs + t, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace spqt
+#endif

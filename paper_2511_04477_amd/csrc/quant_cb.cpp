@@ -1,0 +1,162 @@
+// Host-side quantizer for the column-block variant of the zigzag layout.
+//
+// Paper Section 4.1.2: the quantization groups run along a column (a superblock is 256
+// consecutive rows of one column, in blocks of 32 as in Section 4.1.1) and superblocks are
+// stored row-major by superblock-row; Section 5: the model is converted offline.  The rule
+// (symmetric int4, one fp16 scale per 32-row block) and the byte layout are documented in
+// spqt_colblock.h.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "spqt_colblock.h"
+#include "spqt_internal.h"
+
+using namespace spqt;
+
+namespace {
+
+constexpr int kBlockRows = SPQT_CB_BLOCK_ROWS;
+constexpr int kBlocksPerTile = kTileRows / kBlockRows;           // 8
+constexpr int kCbScaleBytes = kGroup * kBlocksPerTile * 2;       // 2048
+constexpr int kCbChunkBytes = SPQT_CB_CHUNK_BYTES;
+static_assert(kCbChunkBytes == kCbScaleBytes + kGroup * kColBytes, "chunk size");
+
+// fp32 -> fp16 bits, round to nearest even (finite inputs; overflow gives infinity).
+uint16_t float_to_half_bits(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    const uint32_t sign = (u >> 16) & 0x8000u;
+    const uint32_t a = u & 0x7FFFFFFFu;
+    if (a >= 0x47800000u) return (uint16_t)(sign | 0x7C00u);      // >= 65536 (or inf/nan): infinity
+    if (a < 0x38800000u) {                                        // below the smallest normal half
+        if (a < 0x33000000u) return (uint16_t)sign;               // < 2^-25: zero
+        const int shift = 126 - (int)(a >> 23);                   // 14..24
+        const uint32_t mant = (a & 0x7FFFFFu) | 0x800000u;
+        const uint32_t q = mant >> shift, rem = mant & ((1u << shift) - 1u), half = 1u << (shift - 1);
+        return (uint16_t)(sign | (q + ((rem > half || (rem == half && (q & 1u))) ? 1u : 0u)));
+    }
+    const uint32_t q = (a - 0x38000000u) >> 13, rem = a & 0x1FFFu;
+    const uint32_t r = q + ((rem > 0x1000u || (rem == 0x1000u && (q & 1u))) ? 1u : 0u);
+    return (uint16_t)(sign | r);                                  // a carry into the exponent is correct
+}
+
+float half_bits_to_float(uint16_t h) {
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    const uint32_t e = (h >> 10) & 0x1Fu, m = h & 0x3FFu;
+    uint32_t u;
+    if (e == 0) {
+        if (m == 0) {
+            u = sign;
+        } else {
+            const float v = (float)m * (1.0f / 16777216.0f);      // m * 2^-24, exact
+            std::memcpy(&u, &v, 4);
+            u |= sign;
+        }
+    } else if (e == 31) {
+        u = sign | 0x7F800000u | (m << 13);
+    } else {
+        u = sign | ((e + 112u) << 23) | (m << 13);
+    }
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+template <class F>
+void for_each_tile_row(int64_t T, F fn) {
+    unsigned hw = std::thread::hardware_concurrency();
+    int nthreads = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<unsigned>(hw ? hw : 1, 16u), T));
+    if (nthreads == 1) {
+        for (int64_t t = 0; t < T; ++t) fn(t);
+        return;
+    }
+    std::vector<std::thread> pool;
+    for (int w = 0; w < nthreads; ++w)
+        pool.emplace_back([=]() {
+            for (int64_t t = w; t < T; t += nthreads) fn(t);
+        });
+    for (auto &th : pool) th.join();
+}
+
+int check_cb_shape(int64_t M, int64_t K) { return check_shape(M, K, kGroup); }
+
+}  // namespace
+
+extern "C" int spqt_cb_packed_bytes(int64_t M, int64_t K, size_t *out_bytes) {
+    if (!out_bytes) return SPQT_EINVAL;
+    if (int rc = check_cb_shape(M, K)) return rc;
+    *out_bytes = (size_t)(M / kTileRows) * (size_t)(K / kGroup) * (size_t)kCbChunkBytes;
+    return SPQT_OK;
+}
+
+extern "C" int spqt_cb_quantize(const float *w, int64_t M, int64_t K, void *out_packed, size_t out_bytes) {
+    if (!w || !out_packed) return SPQT_EINVAL;
+    size_t need = 0;
+    if (int rc = spqt_cb_packed_bytes(M, K, &need)) return rc;
+    if (out_bytes < need) return SPQT_ESIZE;
+    const int64_t T = M / kTileRows, NC = K / kGroup;
+    uint8_t *out = (uint8_t *)out_packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        float scale[kBlocksPerTile][kGroup];
+        for (int64_t c = 0; c < NC; ++c) {
+            uint8_t *chunk = out + (size_t)(t * NC + c) * kCbChunkBytes;
+            const float *tile = w + (size_t)t * kTileRows * K + (size_t)c * kGroup;   // row stride K
+            for (int b = 0; b < kBlocksPerTile; ++b) {
+                float amax[kGroup];
+                for (int j = 0; j < kGroup; ++j) amax[j] = 0.0f;
+                for (int r = 0; r < kBlockRows; ++r) {
+                    const float *row = tile + (size_t)(b * kBlockRows + r) * K;
+                    for (int j = 0; j < kGroup; ++j) amax[j] = std::max(amax[j], std::fabs(row[j]));
+                }
+                for (int j = 0; j < kGroup; ++j) {
+                    const uint16_t h = float_to_half_bits(amax[j] / 7.0f);
+                    chunk[16 * j + 2 * b] = (uint8_t)(h & 0xFF);
+                    chunk[16 * j + 2 * b + 1] = (uint8_t)(h >> 8);
+                    scale[b][j] = half_bits_to_float(h);
+                }
+            }
+            uint8_t *codes = chunk + kCbScaleBytes;
+            for (int r = 0; r < kTileRows; ++r) {
+                const float *row = tile + (size_t)r * K;
+                const float *sc = scale[r / kBlockRows];
+                for (int j = 0; j < kGroup; ++j) {
+                    int q = 0;
+                    if (sc[j] > 0.0f) {
+                        const float v = std::nearbyintf(row[j] / sc[j]);   // round half to even
+                        q = (int)std::min(7.0f, std::max(-8.0f, v));
+                    }
+                    uint8_t &byte = codes[128 * j + r / 2];
+                    const uint8_t n = (uint8_t)(q + 8);
+                    byte = (r & 1) ? (uint8_t)((byte & 0x0F) | (n << 4)) : n;   // even row first: overwrites
+                }
+            }
+        }
+    });
+    return SPQT_OK;
+}
+
+extern "C" int spqt_cb_dequantize(const void *packed, int64_t M, int64_t K, float *w_out) {
+    if (!packed || !w_out) return SPQT_EINVAL;
+    if (int rc = check_cb_shape(M, K)) return rc;
+    const int64_t T = M / kTileRows, NC = K / kGroup;
+    const uint8_t *in = (const uint8_t *)packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        for (int64_t c = 0; c < NC; ++c) {
+            const uint8_t *chunk = in + (size_t)(t * NC + c) * kCbChunkBytes;
+            float *tile = w_out + (size_t)t * kTileRows * K + (size_t)c * kGroup;
+            for (int j = 0; j < kGroup; ++j) {
+                for (int r = 0; r < kTileRows; ++r) {
+                    const int b = r / kBlockRows;
+                    const uint16_t h = (uint16_t)(chunk[16 * j + 2 * b] | (chunk[16 * j + 2 * b + 1] << 8));
+                    const uint8_t byte = chunk[kCbScaleBytes + 128 * j + r / 2];
+                    const int q = (int)((byte >> (4 * (r & 1))) & 15) - 8;
+                    tile[(size_t)r * K + j] = (float)q * half_bits_to_float(h);
+                }
+            }
+        }
+    });
+    return SPQT_OK;
+}

@@ -1,0 +1,149 @@
+"""GPU parity of the column-block GEMV (spqt_cb_gemv, through the C ABI) against the NumPy oracle
+oracle/colblock.py on the same seeded inputs.  The packed bytes come from the library's host
+quantizer, which the CPU tests pin bit for bit to the oracle's; outputs must satisfy
+|y_gpu - y_ref| <= 1e-2 + 2e-3 * |y_ref| elementwise (fp32 accumulation vs the fp64 oracle)."""
+import numpy as np
+import pytest
+
+from oracle import colblock as cb
+from workloads import make_fp_weights, make_x, quantile_threshold
+
+pytestmark = pytest.mark.gpu
+
+ATOL, RTOL = 1e-2, 2e-3
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2511_04477_amd as spqt
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    spqt.lib()
+    return torch, spqt, torch.device("cuda:0")
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def assert_close(got, ref, what):
+    err = np.abs(got.astype(np.float64) - ref)
+    bad = err > ATOL + RTOL * np.abs(ref)
+    assert not bad.any(), f"{what}: {int(bad.sum())} outputs off, max err {err.max():.3e}"
+
+
+def gpu_cb_gemv(gpu, W, x_np, thr, dense=False, splits=0, waves=0, packed=None):
+    torch, spqt, dev = gpu
+    M, K = W.shape
+    if packed is None:
+        packed = torch.from_numpy(spqt.spqt_cb_quantize(W)).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)[0]
+    y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K)
+    if dense:
+        spqt.spqt_cb_gemv(packed, M, K, x, None, None, y, ws, splits=splits, waves=waves)
+    else:
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        spqt.spqt_cb_gemv(packed, M, K, x, idx, cnt, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()[None, :]
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 1024), (1024, 4096), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (2, 4), (7, 2), (16, 4), (64, 1)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_cb_sparse_gemv(gpu, M, K, splits, waves, sparsity):
+    W = make_fp_weights(M, K, 8100 + M + K)
+    x = make_x(K, "laplace", 8101 + M + K)
+    thr = quantile_threshold(x, sparsity)
+    say(f"cb M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    q, s = cb.quantize(W)
+    ref = cb.gemv(q, s, x, thr)
+    assert_close(gpu_cb_gemv(gpu, W, x, thr, splits=splits, waves=waves), ref, "cb sparse")
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (1024, 2048), (768, 640)])
+def test_cb_dense_kernel_and_threshold_zero(gpu, M, K):
+    W = make_fp_weights(M, K, 8200 + M + K)
+    x = make_x(K, "normal", 8201 + M + K)
+    q, s = cb.quantize(W)
+    ref = cb.gemv(q, s, x, 0.0)
+    for splits, waves in [(0, 0), (1, 4), (5, 2)]:
+        say(f"cb dense M={M} K={K} {splits}x{waves}")
+        d = gpu_cb_gemv(gpu, W, x, 0.0, dense=True, splits=splits, waves=waves)
+        z = gpu_cb_gemv(gpu, W, x, 0.0, dense=False, splits=splits, waves=waves)
+        assert_close(d, ref, "cb dense")
+        assert np.array_equal(d, z), "index-free kernel and threshold 0 must agree bit for bit"
+
+
+def test_cb_exact_arithmetic_is_bit_exact(gpu):
+    """Power-of-two scales, codes that hit them exactly, small integer x: every product and
+    partial sum is representable, so any summation order gives the oracle's result exactly."""
+    M, K = 512, 1024
+    rng = np.random.default_rng(8300)
+    q0 = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    q0.reshape(M // 32, 32, K)[:, 0, :] = 7
+    s0 = (2.0 ** rng.integers(-8, -3, size=(M // 32, K))).astype(np.float32)
+    W = q0.astype(np.float32) * np.repeat(s0, 32, axis=0)
+    x = rng.integers(-4, 5, size=(1, K)).astype(np.float16)
+    q, s = cb.quantize(W)
+    assert np.array_equal(q, q0)
+    ref = cb.gemv(q, s, x, 2.0)
+    for splits, waves in [(0, 0), (3, 4), (16, 1)]:
+        got = gpu_cb_gemv(gpu, W, x, 2.0, splits=splits, waves=waves)
+        assert np.array_equal(got.astype(np.float64), ref), f"{splits}x{waves}"
+
+
+def test_cb_column_probe(gpu):
+    """x = c e_k reads exactly column k: y = c * dequant(W)[:, k] - any address mix-up shows."""
+    torch, spqt, dev = gpu
+    M, K = 512, 384
+    W = make_fp_weights(M, K, 8400)
+    q, s = cb.quantize(W)
+    Wd = cb.dequant(q, s)
+    packed = torch.from_numpy(spqt.spqt_cb_quantize(W)).to(dev)
+    for k in list(range(0, K, 7)) + [K - 1]:
+        e = np.zeros((1, K), dtype=np.float16)
+        e[0, k] = -1.5
+        got = gpu_cb_gemv(gpu, W, e, 0.5, packed=packed)[0].astype(np.float64)
+        want = (-1.5 * Wd[:, k]).astype(np.float32).astype(np.float64)
+        assert np.array_equal(got, want), k
+
+
+def test_cb_clustered_and_reproducible(gpu):
+    M, K = 1024, 2048
+    W = make_fp_weights(M, K, 8500)
+    x = make_x(K, "laplace_clustered", 8501)
+    x[0, 0:300] = 0
+    x[0, 1000] = 0.75            # a tie with the threshold is kept
+    thr = 0.75
+    q, s = cb.quantize(W)
+    ref = cb.gemv(q, s, x, thr)
+    first = None
+    for rep in range(10):
+        got = gpu_cb_gemv(gpu, W, x, thr)
+        assert_close(got, ref, "cb clustered")
+        first = got if first is None else first
+        assert np.array_equal(got, first), "results must be reproducible"
+
+
+def test_cb_full_size_sampled_rows(gpu):
+    """The benchmark's shapes in the default launch configuration, checked on sampled 256-row
+    tiles (the oracle computes any subset of tiles independently)."""
+    torch, spqt, dev = gpu
+    for M, K in [(4096, 4096), (28672, 8192), (8192, 28672)]:
+        say(f"cb full size {M}x{K}")
+        W = make_fp_weights(M, K, 8600 + M)
+        x = make_x(K, "laplace", 8601 + M)
+        thr = quantile_threshold(x, 0.5)
+        got = gpu_cb_gemv(gpu, W, x, thr)[0]
+        gotd = gpu_cb_gemv(gpu, W, x, thr, dense=True)[0]
+        rng = np.random.default_rng(M)
+        tiles = np.unique(np.concatenate([[0, M // 256 - 1], rng.integers(0, M // 256, size=3)]))
+        rows = (tiles[:, None] * 256 + np.arange(256)[None, :]).ravel()
+        q, s = cb.quantize(W[rows])           # blocks are quantized independently of each other
+        assert_close(got[rows][None, :], cb.gemv(q, s, x, thr), f"cb {M}x{K} sparse")
+        assert_close(gotd[rows][None, :], cb.gemv(q, s, x, 0.0), f"cb {M}x{K} dense")
+        del W

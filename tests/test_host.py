@@ -41,6 +41,49 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, n) is not None
 
 
+def test_colblock_header_symbols_are_exported():
+    L = spqt.lib()
+    names = [n for n in declared_functions("spqt_colblock.h") if n.startswith("spqt_cb_")]
+    assert set(names) == set(spqt.CB_EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 384), (1024, 1024)])
+def test_colblock_quantizer_matches_oracle_bit_exact(M, K):
+    """The library's offline quantizer and the oracle's (independent NumPy code, same fp32 rule)
+    must agree on every scale bit and every code, and on the packed bytes."""
+    from oracle import colblock as cb
+    from workloads import make_fp_weights
+    W = make_fp_weights(M, K, 500 + M + K)
+    W[0:32, 3] = 0.0                      # an all-zero block
+    W[32:64, 7] = np.float32(1e-9)        # a block whose scale underflows to zero
+    W[64:96, 11] = [(-1) ** r * 0.5 * (r % 15) for r in range(32)]   # exact ties: amax = 7, scale = 1
+    got = spqt.spqt_cb_quantize(W)
+    q, s = cb.quantize(W)
+    want = cb.pack(q, s)
+    assert got.nbytes == want.nbytes == spqt.spqt_cb_packed_bytes(M, K) == cb.packed_bytes(M, K)
+    assert np.array_equal(got, want)
+    back = spqt.spqt_cb_dequantize(got, M, K)
+    assert np.array_equal(back.astype(np.float64), cb.dequant(q, s))
+
+
+def test_colblock_bad_arguments():
+    L = spqt.lib()
+    out = ctypes.c_size_t()
+    assert L.spqt_cb_packed_bytes(255, 128, ctypes.byref(out)) == -2
+    assert L.spqt_cb_packed_bytes(256, 128, None) == -1
+    w = np.zeros((256, 128), dtype=np.float32)
+    small = np.zeros(16, dtype=np.uint8)
+    vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    assert L.spqt_cb_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
+    assert L.spqt_cb_quantize(None, 256, 128, vp(small), small.nbytes) == -1
+    assert L.spqt_cb_gemv(None, 256, 128, 16, None, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cb_gemv(128, 100, 128, 16, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb_gemv(64, 256, 128, 16, None, None, 16, None, 0, None, None) == -3
+    assert L.spqt_cb_gemv(128, 256, 128, 16, 16, None, 16, None, 0, None, None) == -1
+
+
 def test_status_strings():
     assert spqt.spqt_status_str(0) == "SPQT_OK"
     for code in (-1, -2, -3, -4, -5):
