@@ -67,6 +67,14 @@ int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev
                  const int32_t *count_dev, float *y_dev, void *workspace_dev, size_t workspace_bytes,
                  void *stream, const spqt_launch_cfg *cfg);
 
+/* DEVICE, async.  Gather and GEMV in ONE launch (the column-block counterpart of
+ * spqt_gemv_fused): the kernel applies the sparsity test of Section 2 to x itself on static
+ * 64-column ranges, compacts the kept columns with a wavefront ballot and multiplies; no index
+ * list exists.  Same y as spqt_gather followed by spqt_cb_gemv up to summation order. */
+int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, float threshold,
+                       float *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
+                       const spqt_launch_cfg *cfg);
+
 #ifdef __cplusplus
 }
 #endif

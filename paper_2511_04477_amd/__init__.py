@@ -31,4 +31,5 @@ from .binding import (  # noqa: F401
     spqt_cb_quantize,
     spqt_cb_dequantize,
     spqt_cb_gemv,
+    spqt_cb_gemv_fused,
 )

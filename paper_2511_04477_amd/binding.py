@@ -29,7 +29,8 @@ EXPORTS = [
 ]
 
 
-CB_EXPORTS = ["spqt_cb_packed_bytes", "spqt_cb_quantize", "spqt_cb_dequantize", "spqt_cb_gemv"]
+CB_EXPORTS = ["spqt_cb_packed_bytes", "spqt_cb_quantize", "spqt_cb_dequantize", "spqt_cb_gemv",
+              "spqt_cb_gemv_fused"]
 CB_CHUNK_BYTES = 18432
 
 
@@ -71,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.spqt_cb_quantize.argtypes = [vp, i64, i64, vp, sz]
         L.spqt_cb_dequantize.argtypes = [vp, i64, i64, vp]
         L.spqt_cb_gemv.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cb_gemv_fused.argtypes = [vp, i64, i64, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         for name in EXPORTS[1:] + CB_EXPORTS:
             getattr(L, name).restype = i32
         _lib = L
@@ -269,3 +271,20 @@ def spqt_cb_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=Non
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
     cfg = LaunchCfg(int(splits), int(waves), 0)
     _check(lib().spqt_cb_gemv(pp, M, K, xp, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
+
+
+def spqt_cb_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, stream=None,
+                       splits: int = 0, waves: int = 0) -> None:
+    """Threshold + compaction + column-block GEMV in one launch (batch 1)."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp = _dev(y, torch.float32, "y")
+    if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb_packed_bytes(M, K):
+        raise SpqtError("spqt_cb_gemv_fused: x / y / packed sizes do not match M, K (batch 1 only)")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    cfg = LaunchCfg(int(splits), int(waves), 0)
+    _check(lib().spqt_cb_gemv_fused(pp, M, K, xp, float(threshold), yp, wp, wbytes, _stream_ptr(stream),
+                                    ctypes.byref(cfg)))

@@ -43,11 +43,15 @@ __device__ __forceinline__ float sum_over_columns(float v) {
     return v;
 }
 
-template <int WAVES, bool DENSE>
+// FUSED: the kernel applies the sparsity test itself instead of reading an index list (as
+// spqt_gemv_fused does for the group layout): a wavefront's slice is a static range of
+// 64-column units; lane l tests column 64u + l, a ballot gives the kept set, mbcnt the rank,
+// and the kept columns are staged in rank order.
+template <int WAVES, bool DENSE, bool FUSED>
 __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    void *partials, int32_t *epochs, int K, int NC, int S, int T, int M) {
+    void *partials, int32_t *epochs, int K, int NC, int S, int T, int M, float thr) {
     __shared__ uint32_t stage_off[WAVES][2][kPassCols];                            // byte offset of each column
     __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][2][kPassCols][8];  // x * scale * 2^24 per block
     __shared__ __attribute__((aligned(16))) float red[WAVES][kTileRows];
@@ -68,7 +72,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     int tag = 0;
     if (S > 1) tag = __hip_atomic_load(epochs + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
 
-    const int n_ns = DENSE ? K : __builtin_amdgcn_readfirstlane(*count);
+    const int n_ns = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));
     const int parts = S * WAVES;
     const int part = s * WAVES + wave;
     int pos = (int)(((int64_t)n_ns * part) / parts);
@@ -114,9 +118,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
             n_out = n;
         };
 
-        // MULTIPLY stage of a fetched pass.
-        auto multiply = [&](int n, uint32_t xraw, u32x4 sv, int slot, const u32x4(&w)[8]) {
-            const float xf = lane < n ? half_bits_to_float(xraw) * kTwo24 : 0.0f;
+        // MULTIPLY stage of a fetched pass: the lane that owns list entry `ent` stages the 8
+        // products x * s_b * 2^24 of its column (xf = x * 2^24, or 0 for a filler entry).
+        auto multiply = [&](int n, float xf, int ent, u32x4 sv, int slot, const u32x4(&w)[8]) {
             f32x4 lo, hi;
             lo.x = xf * half_bits_to_float(sv.x & 0xFFFFu);
             lo.y = xf * half_bits_to_float(sv.x >> 16);
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
             hi.y = xf * half_bits_to_float(sv.z >> 16);
             hi.z = xf * half_bits_to_float(sv.w & 0xFFFFu);
             hi.w = xf * half_bits_to_float(sv.w >> 16);
-            f32x4 *dst = reinterpret_cast<f32x4 *>(stage_xs[wave][slot][lane]);
+            f32x4 *dst = reinterpret_cast<f32x4 *>(stage_xs[wave][slot][ent]);
             dst[0] = lo;
             dst[1] = hi;
             __builtin_amdgcn_wave_barrier();
@@ -143,25 +147,84 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
                 }
             __builtin_amdgcn_wave_barrier();
         };
+        auto multiply_list = [&](int n, uint32_t xraw, u32x4 sv, int slot, const u32x4(&w)[8]) {
+            multiply(n, lane < n ? half_bits_to_float(xraw) * kTwo24 : 0.0f, lane, sv, slot, w);
+        };
 
         u32x4 wA[8], wB[8], svA, svB;
-        uint32_t xrA, xrB;
-        int nA, nB, kA, kB;
-        kA = fetch_k(pos);
-        fetch(kA, pos, 0, wA, nA, xrA, svA, kB);
-        if (pos + nA >= end) {
-            multiply(nA, xrA, svA, 0, wA);      // the whole slice is one pass
-        } else {
+        int nA, nB;
+        if (FUSED) {
+            // FETCH stage of unit u (xr = this lane's x[64u + lane], requested one stage earlier):
+            // threshold, rank, stage the offsets, request the next unit's x, this unit's scales
+            // (every lane its own column's) and weights.
+            auto fetch_unit = [&](uint32_t xr, int u, int slot, u32x4(&w)[8], int &n_out, float &xf_out,
+                                  int &ent_out, u32x4 &sv_out, uint32_t &xr_next) {
+                const bool any = u < end;
+                const float xv = half_bits_to_float(xr);
+                const bool keep = any && !(__builtin_fabsf(xv) < thr);
+                const uint64_t mask = __ballot(keep);
+                const int n = __builtin_amdgcn_readfirstlane((int)__popcll(mask));
+                const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                {
+                    const int c = (u + 1) * kPassCols + lane;
+                    xr_next = x[c < K ? c : K - 1];
+                }
+                const int uu = any ? u : 0;
+                const uint32_t chunk_off = (uint32_t)(uu >> 1) * (uint32_t)kCbChunkBytes;
+                const uint32_t col_own = (uint32_t)((uu & 1) * kPassCols + lane);
+                const uint32_t col_first = (uint32_t)((uu & 1) * kPassCols + (n ? (int)__builtin_ctzll(mask) : 0));
+                sv_out = *reinterpret_cast<const u32x4 *>(row_base + (size_t)(chunk_off + col_own * 16u));
+                // kept columns go to entries 0..n-1 in ascending order; the other lanes fill entries
+                // n..63 with the unit's first kept column and x = 0
+                const int entry = keep ? rank : n + lane - rank;
+                stage_off[wave][slot][entry] =
+                    chunk_off + (uint32_t)kCbScaleBytes + (keep ? col_own : col_first) * (uint32_t)kColBytes;
+                __builtin_amdgcn_wave_barrier();
+                uint32_t off[8];
+#pragma unroll
+                for (int v = 0; v < 8; ++v) off[v] = stage_off[wave][slot][v * 8 + cg] + seg16;
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    w[v] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row_base + (size_t)off[v]));
+                n_out = n;
+                xf_out = keep ? xv * kTwo24 : 0.0f;
+                ent_out = entry;
+            };
+            float xfA, xfB;
+            int entA, entB;
+            uint32_t xa = x[pos * kPassCols + lane], xb;
+            fetch_unit(xa, pos, 0, wA, nA, xfA, entA, svA, xb);
             for (;;) {
-                const int posB = pos + nA;
-                fetch(kB, posB, 1, wB, nB, xrB, svB, kA);
-                multiply(nA, xrA, svA, 0, wA);
-                if (posB >= end) break;
-                const int posA = posB + nB;
-                fetch(kA, posA, 0, wA, nA, xrA, svA, kB);
-                multiply(nB, xrB, svB, 1, wB);
-                if (posA >= end) break;
-                pos = posA;
+                const int uB = pos + 1;
+                fetch_unit(xb, uB, 1, wB, nB, xfB, entB, svB, xa);
+                if (nA > 0) multiply(nA, xfA, entA, svA, 0, wA);
+                if (uB >= end) break;
+                const int uA = uB + 1;
+                fetch_unit(xa, uA, 0, wA, nA, xfA, entA, svA, xb);
+                if (nB > 0) multiply(nB, xfB, entB, svB, 1, wB);
+                if (uA >= end) break;
+                pos = uA;
+            }
+        } else {
+            uint32_t xrA, xrB;
+            int kA, kB;
+            kA = fetch_k(pos);
+            fetch(kA, pos, 0, wA, nA, xrA, svA, kB);
+            if (pos + nA >= end) {
+                multiply_list(nA, xrA, svA, 0, wA);      // the whole slice is one pass
+            } else {
+                for (;;) {
+                    const int posB = pos + nA;
+                    fetch(kB, posB, 1, wB, nB, xrB, svB, kA);
+                    multiply_list(nA, xrA, svA, 0, wA);
+                    if (posB >= end) break;
+                    const int posA = posB + nB;
+                    fetch(kA, posA, 0, wA, nA, xrA, svA, kB);
+                    multiply_list(nB, xrB, svB, 1, wB);
+                    if (posA >= end) break;
+                    pos = posA;
+                }
             }
         }
     }
@@ -178,31 +241,31 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
 }
 
 template <int WAVES>
-hipError_t launch_cb(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
+hipError_t launch_cb(int mode, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                      const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
-                     int K, int NC, int S, int T, int M) {
-    if (dense)
-        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true>), dim3(grid), dim3(WAVES * 64), 0, stream, packed, x,
-                           idx, count, y, partials, epochs, K, NC, S, T, M);
-    else
-        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, stream, packed, x,
-                           idx, count, y, partials, epochs, K, NC, S, T, M);
+                     int K, int NC, int S, int T, int M, float thr) {
+    const dim3 g(grid), b(WAVES * 64);
+    if (mode == 0)        // index list
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false>), g, b, 0, stream, packed, x, idx, count, y,
+                           partials, epochs, K, NC, S, T, M, thr);
+    else if (mode == 1)   // dense
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false>), g, b, 0, stream, packed, x, idx, count, y,
+                           partials, epochs, K, NC, S, T, M, thr);
+    else                  // threshold inside the kernel
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true>), g, b, 0, stream, packed, x, idx, count, y,
+                           partials, epochs, K, NC, S, T, M, thr);
     return hipGetLastError();
 }
 
-}  // namespace
-
-extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
-                            const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
-                            void *workspace_dev, size_t workspace_bytes, void *stream,
-                            const spqt_launch_cfg *cfg) {
+int run_cb(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+           const int32_t *count_dev, float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+           void *stream, const spqt_launch_cfg *cfg) {
     if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
-    if (idx_dev && !count_dev) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
         return SPQT_EALIGN;
     spqt_launch_cfg c;
-    if (int rc = spqt_default_cfg(M, K, 1, idx_dev != nullptr, &c)) return rc;
+    if (int rc = spqt_default_cfg(M, K, 1, mode != 1, &c)) return rc;
     if (cfg) {
         if (cfg->flags) return SPQT_EINVAL;
         if (cfg->splits) c.splits = cfg->splits;
@@ -223,15 +286,33 @@ extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const 
     }
     const int T = (int)(M / kTileRows), NC = (int)(K / kGroup);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
-    const bool dense = idx_dev == nullptr;
     hipStream_t st = (hipStream_t)stream;
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
     switch (c.waves) {
-        case 1: err = launch_cb<1>(dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M); break;
-        case 2: err = launch_cb<2>(dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M); break;
-        default: err = launch_cb<4>(dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M); break;
+        case 1: err = launch_cb<1>(mode, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
+        case 2: err = launch_cb<2>(mode, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
+        default: err = launch_cb<4>(mode, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
+}
+
+}  // namespace
+
+extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
+                            const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                            void *workspace_dev, size_t workspace_bytes, void *stream,
+                            const spqt_launch_cfg *cfg) {
+    if (idx_dev && !count_dev) return SPQT_EINVAL;
+    return run_cb(idx_dev ? 0 : 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
+                  workspace_bytes, stream, cfg);
+}
+
+extern "C" int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
+                                  float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                                  void *stream, const spqt_launch_cfg *cfg) {
+    if (threshold != threshold) return SPQT_EINVAL;
+    return run_cb(2, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev,
+                  workspace_bytes, stream, cfg);
 }

@@ -64,6 +64,57 @@ def test_cb_sparse_gemv(gpu, M, K, splits, waves, sparsity):
     assert_close(gpu_cb_gemv(gpu, W, x, thr, splits=splits, waves=waves), ref, "cb sparse")
 
 
+def gpu_cb_gemv_fused(gpu, W, x_np, thr, splits=0, waves=0, packed=None):
+    torch, spqt, dev = gpu
+    M, K = W.shape
+    if packed is None:
+        packed = torch.from_numpy(spqt.spqt_cb_quantize(W)).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)[0]
+    y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K)
+    spqt.spqt_cb_gemv_fused(packed, M, K, x, thr, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()[None, :]
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 1024), (1024, 4096), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (2, 4), (7, 2), (16, 4), (64, 1)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_cb_fused_gemv(gpu, M, K, splits, waves, sparsity):
+    """One launch: threshold, in-wave compaction and the column-block GEMV."""
+    W = make_fp_weights(M, K, 8700 + M + K)
+    x = make_x(K, "laplace_clustered" if sparsity == 0.9 else "laplace", 8701 + M + K)
+    thr = quantile_threshold(x, sparsity)
+    say(f"cb fused M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    q, s = cb.quantize(W)
+    ref = cb.gemv(q, s, x, thr)
+    assert_close(gpu_cb_gemv_fused(gpu, W, x, thr, splits=splits, waves=waves), ref, "cb fused")
+
+
+def test_cb_fused_ties_empty_units_and_exact(gpu):
+    M, K = 1024, 2048
+    W = make_fp_weights(M, K, 8800)
+    x = make_x(K, "laplace", 8801)
+    x[0, 0:512] = 0            # empty 64-column units
+    x[0, 700] = 3.0
+    x[0, 1024:1152] = 2.0      # two full units
+    x[0, 1500] = 0.75          # a tie with the threshold is kept
+    thr = 0.75
+    q, s = cb.quantize(W)
+    ref = cb.gemv(q, s, x, thr)
+    for splits, waves in [(0, 0), (1, 1), (5, 4), (16, 2)]:
+        assert_close(gpu_cb_gemv_fused(gpu, W, x, thr, splits=splits, waves=waves), ref, f"cb fused {splits}x{waves}")
+    rng = np.random.default_rng(8802)
+    q0 = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    q0.reshape(M // 32, 32, K)[:, 0, :] = 7
+    s0 = (2.0 ** rng.integers(-8, -3, size=(M // 32, K))).astype(np.float32)
+    We = q0.astype(np.float32) * np.repeat(s0, 32, axis=0)
+    xi = rng.integers(-4, 5, size=(1, K)).astype(np.float16)
+    qe, se = cb.quantize(We)
+    got = gpu_cb_gemv_fused(gpu, We, xi, 2.0)
+    assert np.array_equal(got.astype(np.float64), cb.gemv(qe, se, xi, 2.0))
+
+
 @pytest.mark.parametrize("M,K", [(256, 128), (1024, 2048), (768, 640)])
 def test_cb_dense_kernel_and_threshold_zero(gpu, M, K):
     W = make_fp_weights(M, K, 8200 + M + K)
@@ -138,12 +189,16 @@ def test_cb_full_size_sampled_rows(gpu):
         W = make_fp_weights(M, K, 8600 + M)
         x = make_x(K, "laplace", 8601 + M)
         thr = quantile_threshold(x, 0.5)
-        got = gpu_cb_gemv(gpu, W, x, thr)[0]
-        gotd = gpu_cb_gemv(gpu, W, x, thr, dense=True)[0]
+        packed = torch.from_numpy(spqt.spqt_cb_quantize(W)).to(dev)
+        got = gpu_cb_gemv(gpu, W, x, thr, packed=packed)[0]
+        gotd = gpu_cb_gemv(gpu, W, x, thr, dense=True, packed=packed)[0]
+        gotf = gpu_cb_gemv_fused(gpu, W, x, thr, packed=packed)[0]
         rng = np.random.default_rng(M)
         tiles = np.unique(np.concatenate([[0, M // 256 - 1], rng.integers(0, M // 256, size=3)]))
         rows = (tiles[:, None] * 256 + np.arange(256)[None, :]).ravel()
         q, s = cb.quantize(W[rows])           # blocks are quantized independently of each other
         assert_close(got[rows][None, :], cb.gemv(q, s, x, thr), f"cb {M}x{K} sparse")
         assert_close(gotd[rows][None, :], cb.gemv(q, s, x, 0.0), f"cb {M}x{K} dense")
+        assert_close(gotf[rows][None, :], cb.gemv(q, s, x, thr), f"cb {M}x{K} fused")
+        del packed
         del W
