@@ -245,6 +245,74 @@ def ablations(torch, spqt, use_graph):
     return rows
 
 
+def colblock_rows(torch, spqt, use_graph):
+    """The column-block variant of the layout (the paper's own grouping, Section 4.1.2: 32-row
+    blocks along a column, scales skipped with their column) on the headline and 70B shapes.
+    Copy 0 is quantized from seeded fp32 weights by the library and checked against the
+    NumPy oracle on sampled 256-row tiles; the other copies are random packed bytes."""
+    import numpy as np
+    from oracle import colblock as cb
+    from workloads import make_fp_weights, make_x, quantile_threshold
+    dev = torch.device("cuda:0")
+    rows = []
+    for M, K, sps in ((4096, 4096, (0.5,)), (28672, 8192, (0.3, 0.5, 0.7)), (8192, 28672, (0.5,))):
+        pbytes = spqt.spqt_cb_packed_bytes(M, K)
+        copies = max(2, -(-ROTATE_BYTES // pbytes))
+        T, NC = M // 256, K // 128
+        W0 = make_fp_weights(M, K, 9000 + M)
+        packed = [torch.from_numpy(spqt.spqt_cb_quantize(W0)).to(dev)]
+        g = torch.Generator(device=dev)
+        g.manual_seed(9001 + M)
+        for _ in range(1, copies):
+            buf = torch.randint(0, 256, (T * NC, spqt.CB_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NC, 1024), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
+            buf[:, :2048] = sc.view(torch.uint8)
+            packed.append(buf.reshape(-1))
+        tiles = np.unique(np.array([0, T // 2, T - 1]))
+        sample = (tiles[:, None] * 256 + np.arange(256)[None, :]).ravel()
+        q0, s0 = cb.quantize(W0[sample])
+        del W0
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        y = torch.empty(M, dtype=torch.float32, device=dev)
+        ws = spqt.new_workspace(M, K)
+        for s in sps:
+            x_np = make_x(K, "laplace", 9002 + M)
+            thr = quantile_threshold(x_np, s)
+            x = torch.from_numpy(x_np[0]).to(dev)
+            spqt.spqt_gather(x, thr, idx, cnt)
+            torch.cuda.synchronize()
+            n = int(cnt.item())
+            ref = cb.gemv(q0, s0, x_np, thr)[0]
+            for name, call in (("list", lambda: spqt.spqt_cb_gemv(packed[0], M, K, x, idx, cnt, y, ws)),
+                               ("fused", lambda: spqt.spqt_cb_gemv_fused(packed[0], M, K, x, thr, y, ws))):
+                y.fill_(float("nan"))
+                call()
+                torch.cuda.synchronize()
+                err = np.abs(y.cpu().numpy().astype(np.float64)[sample] - ref)
+                if not bool(np.all(err <= 1e-2 + 2e-3 * np.abs(ref))):
+                    print(f"bench.py: column-block parity check FAILED ({M}x{K}, {name})", file=sys.stderr)
+                    sys.exit(1)
+            fns = {"us_gemv": lambda i: spqt.spqt_cb_gemv(packed[i], M, K, x, idx, cnt, y, ws),
+                   "us_dense": lambda i: spqt.spqt_cb_gemv(packed[i], M, K, x, None, None, y, ws),
+                   "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
+                                                     spqt.spqt_cb_gemv(packed[i], M, K, x, idx, cnt, y, ws)),
+                   "us_fused": lambda i: spqt.spqt_cb_gemv_fused(packed[i], M, K, x, thr, y, ws)}
+            t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
+            kept = n * (M // 2 + M // 16)
+            rows.append({"M": M, "K": K, "sparsity": s, "kept_frac": round(n / K, 4),
+                         "bits_per_weight": 4.5, "kept_bytes": kept,
+                         **{k: round(v, 3) for k, v in t.items()},
+                         "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
+                         "frac_of_8TBps": round(kept / (t["us_gemv"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "dense_GBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9, 1),
+                         "speedup_vs_dense": round(t["us_dense"] / t["us_gemv"], 3),
+                         "fused_speedup_vs_dense": round(t["us_dense"] / t["us_fused"], 3)})
+        del packed
+        torch.cuda.empty_cache()
+    return rows
+
+
 def dense_shape_sweep(torch, spqt, use_graph):
     """The dense zigzag kernel on the 15 shapes of the paper's dense micro-benchmark
     (Section 6.4: m in {2048, 4096, 8192} x k in {1024 ... 16384}); random packed bytes."""
@@ -562,6 +630,7 @@ def main():
         if args.full:
             # decoder-layer sequences: Llama-2-7B MLP over 16 layers (config 3), Llama-3-8B full layer
             # over 32 layers (config 4); spqt_gather time included
+            out["colblock_layout"] = colblock_rows(torch, spqt, use_graph)
             out["ablations"] = ablations(torch, spqt, use_graph)
             out["dense_shape_sweep"] = dense_shape_sweep(torch, spqt, use_graph)
             out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),

@@ -266,6 +266,14 @@ int run_cb(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x
         return SPQT_EALIGN;
     spqt_launch_cfg c;
     if (int rc = spqt_default_cfg(M, K, 1, mode != 1, &c)) return rc;
+    {
+        // Measured on MI355X (sweep of S per shape, 50 % and dense): this kernel has no per-group
+        // work, so on matrices large enough to be bandwidth-bound (>= 64 MB packed) fewer, longer
+        // slices win for the list-driven and dense kernels: about 256 workgroups instead of 512 / 1024.
+        const int64_t T64 = M / kTileRows;
+        if (mode != 2 && (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20))
+            while (c.splits > 1 && (int64_t)c.splits * T64 > 256) c.splits /= 2;
+    }
     if (cfg) {
         if (cfg->flags) return SPQT_EINVAL;
         if (cfg->splits) c.splits = cfg->splits;
