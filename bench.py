@@ -494,6 +494,57 @@ def cpu_baseline(case, x_np, thr, budget_s=12.0):
     return dt / reps * 1e6, reps, oracle.threads()
 
 
+def pmc_pass_large(torch, spqt, which):
+    """Hardware-counter pass on the 70B gate shape (28672 x 8192, 50 %): 8 plain copies of 64 MiB
+    for counter scaling, then the sparse, dense and one-launch kernels once per weight copy."""
+    import numpy as np
+    from workloads import CONFIG_SCALE_RANGE, make_x, quantile_threshold
+    M, K, s = 28672, 8192, 0.5
+    cal = Calib(torch)
+    dev = torch.device("cuda:0")
+    a = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 256)
+    b = torch.empty_like(a)
+    for _ in range(8):
+        cal.copy(b, a, 64 << 20)
+    if which == "gate70b":
+        wl = Workload(torch, spqt, M, K, "laplace", CONFIG_SCALE_RANGE[5], 5, "gate", s)
+        for fn in (wl.gemv_only, wl.dense_only, wl.fused):
+            for i in range(wl.copies):
+                fn(i)
+        kept, dense, copies = wl.mean_kept_bytes, wl.dense_bytes, wl.copies
+    else:
+        pbytes = spqt.spqt_cb_packed_bytes(M, K)
+        copies = max(2, -(-ROTATE_BYTES // pbytes))
+        T, NC = M // 256, K // 128
+        g = torch.Generator(device=dev)
+        g.manual_seed(9101)
+        packed = []
+        for _ in range(copies):
+            buf = torch.randint(0, 256, (T * NC, spqt.CB_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NC, 1024), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
+            buf[:, :2048] = sc.view(torch.uint8)
+            packed.append(buf.reshape(-1))
+        x_np = make_x(K, "laplace", 9102)
+        thr = quantile_threshold(x_np, s)
+        x = torch.from_numpy(x_np[0]).to(dev)
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        y = torch.empty(M, dtype=torch.float32, device=dev)
+        ws = spqt.new_workspace(M, K)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        torch.cuda.synchronize()
+        for i in range(copies):
+            spqt.spqt_cb_gemv(packed[i], M, K, x, idx, cnt, y, ws)
+        for i in range(copies):
+            spqt.spqt_cb_gemv(packed[i], M, K, x, None, None, y, ws)
+        for i in range(copies):
+            spqt.spqt_cb_gemv_fused(packed[i], M, K, x, thr, y, ws)
+        kept, dense = int(cnt.item()) * (M // 2 + M // 16), pbytes
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_pass": True, "workload": which, "copy_bytes": 64 << 20, "launches_per_kernel": copies,
+                      "kept_bytes_per_launch": kept, "dense_bytes_per_launch": dense, "y_bytes_per_launch": 4 * M}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -506,6 +557,9 @@ def main():
     ap.add_argument("--pmc-pass", action="store_true",
                     help="for hardware-counter runs: launch only a 64 MiB calibration copy (x8) and the "
                          "headline sparse GEMV once per weight copy, eagerly, and exit")
+    ap.add_argument("--pmc-workload", choices=["headline", "gate70b", "gate70b_colblock"], default="headline",
+                    help="with --pmc-pass: which sparse GEMV to launch (4096x4096 group layout, 28672x8192 group "
+                         "layout, 28672x8192 column-block layout), all at 50 %%")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
@@ -521,6 +575,10 @@ def main():
     spqt.lib()
     use_graph = not args.eager
     K_steps, W = args.steps, args.warmup
+
+    if args.pmc_pass and args.pmc_workload != "headline":
+        pmc_pass_large(torch, spqt, args.pmc_workload)
+        return
 
     # ---------------- headline: config 2, 4096 x 4096, 50 % -------------------------------
     M, K = 4096, 4096
