@@ -404,6 +404,20 @@ def layer_sequence(torch, spqt, config, layers, sparsity, use_graph=True, reps=5
             mitems.append((Mtot, K, pk, g_items[0][4], g_items[0][5], g_items[0][6], g_items[0][7], y))
         merged.append(mitems)
 
+    # The same merged matrices in the column-block layout (random packed bytes of that format).
+    cb_merged = []
+    for li, mitems in enumerate(merged):
+        row = []
+        for mi, (Mtot, K, pk, x, t, idx, cnt, y) in enumerate(mitems):
+            g = torch.Generator(device=dev)
+            g.manual_seed(seed_for(config, li, "w") + 7000 + mi)
+            T, NC = Mtot // 256, K // 128
+            buf = torch.randint(0, 256, (T * NC, spqt.CB_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NC, 1024), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
+            buf[:, :2048] = sc.view(torch.uint8)
+            row.append(buf.reshape(-1))
+        cb_merged.append(row)
+
     # achieved kept counts (one eager pass)
     for items in L:
         for name, M, K, pk, x, t, idx, cnt, y, site in items:
@@ -416,6 +430,17 @@ def layer_sequence(torch, spqt, config, layers, sparsity, use_graph=True, reps=5
             n_gemv += 1
 
     def run(mode):
+        if mode.startswith("cb_"):
+            for mitems, cbrow in zip(merged, cb_merged):
+                for (Mtot, K, pk, x, t, idx, cnt, y), cpk in zip(mitems, cbrow):
+                    if mode == "cb_merged_fused":
+                        spqt.spqt_cb_gemv_fused(cpk, Mtot, K, x, t, y, ws[(Mtot, K)])
+                    elif mode == "cb_merged_dense":
+                        spqt.spqt_cb_gemv(cpk, Mtot, K, x, None, None, y, ws[(Mtot, K)])
+                    else:
+                        spqt.spqt_gather(x, t, idx, cnt)
+                        spqt.spqt_cb_gemv(cpk, Mtot, K, x, idx, cnt, y, ws[(Mtot, K)])
+            return
         if mode.startswith("merged"):
             for mitems in merged:
                 for Mtot, K, pk, x, t, idx, cnt, y in mitems:
@@ -448,7 +473,8 @@ def layer_sequence(torch, spqt, config, layers, sparsity, use_graph=True, reps=5
     out = {"config": config, "layers": layers, "gemvs_per_layer": len(shapes), "sparsity_target": sparsity,
            "packed_MB": round(dense_bytes_total / 1e6, 1), "kept_MB": round(kept_bytes_total / 1e6, 1)}
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for mode in ("strict", "shared", "fused", "merged_gather_gemv", "merged_fused", "dense", "merged_dense"):
+    for mode in ("strict", "shared", "fused", "merged_gather_gemv", "merged_fused", "dense", "merged_dense",
+                 "cb_merged_gather_gemv", "cb_merged_fused", "cb_merged_dense"):
         run(mode)
         torch.cuda.synchronize()
         st = torch.cuda.Stream()
@@ -469,11 +495,14 @@ def layer_sequence(torch, spqt, config, layers, sparsity, use_graph=True, reps=5
             torch.cuda.synchronize()
         us_pass = start.elapsed_time(stop) * 1e3 / reps
         nbytes = dense_bytes_total if mode.endswith("dense") else kept_bytes_total
+        if mode.startswith("cb_"):
+            nbytes *= 0.5625 / 0.515625          # 4.5 instead of 4.125 bits per weight
         out[mode] = {"us_per_layer": round(us_pass / layers, 2), "us_per_gemv": round(us_pass / n_gemv, 3),
                      "GBps": round(nbytes / (us_pass * 1e-6) / 1e9, 1)}
     out["speedup_strict_vs_dense"] = round(out["dense"]["us_per_layer"] / out["strict"]["us_per_layer"], 3)
     out["speedup_fused_vs_dense"] = round(out["dense"]["us_per_layer"] / out["fused"]["us_per_layer"], 3)
     out["speedup_merged_fused_vs_merged_dense"] = round(out["merged_dense"]["us_per_layer"] / out["merged_fused"]["us_per_layer"], 3)
+    out["speedup_cb_merged_fused_vs_cb_merged_dense"] = round(out["cb_merged_dense"]["us_per_layer"] / out["cb_merged_fused"]["us_per_layer"], 3)
     out["launches_per_layer"] = {"strict": 2 * len(shapes), "shared": len(shapes) + len(merged[0]), "fused": len(shapes),
                                  "merged_gather_gemv": 2 * len(merged[0]), "merged_fused": len(merged[0]), "dense": len(shapes), "merged_dense": len(merged[0])}
     return out
