@@ -83,8 +83,11 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const int s = slot % S;
     if (t >= T) return;
     // This call's tag for the cross-workgroup exchange (requested now, used at the very end).
-    int tag = 0;
-    if (S > 1) tag = __hip_atomic_load(epochs + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+    uint32_t tag = 0;   // unsigned: the epoch wraps after 2^32 calls on one workspace, skipping 0
+    if (S > 1) {        // (0 is what a cleared, never written word carries)
+        tag = __hip_atomic_load(reinterpret_cast<uint32_t *>(epochs) + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        tag += tag == 0u;
+    }
 
     // Even split of the index list over the S*WAVES wavefronts of this block-row.
     const int n_ns = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));

@@ -69,8 +69,11 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     const int t = xcd + 8 * (slot_id / S);
     const int s = slot_id % S;
     if (t >= T) return;
-    int tag = 0;
-    if (S > 1) tag = __hip_atomic_load(epochs + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+    uint32_t tag = 0;   // unsigned: the epoch wraps after 2^32 calls on one workspace, skipping 0
+    if (S > 1) {        // (0 is what a cleared, never written word carries)
+        tag = __hip_atomic_load(reinterpret_cast<uint32_t *>(epochs) + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        tag += tag == 0u;
+    }
 
     const int n_ns = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));
     const int parts = S * WAVES;

@@ -152,7 +152,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // and workgroups are dispatched in index order, so everything it waits for is running or
 // finished; the wait is bounded anyway and a give-up poisons y with NaN instead of hanging.
 template <int WAVES, int BATCH>
-__device__ __forceinline__ void combine_block_row(const float *red, int tid, int t, int s, int S, int tag,
+__device__ __forceinline__ void combine_block_row(const float *red, int tid, int t, int s, int S, uint32_t tag,
                                                   void *partials, int32_t *epochs, float *__restrict__ y,
                                                   int M) {
     constexpr int kOut = BATCH * kTileRows;      // values one workgroup contributes: [BATCH][256]
@@ -165,7 +165,7 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
         if (S == 1) {
             *y_out = sum;
         } else if (s != S - 1) {
-            const unsigned long long word = ((unsigned long long)(uint32_t)tag << 32) | as_u32(sum);
+            const unsigned long long word = ((unsigned long long)tag << 32) | as_u32(sum);
             __hip_atomic_store(slots + (size_t)s * kOut + r, word, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         } else {
@@ -185,7 +185,7 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
                     }
                     uint32_t missing = 0u;
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[j] >> 32) ^ (uint32_t)tag;
+                    for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[j] >> 32) ^ tag;
                     all_here = missing == 0u;
                 } while (!all_here && ++polls < kMaxPolls);
                 gave_up = gave_up || !all_here;
@@ -198,7 +198,7 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
         }
     }
     if (S > 1 && s == S - 1 && tid == 0)
-        __hip_atomic_store(epochs + t, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(reinterpret_cast<uint32_t *>(epochs) + t, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace spqt

@@ -320,6 +320,30 @@ def test_fused_full_size_headline(gpu):
         assert_close(gpu_gemv_fused(gpu, case, case["x"], thr, packed=packed), ref, f"fused cfg2 s={s}")
 
 
+def test_exchange_tag_wraps_around(gpu):
+    """The tag of the partial-sum exchange is the block-row's epoch + 1 as an unsigned 32-bit
+    number; start the epochs just under 2^32 and run across the wrap."""
+    torch, spqt, dev = gpu
+    M, K = 1024, 2048
+    w = make_weights(M, K, 91)
+    x_np = make_x(K, "laplace", 92)
+    thr = quantile_threshold(x_np, 0.5)
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x_np, thr)
+    packed = torch.from_numpy(spqt.spqt_pack(w["q_rowmajor"], w["scales"])).to(dev)
+    x = torch.from_numpy(x_np[0]).to(dev)
+    idx = torch.empty(K, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    spqt.spqt_gather(x, thr, idx, cnt)
+    ws = spqt.new_workspace(M, K)
+    ws.view(torch.int32)[: M // 256] = -3          # 0xFFFFFFFD: the third call from now wraps
+    for call in range(6):
+        y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+        spqt.spqt_gemv(packed, M, K, x, idx, cnt, y, ws, splits=8, waves=2)
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy()[None, :], ref, f"call {call} across the epoch wrap")
+    assert int(ws.view(torch.int32)[0].item()) == 4    # ... FFFFFFFE, FFFFFFFF, 1 (0 skipped), 2, 3, 4
+
+
 def test_hip_graph_replay_matches_eager(gpu):
     """gather + GEMV captured in one HIP graph and replayed, with eager work and
     synchronizations between the replays: every replay must reproduce the eager result."""
