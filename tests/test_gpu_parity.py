@@ -320,6 +320,22 @@ def test_fused_full_size_headline(gpu):
         assert_close(gpu_gemv_fused(gpu, case, case["x"], thr, packed=packed), ref, f"fused cfg2 s={s}")
 
 
+def test_longest_supported_k(gpu):
+    """K = 65536 (the gather's limit), one block-row: list-driven, dense and one-launch paths."""
+    M, K = 256, 65536
+    w = make_weights(M, K, 93)
+    x = make_x(K, "laplace", 94)
+    thr = quantile_threshold(x, 0.5)
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    idx, cnt = gpu_gather(gpu, x, thr)
+    ref_idx, n = oracle.gather(x, thr)
+    assert int(cnt[0]) == n and np.array_equal(idx[:n], ref_idx)
+    for splits, waves in [(0, 0), (64, 4), (3, 2)]:
+        assert_close(gpu_gemv(gpu, w, x, thr, splits=splits, waves=waves), ref, f"K=65536 {splits}x{waves}")
+        assert_close(gpu_gemv_fused(gpu, w, x, thr, splits=splits, waves=waves), ref, f"K=65536 fused {splits}x{waves}")
+    assert_close(gpu_gemv(gpu, w, x, 0.0, dense=True), oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0), "K=65536 dense")
+
+
 def test_exchange_tag_wraps_around(gpu):
     """The tag of the partial-sum exchange is the block-row's epoch + 1 as an unsigned 32-bit
     number; start the epochs just under 2^32 and run across the wrap."""
