@@ -129,8 +129,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         // pass (the run of entries that share the group of idx[p], at most 64), request the
         // NEXT pass's entries, this pass's x, its weights (8 steps, always) and its scales.
         // Past the end of the slice (p >= end) it degenerates to n = 0 with harmless re-reads.
-        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, int &g_out,
-                         uint32_t(&xraw_out)[BATCH], u32x2 &sc_out, int &k_after) {
+        // Everything of the FETCH stage but the weight loads: hands back where they go.
+        auto fetch_head = [&](int kk, int p, int slot, const uint8_t *&chunk_out, uint32_t(&off)[8], int &n_out,
+                              int &g_out, uint32_t(&xraw_out)[BATCH], u32x2 &sc_out, int &k_after) {
             const bool any = p < end;
             const int g = any ? (__builtin_amdgcn_readfirstlane(kk) >> 7) : 0;
             const bool in = any && ((kk >> 7) == g);
@@ -145,20 +146,30 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             stage_off[wave][slot][lane] = in ? koff_in : koff_first;
             const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;   // wave-uniform base
             __builtin_amdgcn_wave_barrier();
-            uint32_t off[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) off[u] = stage_off[wave][slot][u * 8 + cg] + seg16;
+            sc_out = *reinterpret_cast<const u32x2 *>(chunk + (size_t)sc_off);
+            chunk_out = chunk;
+            n_out = n;
+            g_out = g;
+        };
+        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, int &g_out,
+                         uint32_t(&xraw_out)[BATCH], u32x2 &sc_out, int &k_after) {
+            const uint8_t *chunk;
+            uint32_t off[8];
+            fetch_head(kk, p, slot, chunk, off, n_out, g_out, xraw_out, sc_out, k_after);
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 w[u] = __builtin_nontemporal_load(
                     reinterpret_cast<const u32x4 *>(chunk + kScaleBytes + (size_t)off[u]));
-            sc_out = *reinterpret_cast<const u32x2 *>(chunk + (size_t)sc_off);
-            n_out = n;
-            g_out = g;
         };
 
         // MULTIPLY stage of a fetched pass.
-        auto multiply = [&](int n, const uint32_t(&xraw)[BATCH], int slot, const u32x4(&w)[8]) {
+        // With chunk_next != nullptr the stage is "rolling": as soon as step u has been consumed, the
+        // registers of w[u] receive step u of the NEXT pass (whose FETCH head has already run), so
+        // the next pass's weights fly during this pass's arithmetic without a second buffer.
+        auto multiply = [&](int n, const uint32_t(&xraw)[BATCH], int slot, u32x4(&w)[8],
+                            const uint8_t *chunk_next = nullptr, const uint32_t *off_next = nullptr) {
             if (FUSED) {    // the fused fetch stage has already staged x; xraw carries this lane's share
                 xsum[0] += as_float(xraw[0]);
             } else {
@@ -194,6 +205,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                             else fma_step<false>(w[u], xl[b], acc[b]);
                         }
                     }
+                    if (chunk_next)
+                        w[u] = __builtin_nontemporal_load(
+                            reinterpret_cast<const u32x4 *>(chunk_next + kScaleBytes + (size_t)off_next[u]));
                 }
             }
 #pragma unroll
@@ -296,20 +310,31 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         kA = fetch_k(pos);
         fetch(kA, pos, 0, wA, nA, gA, xrA, scA, kB);
         if (BATCH > 1) {
-            // Several activation rows: the multiply stage dominates (BATCH fused multiply-adds per
-            // code) and the accumulators take most of the register file, so passes are simply
-            // fetched and multiplied one after the other with one weight buffer.
+            // Several activation rows: the accumulators take most of the register file, so there is
+            // one weight buffer, refilled step by step while the pass is being multiplied.
+            int slot = 0;
             for (;;) {
-                multiply(nA, xrA, 0, wA);
-                pos += nA;
-                if (pos >= end) break;
-                const int g_prev = gA;
-                const u32x2 sc_prev = scA;
-                fetch(kB, pos, 0, wA, nA, gA, xrA, scA, kA);
-                kB = kA;
-                if (gA != g_prev) flush(sc_prev);
+                const int posN = pos + nA;
+                const uint8_t *chunkN;
+                uint32_t offN[8], xrN[BATCH];
+                u32x2 scN;
+                int nN, gN, kC;
+                fetch_head(kB, posN, slot ^ 1, chunkN, offN, nN, gN, xrN, scN, kC);
+                multiply(nA, xrA, slot, wA, chunkN, offN);
+                if (posN >= end) {
+                    flush(scA);
+                    break;
+                }
+                if (gN != gA) flush(scA);
+                pos = posN;
+                nA = nN;
+                gA = gN;
+                scA = scN;
+                kB = kC;
+                slot ^= 1;
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) xrA[b] = xrN[b];
             }
-            flush(scA);
         } else if (pos + nA >= end) {
             // the whole slice is one pass (small matrices): nothing to overlap with
             multiply(nA, xrA, 0, wA);
