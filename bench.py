@@ -252,7 +252,9 @@ def colblock_rows(torch, spqt, use_graph, cpu):
     from workloads import make_fp_weights, make_x, quantile_threshold
     dev = torch.device("cuda:0")
     rows = []
-    for M, K, sps in ((4096, 4096, (0.5,)), (28672, 8192, (0.3, 0.5, 0.7)), (8192, 28672, (0.5,))):
+    L, C = "laplace", "laplace_clustered"     # C: 7 of 8 kept columns in the first half of K
+    for M, K, sps in ((4096, 4096, ((0.5, L),)), (28672, 8192, ((0.3, L), (0.5, L), (0.7, L), (0.5, C))),
+                      (8192, 28672, ((0.5, L),))):
         pbytes = spqt.spqt_cb_packed_bytes(M, K)
         copies = max(2, -(-ROTATE_BYTES // pbytes))
         T, NC = M // 256, K // 128
@@ -273,8 +275,8 @@ def colblock_rows(torch, spqt, use_graph, cpu):
         cnt = torch.zeros(1, dtype=torch.int32, device=dev)
         y = torch.empty(M, dtype=torch.float32, device=dev)
         ws = spqt.new_workspace(M, K)
-        for s in sps:
-            x_np = make_x(K, "laplace", 9002 + M)
+        for s, dist in sps:
+            x_np = make_x(K, dist, 9002 + M)
             thr = quantile_threshold(x_np, s)
             x = torch.from_numpy(x_np[0]).to(dev)
             spqt.spqt_gather(x, thr, idx, cnt)
@@ -297,7 +299,7 @@ def colblock_rows(torch, spqt, use_graph, cpu):
                    "us_fused": lambda i: spqt.spqt_cb_gemv_fused(packed[i], M, K, x, thr, y, ws)}
             t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
             kept = n * (M // 2 + M // 16)
-            rows.append({"M": M, "K": K, "sparsity": s, "kept_frac": round(n / K, 4),
+            rows.append({"M": M, "K": K, "sparsity": s, "activations": dist, "kept_frac": round(n / K, 4),
                          "bits_per_weight": 4.5, "kept_bytes": kept,
                          **{k: round(v, 3) for k, v in t.items()},
                          "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
