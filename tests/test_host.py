@@ -163,3 +163,22 @@ def test_default_launch_shape_is_valid(M, K):
     for sparse in (False, True):
         splits, waves = spqt.spqt_default_cfg(M, K, 1, sparse)
         assert 1 <= splits <= spqt.MAX_SPLITS and waves in (1, 2, 4)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU measurement: --gpus N > 1 exits with a message before touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2
+    assert "one-GPU" in r.stderr
+
+
+def test_product_package_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing under the product package may reference it."""
+    pkg = os.path.join(ROOT, "paper_2511_04477_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f), encoding="utf-8", errors="ignore").read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)
