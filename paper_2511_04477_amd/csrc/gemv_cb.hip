@@ -75,7 +75,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
         tag += tag == 0u;
     }
 
-    const int n_ns = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));
+    // (a count outside 0..K cannot come from spqt_gather; clamping keeps a corrupt one inside idx)
+    const int n_raw = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));
+    const int n_ns = n_raw < 0 ? 0 : (n_raw > K ? K : n_raw);
     const int parts = S * WAVES;
     const int part = s * WAVES + wave;
     int pos = (int)(((int64_t)n_ns * part) / parts);
