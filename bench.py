@@ -312,6 +312,52 @@ def colblock_rows(torch, spqt, use_graph, cpu):
     return rows
 
 
+def speedup_grid(torch, spqt, use_graph):
+    """Sparse-over-dense speed-up against sparsity on the GEMV shapes of the paper's kernel
+    micro-benchmark (Section 6.3: Llama-3-8B, Llama-2-13B and Llama-2-70B projections at 25 / 40 /
+    50 %), for both layouts; random packed bytes, iid Laplace activations, gather time not included."""
+    import numpy as np
+    from workloads import make_x, quantile_threshold
+    dev = torch.device("cuda:0")
+    shapes = [("llama-3-8b", 4096, 4096), ("llama-3-8b", 14336, 4096), ("llama-3-8b", 4096, 14336),
+              ("llama-2-13b", 5120, 5120), ("llama-2-13b", 13824, 5120), ("llama-2-13b", 5120, 13824),
+              ("llama-2-70b", 8192, 8192), ("llama-2-70b", 28672, 8192), ("llama-2-70b", 8192, 28672)]
+    rows = []
+    for model, M, K in shapes:
+        T, NC = M // 256, K // 128
+        x_np = make_x(K, "laplace", 9200 + M + K)
+        x = torch.from_numpy(x_np[0]).to(dev)
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        y = torch.empty(M, dtype=torch.float32, device=dev)
+        ws = spqt.new_workspace(M, K)
+        for layout, chunk, nscale, gemv in (("group", spqt.CHUNK_BYTES, 256, spqt.spqt_gemv),
+                                            ("colblock", spqt.CB_CHUNK_BYTES, 1024, spqt.spqt_cb_gemv)):
+            pbytes = T * NC * chunk
+            copies = max(2, -(-ROTATE_BYTES // pbytes))
+            g = torch.Generator(device=dev)
+            g.manual_seed(9201 + M + K)
+            packed = []
+            for _ in range(copies):
+                buf = torch.randint(0, 256, (T * NC, chunk), dtype=torch.uint8, device=dev, generator=g)
+                sc = (torch.rand((T * NC, nscale), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
+                buf[:, :2 * nscale] = sc.view(torch.uint8)
+                packed.append(buf.reshape(-1))
+            steps = max(copies * 4, 400)
+            t_dense = time_sequence(torch, lambda i: gemv(packed[i], M, K, x, None, None, y, ws), copies, steps, copies, use_graph)
+            row = {"model": model, "M": M, "K": K, "layout": layout, "us_dense": round(t_dense, 3), "sparse": []}
+            for sp in (0.25, 0.4, 0.5):
+                thr = quantile_threshold(x_np, sp)
+                spqt.spqt_gather(x, thr, idx, cnt)
+                torch.cuda.synchronize()
+                t_sparse = time_sequence(torch, lambda i: gemv(packed[i], M, K, x, idx, cnt, y, ws), copies, steps, copies, use_graph)
+                row["sparse"].append({"sparsity": sp, "us": round(t_sparse, 3), "speedup_vs_dense": round(t_dense / t_sparse, 3)})
+            rows.append(row)
+            del packed
+            torch.cuda.empty_cache()
+    return rows
+
+
 def dense_shape_sweep(torch, spqt, use_graph):
     """The dense zigzag kernel on the 15 shapes of the paper's dense micro-benchmark
     (Section 6.4: m in {2048, 4096, 8192} x k in {1024 ... 16384}); random packed bytes."""
@@ -748,6 +794,7 @@ def main():
             out["colblock_layout"] = colblock_rows(torch, spqt, use_graph, cpu)
             out["ablations"] = ablations(torch, spqt, use_graph, cpu)
             out["dense_shape_sweep"] = dense_shape_sweep(torch, spqt, use_graph)
+            out["speedup_grid"] = speedup_grid(torch, spqt, use_graph)
             out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),
                                       layer_sequence(torch, spqt, 3, 16, 0.5, use_graph),
                                       layer_sequence(torch, spqt, 4, 32, 0.5, use_graph)]
