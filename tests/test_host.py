@@ -182,3 +182,29 @@ def test_product_package_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".cpp", ".hpp", ".h")):
                 text = open(os.path.join(dirpath, f), encoding="utf-8", errors="ignore").read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_packers_agree_on_random_shapes_and_bytes():
+    """Property check (hypothesis): for arbitrary code bytes and scale bit patterns the library's
+    repacker equals the oracle's byte for byte and unpack inverts it; the column-block quantizer
+    equals the oracle's on arbitrary finite weights with mixed magnitudes."""
+    from hypothesis import given, settings, strategies as st
+    from oracle import colblock as cb
+
+    @settings(max_examples=25, deadline=None)
+    @given(st.integers(1, 3), st.integers(1, 5), st.integers(0, 2 ** 32 - 1))
+    def check(tm, kg, seed):
+        M, K = 256 * tm, 128 * kg
+        rng = np.random.default_rng(seed)
+        raw = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+        sc = rng.integers(0, 65536, size=(M, K // 128), dtype=np.uint16)
+        got = spqt.spqt_pack(raw, sc)
+        assert np.array_equal(got, oracle.pack(raw, sc))
+        q2, s2 = spqt.spqt_unpack(got, M, K)
+        assert np.array_equal(q2, raw) and np.array_equal(s2.view(np.uint16), sc)
+        W = (rng.standard_normal((M, K)) * 10.0 ** rng.integers(-6, 3, size=(1, K))).astype(np.float32)
+        W[rng.random((M, K)) < 0.05] = 0.0
+        q, s = cb.quantize(W)
+        assert np.array_equal(spqt.spqt_cb_quantize(W), cb.pack(q, s))
+
+    check()
