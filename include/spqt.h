@@ -77,7 +77,10 @@ int spqt_packed_bytes(int64_t M, int64_t K, int group, size_t *out_bytes);
  * spqt_workspace_init before its first use; every call leaves it ready for the next one
  * (the tag of a call is its block-row's epoch + 1, so words of earlier calls never match).
  * Two calls that may overlap in time (different streams) need two workspaces; calls on one
- * stream, or replays of one graph, may share one. */
+ * stream, or replays of one graph, may share one PROVIDED THEY HAVE THE SAME M (any K, batch,
+ * launch shape, dense / sparse / fused, group or column-block layout): the epochs of all
+ * block-rows then advance in step, which is what keeps leftover words from matching.  Before
+ * a workspace is reused for a different M, run spqt_workspace_init on it again. */
 int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out_bytes);
 
 /* DEVICE, async.  Clears the whole workspace (epochs and tagged words) with a small fill
