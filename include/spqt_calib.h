@@ -22,6 +22,11 @@ int spqt_calib_read(const void *src_dev, size_t bytes, uint32_t *sink_dev, int b
  * time, `unroll` (2, 4, 8, 16) loads in flight - the order a GEMV wavefront reads its columns in. */
 int spqt_calib_read_blocked(const void *src_dev, size_t bytes, uint32_t *sink_dev, int blocks, int unroll,
                             void *stream);
+/* Reads only the 128-byte lines whose numbers are listed in lines_dev (ascending int32, n_lines
+ * of them; src_dev 128-byte aligned), 8 lines per wavefront load, each wavefront a contiguous
+ * slice of the list - the sparse GEMV's access pattern with no arithmetic. */
+int spqt_calib_read_lines(const void *src_dev, const int32_t *lines_dev, int n_lines, uint32_t *sink_dev,
+                          int blocks, int unroll, void *stream);
 /* Copies `bytes` (multiple of 16) from src to dst: reads bytes, writes bytes. */
 int spqt_calib_copy(void *dst_dev, const void *src_dev, size_t bytes, int blocks, void *stream);
 /* Launches one empty workgroup. */

@@ -24,7 +24,8 @@ def declared_functions(header="spqt.h"):
 def test_calibration_library_exports_every_declared_symbol():
     L = ctypes.CDLL(os.path.join(ROOT, "paper_2511_04477_amd", "libspqt_calib.so"))
     names = declared_functions("spqt_calib.h")
-    assert names == ["spqt_calib_copy", "spqt_calib_empty", "spqt_calib_read", "spqt_calib_read_blocked"]
+    assert names == ["spqt_calib_copy", "spqt_calib_empty", "spqt_calib_read", "spqt_calib_read_blocked",
+                     "spqt_calib_read_lines"]
     for n in names:
         assert getattr(L, n) is not None
     # argument checks happen before any launch
