@@ -50,22 +50,23 @@ int spqt_cb_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_pa
 /* HOST.  The values the packed form stands for: w_out[m][k] = q * float(s), float[M][K]. */
 int spqt_cb_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 
-/* DEVICE, async.  y[m] = sum over the listed columns k of q[m][k] * s[m/32][k] * x[k], fp32
- * accumulation, batch 1 (Section 4.2.2 / 4.2.3: same block-row parallelism and even split
- * of the index list as spqt_gemv).
+/* DEVICE, async.  y[b][m] = sum over the listed columns k of q[m][k] * s[m/32][k] * x[b][k], fp32
+ * accumulation (Section 4.2.2 / 4.2.3: same block-row parallelism and even split of the index
+ * list as spqt_gemv).
  *   packed_dev     device copy of spqt_cb_quantize's output, 128-byte aligned.
- *   x_dev          fp16[K].
+ *   x_dev          fp16[batch][K], batch in 1..SPQT_MAX_BATCH (rows share the union index list
+ *                  and one pass over the weights).
  *   idx_dev        int32 kept-column list from spqt_gather (ascending), or NULL for the
  *                  dense kernel, which visits every column and reads neither idx nor count.
  *   count_dev      int32[1] n_ns on the device (ignored when idx_dev == NULL).
- *   y_dev          fp32[M], fully overwritten.
- *   workspace_dev  as for spqt_gemv: >= spqt_workspace_bytes(M, K, 1), prepared once by
+ *   y_dev          fp32[batch][M], fully overwritten.
+ *   workspace_dev  as for spqt_gemv: >= spqt_workspace_bytes(M, K, batch), prepared once by
  *                  spqt_workspace_init.
  *   cfg            launch shape or NULL (flags must be 0).
  * Deterministic; same bounded wait and NaN-on-give-up behaviour as spqt_gemv. */
-int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
-                 const int32_t *count_dev, float *y_dev, void *workspace_dev, size_t workspace_bytes,
-                 void *stream, const spqt_launch_cfg *cfg);
+int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
+                 const int32_t *idx_dev, const int32_t *count_dev, float *y_dev, void *workspace_dev,
+                 size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg);
 
 /* DEVICE, async.  Gather and GEMV in ONE launch (the column-block counterpart of
  * spqt_gemv_fused): the kernel applies the sparsity test of Section 2 to x itself on static

@@ -71,7 +71,7 @@ def lib() -> ctypes.CDLL:
         L.spqt_cb_packed_bytes.argtypes = [i64, i64, c.POINTER(sz)]
         L.spqt_cb_quantize.argtypes = [vp, i64, i64, vp, sz]
         L.spqt_cb_dequantize.argtypes = [vp, i64, i64, vp]
-        L.spqt_cb_gemv.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cb_gemv.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_cb_gemv_fused.argtypes = [vp, i64, i64, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         for name in EXPORTS[1:] + CB_EXPORTS:
             getattr(L, name).restype = i32
@@ -254,14 +254,15 @@ def spqt_cb_dequantize(packed: np.ndarray, M: int, K: int) -> np.ndarray:
 
 def spqt_cb_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
                  waves: int = 0) -> None:
-    """Column-block GEMV, batch 1: packed uint8 (device), x fp16[K], idx/count from spqt_gather or
-    None/None for the dense kernel, y fp32[M], workspace from new_workspace()."""
+    """Column-block GEMV: packed uint8 (device), x fp16[K] or [batch, K], idx/count from spqt_gather
+    or None/None for the dense kernel, y fp32[M] or [batch, M], workspace from new_workspace()."""
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
     yp = _dev(y, torch.float32, "y")
-    if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb_packed_bytes(M, K):
-        raise SpqtError("spqt_cb_gemv: x / y / packed sizes do not match M, K (batch 1 only)")
+    batch = 1 if x.dim() == 1 else x.shape[0]
+    if x.shape[-1] != K or y.numel() != batch * M or packed.numel() < spqt_cb_packed_bytes(M, K):
+        raise SpqtError("spqt_cb_gemv: x / y / packed sizes do not match M, K, batch")
     ip = cp = None
     if idx is not None:
         ip = _dev(idx, torch.int32, "idx")
@@ -270,7 +271,7 @@ def spqt_cb_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=Non
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
     cfg = LaunchCfg(int(splits), int(waves), 0)
-    _check(lib().spqt_cb_gemv(pp, M, K, xp, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
+    _check(lib().spqt_cb_gemv(pp, M, K, xp, batch, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
 
 
 def spqt_cb_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, stream=None,

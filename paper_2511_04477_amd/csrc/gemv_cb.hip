@@ -47,14 +47,18 @@ __device__ __forceinline__ float sum_over_columns(float v) {
 // spqt_gemv_fused does for the group layout): a wavefront's slice is a static range of
 // 64-column units; lane l tests column 64u + l, a ballot gives the kept set, mbcnt the rank,
 // and the kept columns are staged in rank order.
-template <int WAVES, bool DENSE, bool FUSED>
+// BATCH activation rows share the (union) index list and ONE pass over the weights; every row has
+// its own staged products, accumulators and bias sum.
+template <int WAVES, bool DENSE, bool FUSED, int BATCH>
 __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
     void *partials, int32_t *epochs, int K, int NC, int S, int T, int M, float thr) {
-    __shared__ uint32_t stage_off[WAVES][2][kPassCols];                            // byte offset of each column
-    __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][2][kPassCols][8];  // x * scale * 2^24 per block
-    __shared__ __attribute__((aligned(16))) float red[WAVES][kTileRows];
+    // One staging area per wavefront is enough: offsets are written and read back inside a FETCH
+    // stage, products inside a MULTIPLY stage, and a wavefront runs its stages one after the other.
+    __shared__ uint32_t stage_off[WAVES][kPassCols];                               // byte offset of each column
+    __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][BATCH][kPassCols][8];  // x * scale * 2^24 per block
+    __shared__ __attribute__((aligned(16))) float red[WAVES][BATCH][kTileRows];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -85,10 +89,14 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
 
     const uint8_t *row_base = packed + (size_t)t * NC * kCbChunkBytes;
 
-    float acc[32];      // this lane's 32 rows, summed over its columns of the whole slice
+    float acc[BATCH][32];   // this lane's 32 rows, summed over its columns of the whole slice
+    float bsum[BATCH];      // sum of the staged products this lane multiplied with (its block)
 #pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-    float bsum = 0.0f;  // sum of the staged products this lane multiplied with (its block)
+    for (int b = 0; b < BATCH; ++b) {
+        bsum[b] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) acc[b][i] = 0.0f;
+    }
 
     if (pos < end) {
         auto fetch_k = [&](int p) -> int {
@@ -101,7 +109,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
         // entries, this pass's x, scales and weights.  Lanes past the pass point at its first
         // column and later carry x = 0; past the end of the slice the stage degenerates to n = 0
         // with harmless re-reads.
-        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, uint32_t &xraw_out,
+        auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], int &n_out, uint32_t(&xraw_out)[BATCH],
                          u32x4 &sv_out, int &k_after) {
             const int left = end - p;
             const int n = left < 0 ? 0 : (left < kPassCols ? left : kPassCols);
@@ -110,13 +118,14 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
             const int kc = lane < n ? kk : k_first;
             const uint32_t chunk_off = (uint32_t)(kc >> 7) * (uint32_t)kCbChunkBytes;
             const uint32_t col = (uint32_t)(kc & (kGroup - 1));
-            xraw_out = x[kc];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) xraw_out[b] = x[(size_t)b * K + kc];
             sv_out = *reinterpret_cast<const u32x4 *>(row_base + (size_t)(chunk_off + col * 16u));
-            stage_off[wave][slot][lane] = chunk_off + (uint32_t)kCbScaleBytes + col * (uint32_t)kColBytes;
+            stage_off[wave][lane] = chunk_off + (uint32_t)kCbScaleBytes + col * (uint32_t)kColBytes;
             __builtin_amdgcn_wave_barrier();
             uint32_t off[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) off[u] = stage_off[wave][slot][u * 8 + cg] + seg16;
+            for (int u = 0; u < 8; ++u) off[u] = stage_off[wave][u * 8 + cg] + seg16;
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row_base + (size_t)off[u]));
@@ -124,36 +133,55 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
         };
 
         // MULTIPLY stage of a fetched pass: the lane that owns list entry `ent` stages the 8
-        // products x * s_b * 2^24 of its column (xf = x * 2^24, or 0 for a filler entry).
-        auto multiply = [&](int n, float xf, int ent, u32x4 sv, int slot, const u32x4(&w)[8]) {
-            f32x4 lo, hi;
-            lo.x = xf * half_bits_to_float(sv.x & 0xFFFFu);
-            lo.y = xf * half_bits_to_float(sv.x >> 16);
-            lo.z = xf * half_bits_to_float(sv.y & 0xFFFFu);
-            lo.w = xf * half_bits_to_float(sv.y >> 16);
-            hi.x = xf * half_bits_to_float(sv.z & 0xFFFFu);
-            hi.y = xf * half_bits_to_float(sv.z >> 16);
-            hi.z = xf * half_bits_to_float(sv.w & 0xFFFFu);
-            hi.w = xf * half_bits_to_float(sv.w >> 16);
-            f32x4 *dst = reinterpret_cast<f32x4 *>(stage_xs[wave][slot][ent]);
-            dst[0] = lo;
-            dst[1] = hi;
+        // products x * s_b * 2^24 of its column (xf = x * 2^24, or 0 for a filler entry), per row.
+        auto multiply = [&](int n, const float(&xf)[BATCH], int ent, u32x4 sv, int slot, const u32x4(&w)[8]) {
+            float sc[8];
+            sc[0] = half_bits_to_float(sv.x & 0xFFFFu);
+            sc[1] = half_bits_to_float(sv.x >> 16);
+            sc[2] = half_bits_to_float(sv.y & 0xFFFFu);
+            sc[3] = half_bits_to_float(sv.y >> 16);
+            sc[4] = half_bits_to_float(sv.z & 0xFFFFu);
+            sc[5] = half_bits_to_float(sv.z >> 16);
+            sc[6] = half_bits_to_float(sv.w & 0xFFFFu);
+            sc[7] = half_bits_to_float(sv.w >> 16);
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                f32x4 *dst = reinterpret_cast<f32x4 *>(stage_xs[wave][b][ent]);
+                dst[0] = f32x4{xf[b] * sc[0], xf[b] * sc[1], xf[b] * sc[2], xf[b] * sc[3]};
+                dst[1] = f32x4{xf[b] * sc[4], xf[b] * sc[5], xf[b] * sc[6], xf[b] * sc[7]};
+            }
             __builtin_amdgcn_wave_barrier();
-            float xl[8];
+            if (BATCH == 1) {
+                float xl[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) xl[u] = stage_xs[wave][slot][u * 8 + cg][seg];
-            fma_step<false>(w[0], xl[0], acc);
-            bsum += xl[0];
+                for (int u = 0; u < 8; ++u) xl[u] = stage_xs[wave][0][u * 8 + cg][seg];
+                fma_step<false>(w[0], xl[0], acc[0]);
+                bsum[0] += xl[0];
 #pragma unroll
-            for (int u = 1; u < 8; ++u)
-                if (u * 8 < n) {
-                    fma_step<false>(w[u], xl[u], acc);
-                    bsum += xl[u];
-                }
+                for (int u = 1; u < 8; ++u)
+                    if (u * 8 < n) {
+                        fma_step<false>(w[u], xl[u], acc[0]);
+                        bsum[0] += xl[u];
+                    }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (u == 0 || u * 8 < n) {
+#pragma unroll
+                        for (int b = 0; b < BATCH; ++b) {
+                            const float xl = stage_xs[wave][b][u * 8 + cg][seg];
+                            fma_step<false>(w[u], xl, acc[b]);
+                            bsum[b] += xl;
+                        }
+                    }
+            }
             __builtin_amdgcn_wave_barrier();
         };
-        auto multiply_list = [&](int n, uint32_t xraw, u32x4 sv, int slot, const u32x4(&w)[8]) {
-            multiply(n, lane < n ? half_bits_to_float(xraw) * kTwo24 : 0.0f, lane, sv, slot, w);
+        auto multiply_list = [&](int n, const uint32_t(&xraw)[BATCH], u32x4 sv, int slot, const u32x4(&w)[8]) {
+            float xf[BATCH];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) xf[b] = lane < n ? half_bits_to_float(xraw[b]) * kTwo24 : 0.0f;
+            multiply(n, xf, lane, sv, slot, w);
         };
 
         u32x4 wA[8], wB[8], svA, svB;
@@ -162,7 +190,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
             // FETCH stage of unit u (xr = this lane's x[64u + lane], requested one stage earlier):
             // threshold, rank, stage the offsets, request the next unit's x, this unit's scales
             // (every lane its own column's) and weights.
-            auto fetch_unit = [&](uint32_t xr, int u, int slot, u32x4(&w)[8], int &n_out, float &xf_out,
+            auto fetch_unit = [&](uint32_t xr, int u, int slot, u32x4(&w)[8], int &n_out, float(&xf_out)[BATCH],
                                   int &ent_out, u32x4 &sv_out, uint32_t &xr_next) {
                 const bool any = u < end;
                 const float xv = half_bits_to_float(xr);
@@ -183,20 +211,20 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
                 // kept columns go to entries 0..n-1 in ascending order; the other lanes fill entries
                 // n..63 with the unit's first kept column and x = 0
                 const int entry = keep ? rank : n + lane - rank;
-                stage_off[wave][slot][entry] =
+                stage_off[wave][entry] =
                     chunk_off + (uint32_t)kCbScaleBytes + (keep ? col_own : col_first) * (uint32_t)kColBytes;
                 __builtin_amdgcn_wave_barrier();
                 uint32_t off[8];
 #pragma unroll
-                for (int v = 0; v < 8; ++v) off[v] = stage_off[wave][slot][v * 8 + cg] + seg16;
+                for (int v = 0; v < 8; ++v) off[v] = stage_off[wave][v * 8 + cg] + seg16;
 #pragma unroll
                 for (int v = 0; v < 8; ++v)
                     w[v] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row_base + (size_t)off[v]));
                 n_out = n;
-                xf_out = keep ? xv * kTwo24 : 0.0f;
+                xf_out[0] = keep ? xv * kTwo24 : 0.0f;
                 ent_out = entry;
             };
-            float xfA, xfB;
+            float xfA[BATCH], xfB[BATCH];
             int entA, entB;
             uint32_t xa = x[pos * kPassCols + lane], xb;
             fetch_unit(xa, pos, 0, wA, nA, xfA, entA, svA, xb);
@@ -212,7 +240,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
                 pos = uA;
             }
         } else {
-            uint32_t xrA, xrB;
+            uint32_t xrA[BATCH], xrB[BATCH];
             int kA, kB;
             kA = fetch_k(pos);
             fetch(kA, pos, 0, wA, nA, xrA, svA, kB);
@@ -236,47 +264,65 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
 
     // fold the 8 column-lanes once and remove the bias.  The products are already in true units
     // (code * 2^-24 times x * s * 2^24); the staged values the bias sums are still scaled by 2^24.
-    float r4[4];
-    fold_columns(acc, r4);
-    const float bias = sum_over_columns(bsum) * (8.0f / kTwo24);
-    reinterpret_cast<f32x4 *>(red[wave])[8 * seg + cgr] =
-        f32x4{r4[0] - bias, r4[1] - bias, r4[2] - bias, r4[3] - bias};
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+        float r4[4];
+        fold_columns(acc[b], r4);
+        const float bias = sum_over_columns(bsum[b]) * (8.0f / kTwo24);
+        reinterpret_cast<f32x4 *>(red[wave][b])[8 * seg + cgr] =
+            f32x4{r4[0] - bias, r4[1] - bias, r4[2] - bias, r4[3] - bias};
+    }
     __syncthreads();
-    combine_block_row<WAVES, 1>(&red[0][0], tid, t, s, S, tag, partials, epochs, y, M);
+    combine_block_row<WAVES, BATCH>(&red[0][0][0], tid, t, s, S, tag, partials, epochs, y, M);
 }
 
-template <int WAVES>
-hipError_t launch_cb(int mode, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                     const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
-                     int K, int NC, int S, int T, int M, float thr) {
+template <int WAVES, int BATCH>
+hipError_t launch_cb_batch(int mode, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
+                           const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                           int K, int NC, int S, int T, int M) {
     const dim3 g(grid), b(WAVES * 64);
     if (mode == 0)        // index list
-        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M, thr);
-    else if (mode == 1)   // dense
-        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M, thr);
-    else                  // threshold inside the kernel
-        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M, thr);
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, BATCH>), g, b, 0, stream, packed, x, idx, count, y,
+                           partials, epochs, K, NC, S, T, M, 0.0f);
+    else                  // dense
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, BATCH>), g, b, 0, stream, packed, x, idx, count, y,
+                           partials, epochs, K, NC, S, T, M, 0.0f);
     return hipGetLastError();
 }
 
-int run_cb(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+template <int WAVES>
+hipError_t launch_cb(int mode, int batch, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
+                     const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                     int K, int NC, int S, int T, int M, float thr) {
+    if (mode == 2) {      // threshold inside the kernel (batch 1)
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true, 1>), dim3(grid), dim3(WAVES * 64), 0, stream, packed,
+                           x, idx, count, y, partials, epochs, K, NC, S, T, M, thr);
+        return hipGetLastError();
+    }
+    switch (batch) {
+        case 1: return launch_cb_batch<WAVES, 1>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
+        case 2: return launch_cb_batch<WAVES, 2>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
+        case 3: return launch_cb_batch<WAVES, 3>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
+        default: return launch_cb_batch<WAVES, 4>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
+    }
+}
+
+int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
            const int32_t *count_dev, float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
            void *stream, const spqt_launch_cfg *cfg) {
     if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
+    if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
         return SPQT_EALIGN;
     spqt_launch_cfg c;
-    if (int rc = spqt_default_cfg(M, K, 1, mode != 1, &c)) return rc;
+    if (int rc = spqt_default_cfg(M, K, batch, mode != 1, &c)) return rc;
     {
         // Measured on MI355X (sweep of S per shape, 50 % and dense): this kernel has no per-group
         // work, so on matrices large enough to be bandwidth-bound (>= 64 MB packed) fewer, longer
-        // slices win for the list-driven and dense kernels: about 256 workgroups instead of 512 / 1024.
+        // slices win for the batch-1 list-driven and dense kernels: about 256 workgroups instead of 512 / 1024.
         const int64_t T64 = M / kTileRows;
-        if (mode != 2 && (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20))
+        if (mode != 2 && batch == 1 && (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20))
             while (c.splits > 1 && (int64_t)c.splits * T64 > 256) c.splits /= 2;
     }
     if (cfg) {
@@ -287,7 +333,7 @@ int run_cb(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x
     if (c.splits < 1 || c.splits > SPQT_MAX_SPLITS) return SPQT_EINVAL;
     if (c.waves != 1 && c.waves != 2 && c.waves != 4) return SPQT_EINVAL;
     size_t need = 0;
-    spqt_workspace_bytes(M, K, 1, &need);
+    spqt_workspace_bytes(M, K, batch, &need);
     void *partials = nullptr;
     int32_t *epochs = nullptr;
     if (c.splits > 1) {
@@ -304,21 +350,21 @@ int run_cb(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
     switch (c.waves) {
-        case 1: err = launch_cb<1>(mode, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
-        case 2: err = launch_cb<2>(mode, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
-        default: err = launch_cb<4>(mode, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
+        case 1: err = launch_cb<1>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
+        case 2: err = launch_cb<2>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
+        default: err = launch_cb<4>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }
 
 }  // namespace
 
-extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
+extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
                             const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
                             void *workspace_dev, size_t workspace_bytes, void *stream,
                             const spqt_launch_cfg *cfg) {
     if (idx_dev && !count_dev) return SPQT_EINVAL;
-    return run_cb(idx_dev ? 0 : 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
+    return run_cb(idx_dev ? 0 : 1, batch, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
                   workspace_bytes, stream, cfg);
 }
 
@@ -326,6 +372,6 @@ extern "C" int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, 
                                   float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
                                   void *stream, const spqt_launch_cfg *cfg) {
     if (threshold != threshold) return SPQT_EINVAL;
-    return run_cb(2, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev,
+    return run_cb(2, 1, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev,
                   workspace_bytes, stream, cfg);
 }

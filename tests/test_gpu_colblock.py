@@ -115,6 +115,42 @@ def test_cb_fused_ties_empty_units_and_exact(gpu):
     assert np.array_equal(got.astype(np.float64), cb.gemv(qe, se, xi, 2.0))
 
 
+@pytest.mark.parametrize("batch", [2, 3, 4])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 4), (5, 2), (16, 4)])
+def test_cb_batch_rows_share_one_pass(gpu, batch, splits, waves):
+    """Batch 2-4: union index list, every row its own x values on the union set."""
+    torch, spqt, dev = gpu
+    M, K = 1024, 2048
+    W = make_fp_weights(M, K, 8900 + batch)
+    x_np = make_x(K, "laplace", 8901 + batch, batch=batch)
+    thr = 0.9
+    q, s = cb.quantize(W)
+    ref = cb.gemv(q, s, x_np, thr)
+    packed = torch.from_numpy(spqt.spqt_cb_quantize(W)).to(dev)
+    x = torch.from_numpy(x_np).to(dev)
+    idx = torch.empty(K, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    spqt.spqt_gather(x, thr, idx, cnt)
+    ws = spqt.new_workspace(M, K, batch)
+    y = torch.full((batch, M), float("nan"), dtype=torch.float32, device=dev)
+    spqt.spqt_cb_gemv(packed, M, K, x, idx, cnt, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), ref, f"cb batch {batch} sparse")
+    yd = torch.full((batch, M), float("nan"), dtype=torch.float32, device=dev)
+    spqt.spqt_cb_gemv(packed, M, K, x, None, None, yd, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    assert_close(yd.cpu().numpy(), cb.gemv(q, s, x_np, 0.0), f"cb batch {batch} dense")
+    # identical rows must reproduce the batch-1 result bit for bit
+    xi = torch.from_numpy(np.repeat(x_np[0:1], batch, axis=0).copy()).to(dev)
+    spqt.spqt_gather(xi, thr, idx, cnt)
+    spqt.spqt_cb_gemv(packed, M, K, xi, idx, cnt, y, ws, splits=splits, waves=waves)
+    y1 = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+    spqt.spqt_cb_gemv(packed, M, K, xi[0].contiguous(), idx, cnt, y1, spqt.new_workspace(M, K), splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        assert np.array_equal(y[b].cpu().numpy(), y1.cpu().numpy()), b
+
+
 @pytest.mark.parametrize("M,K", [(256, 128), (1024, 2048), (768, 640)])
 def test_cb_dense_kernel_and_threshold_zero(gpu, M, K):
     W = make_fp_weights(M, K, 8200 + M + K)

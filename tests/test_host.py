@@ -79,10 +79,11 @@ def test_colblock_bad_arguments():
     vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
     assert L.spqt_cb_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
     assert L.spqt_cb_quantize(None, 256, 128, vp(small), small.nbytes) == -1
-    assert L.spqt_cb_gemv(None, 256, 128, 16, None, None, 16, None, 0, None, None) == -1
-    assert L.spqt_cb_gemv(128, 100, 128, 16, None, None, 16, None, 0, None, None) == -2
-    assert L.spqt_cb_gemv(64, 256, 128, 16, None, None, 16, None, 0, None, None) == -3
-    assert L.spqt_cb_gemv(128, 256, 128, 16, 16, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cb_gemv(None, 256, 128, 16, 1, None, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cb_gemv(128, 100, 128, 16, 1, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb_gemv(64, 256, 128, 16, 1, None, None, 16, None, 0, None, None) == -3
+    assert L.spqt_cb_gemv(128, 256, 128, 16, 1, 16, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cb_gemv(128, 256, 128, 16, 5, None, None, 16, None, 0, None, None) == -2
 
 
 def test_status_strings():
