@@ -307,6 +307,28 @@ def colblock_rows(torch, spqt, use_graph, cpu):
                          "dense_GBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9, 1),
                          "speedup_vs_dense": round(t["us_dense"] / t["us_gemv"], 3),
                          "fused_speedup_vs_dense": round(t["us_dense"] / t["us_fused"], 3)})
+        if M == 28672:      # four activation rows sharing the union list (config 5's batch-4 case)
+            xb_np = make_x(K, "laplace", 9003 + M, 4)
+            thr = quantile_threshold(xb_np, 0.5)
+            xb = torch.from_numpy(xb_np).to(dev)
+            yb = torch.empty((4, M), dtype=torch.float32, device=dev)
+            wsb = spqt.new_workspace(M, K, 4)
+            spqt.spqt_gather(xb, thr, idx, cnt)
+            torch.cuda.synchronize()
+            n = int(cnt.item())
+            if cpu.enabled:
+                from_ref = []
+                spqt.spqt_cb_gemv(packed[0], M, K, xb, idx, cnt, yb, wsb)
+                torch.cuda.synchronize()
+                for b in range(4):      # the union set with each row's own values == that row with the others' dropped columns kept
+                    from_ref.append(cpu.colblock(W0_sample, np.where(np.any(~(np.abs(xb_np.astype(np.float32)) < np.float32(thr)), axis=0), xb_np[b], 0).astype(np.float16)[None, :], 0.0))
+                    if not cpu.close(yb[b].cpu().numpy()[sample], from_ref[b])[0]:
+                        print(f"bench.py: column-block batch-4 parity check FAILED (row {b})", file=sys.stderr)
+                        sys.exit(1)
+            t_s = time_sequence(torch, lambda i: spqt.spqt_cb_gemv(packed[i], M, K, xb, idx, cnt, yb, wsb), copies, max(copies * 4, 400), copies, use_graph)
+            t_d = time_sequence(torch, lambda i: spqt.spqt_cb_gemv(packed[i], M, K, xb, None, None, yb, wsb), copies, max(copies * 4, 400), copies, use_graph)
+            rows.append({"M": M, "K": K, "batch": 4, "sparsity_per_row": 0.5, "activations": L, "kept_frac": round(n / K, 4),
+                         "us_gemv": round(t_s, 3), "us_dense": round(t_d, 3), "speedup_vs_dense": round(t_d / t_s, 3)})
         del packed
         torch.cuda.empty_cache()
     return rows
