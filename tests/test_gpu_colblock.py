@@ -238,3 +238,55 @@ def test_cb_full_size_sampled_rows(gpu):
         assert_close(gotf[rows][None, :], cb.gemv(q, s, x, thr), f"cb {M}x{K} fused")
         del packed
         del W
+
+
+def test_cb_hip_graph_replay_matches_eager(gpu):
+    """A whole little sequence (workspace init, gather, list-driven, dense and one-launch column-block
+    GEMVs plus the group-layout one-launch GEMV on the same x) captured in one HIP graph and replayed
+    with eager work and synchronizations in between: every replay reproduces the eager results."""
+    torch, spqt, dev = gpu
+    from workloads import make_weights
+    import oracle
+    M, K = 1024, 2048
+    W = make_fp_weights(M, K, 9300)
+    gw = make_weights(M, K, 9301)
+    x_np = make_x(K, "laplace", 9302)
+    thr = quantile_threshold(x_np, 0.5)
+    packed = torch.from_numpy(spqt.spqt_cb_quantize(W)).to(dev)
+    gpacked = torch.from_numpy(spqt.spqt_pack(gw["q_rowmajor"], gw["scales"])).to(dev)
+    x = torch.from_numpy(x_np[0]).to(dev)
+    idx = torch.zeros(K, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    ys = [torch.zeros(M, dtype=torch.float32, device=dev) for _ in range(4)]
+    ws = spqt.new_workspace(M, K)
+
+    def run():
+        spqt.spqt_workspace_init(ws)          # a fill kernel, safe under capture
+        spqt.spqt_gather(x, thr, idx, cnt)
+        spqt.spqt_cb_gemv(packed, M, K, x, idx, cnt, ys[0], ws, splits=8)
+        spqt.spqt_cb_gemv(packed, M, K, x, None, None, ys[1], ws, splits=4)
+        spqt.spqt_cb_gemv_fused(packed, M, K, x, thr, ys[2], ws, splits=8)
+        spqt.spqt_gemv_fused(gpacked, M, K, x, thr, ys[3], ws, splits=8)
+
+    run()
+    torch.cuda.synchronize()
+    eager = [y.cpu().numpy().copy() for y in ys]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for rep in range(5):
+        for y in ys:
+            y.fill_(float("nan"))
+        idx.fill_(-1)
+        scratch = torch.randn(1 << 16, device=dev).sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for j, y in enumerate(ys):
+            assert np.array_equal(y.cpu().numpy(), eager[j]), (rep, j)
+        assert float(scratch) == float(scratch)
+    q, s = cb.quantize(W)
+    assert_close(eager[0][None, :], cb.gemv(q, s, x_np, thr), "graph: cb list")
+    assert_close(eager[1][None, :], cb.gemv(q, s, x_np, 0.0), "graph: cb dense")
+    assert_close(eager[2][None, :], cb.gemv(q, s, x_np, thr), "graph: cb fused")
+    assert_close(eager[3][None, :], oracle.gemv(gw["q_rowmajor"], gw["scales"], x_np, thr), "graph: group fused")
