@@ -270,6 +270,7 @@ def colblock_rows(torch, spqt, use_graph, cpu):
         tiles = np.unique(np.array([0, T // 2, T - 1]))
         sample = (tiles[:, None] * 256 + np.arange(256)[None, :]).ravel()
         W0_sample = W0[sample].copy()
+        packed_k0 = torch.from_numpy(spqt.spqt_cbk_quantize(W0)).to(dev) if cpu.enabled else None
         del W0
         idx = torch.empty(K, dtype=torch.int32, device=dev)
         cnt = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -329,6 +330,32 @@ def colblock_rows(torch, spqt, use_graph, cpu):
             t_d = time_sequence(torch, lambda i: spqt.spqt_cb_gemv(packed[i], M, K, xb, None, None, yb, wsb), copies, max(copies * 4, 400), copies, use_graph)
             rows.append({"M": M, "K": K, "batch": 4, "sparsity_per_row": 0.5, "activations": L, "kept_frac": round(n / K, 4),
                          "us_gemv": round(t_s, 3), "us_dense": round(t_d, 3), "speedup_vs_dense": round(t_d / t_s, 3)})
+        # K-quant flavour (6-bit block scales and minima under fp16 superblock scales): copy 0 quantized
+        # by the library and checked, then timed on the rotating buffers with their headers rewritten
+        # (finite superblock scales; any 6-bit fields and codes are valid)
+        x_np = make_x(K, L, 9002 + M)
+        thr = quantile_threshold(x_np, 0.5)
+        x = torch.from_numpy(x_np[0]).to(dev)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        torch.cuda.synchronize()
+        n = int(cnt.item())
+        if cpu.enabled:
+            ref = cpu.colblock_k(W0_sample, x_np, thr)
+            y.fill_(float("nan"))
+            spqt.spqt_cbk_gemv(packed_k0, M, K, x, idx, cnt, y, ws)
+            torch.cuda.synchronize()
+            if not cpu.close(y.cpu().numpy()[sample], ref)[0]:
+                print(f"bench.py: K-quant column-block parity check FAILED ({M}x{K})", file=sys.stderr)
+                sys.exit(1)
+            del packed_k0
+        for buf in packed:
+            hdr = buf.view(T * NC, spqt.CB_CHUNK_BYTES)[:, :2048].view(torch.float16).view(T * NC, 128, 8)
+            hdr[:, :, 0] = 0.0005
+            hdr[:, :, 1] = 0.0004
+        t_ks = time_sequence(torch, lambda i: spqt.spqt_cbk_gemv(packed[i], M, K, x, idx, cnt, y, ws), copies, max(copies * 4, 800), copies, use_graph)
+        t_kd = time_sequence(torch, lambda i: spqt.spqt_cbk_gemv(packed[i], M, K, x, None, None, y, ws), copies, max(copies * 4, 800), copies, use_graph)
+        rows.append({"M": M, "K": K, "format": "k-quant", "sparsity": 0.5, "activations": L, "kept_frac": round(n / K, 4),
+                     "us_gemv": round(t_ks, 3), "us_dense": round(t_kd, 3), "speedup_vs_dense": round(t_kd / t_ks, 3)})
         del packed
         torch.cuda.empty_cache()
     return rows
@@ -598,6 +625,11 @@ class CpuBaseline:
         from oracle import colblock as cb
         q, s = cb.quantize(W_rows)
         return cb.gemv(q, s, x_np, thr)[0]
+
+    def colblock_k(self, W_rows, x_np, thr):
+        """K-quant column-block reference on a subset of whole 256-row tiles of fp32 weights."""
+        from oracle import colblock_k as ck
+        return ck.gemv(ck.quantize(W_rows), x_np, thr)[0]
 
     @staticmethod
     def close(got, ref):

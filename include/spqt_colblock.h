@@ -76,6 +76,29 @@ int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void 
                        float *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
                        const spqt_launch_cfg *cfg);
 
+/* ---- K-quant flavour of the column-block layout --------------------------------------------
+ * Section 4.1.1: Q4_K - a superblock of 256 weights in eight blocks of 32, 4-bit codes, a 6-bit
+ * scale and a 6-bit minimum per block, and two 16-bit superblock scales; a weight is decoded as
+ * (d * sc_b) * q - dmin * m_b with q in 0..15.  Here the superblock is 256 consecutive rows of
+ * one column (Section 4.1.2).  The decode rule is the format's; the quantizer is this build's own
+ * plain min/max rule, in fp32 with round to nearest even:
+ *     lo_b = min(min w, 0), hi_b = max(max w, 0), scale_b = (hi_b - lo_b) / 15, min_b = 0 - lo_b
+ *     d = fp16(max_b scale_b / 63), dmin = fp16(max_b min_b / 63)
+ *     sc_b = clamp(rint(scale_b / d), 0, 63), m_b = clamp(rint(min_b / dmin), 0, 63)   (0 if d / dmin is 0)
+ *     q = clamp(rint((w + dmin*m_b) / (d*sc_b)), 0, 15)                                (0 if d*sc_b is 0)
+ * Packed form: the geometry of ZZ-CB32 (chunk (t, c) at (t*NC + c) * 18432); the 16 header bytes
+ * of column j at [16 j]: d (fp16), dmin (fp16), then a 96-bit little-endian bit string sc_0..sc_7,
+ * m_0..m_7 of 6 bits each; codes at [2048 + 128 j + i] as plain nibbles (low = row 2i). */
+int spqt_cbk_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_packed, size_t out_bytes);
+
+/* HOST.  w_out[m][k] = (d * sc_b) * q - dmin * m_b, float[M][K]. */
+int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
+
+/* DEVICE, async.  As spqt_cb_gemv with batch 1, on spqt_cbk_quantize's output. */
+int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+                  const int32_t *count_dev, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                  void *stream, const spqt_launch_cfg *cfg);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ integers:
 
   block b of a superblock (rows 32b..32b+31 of the column):
       lo_b = min(min w, 0)     hi_b = max(max w, 0)
-      scale_b = (hi_b - lo_b) / 15        min_b = -lo_b                       (both >= 0)
+      scale_b = (hi_b - lo_b) / 15        min_b = 0 - lo_b                    (both >= 0; a zero minimum is +0)
   superblock:
       d    = fp16( max_b scale_b / 63 )   dmin = fp16( max_b min_b / 63 )     (round to nearest even)
       sc_b = d    > 0 ? clamp(rint(scale_b / float(d)),    0, 63) : 0
@@ -65,7 +65,7 @@ def quantize(W: np.ndarray):
     lo = np.minimum(blocks.min(axis=1), f32(0))
     hi = np.maximum(blocks.max(axis=1), f32(0))
     scale_b = ((hi - lo) / f32(15)).astype(np.float32)             # [M/32, K]
-    min_b = (-lo).astype(np.float32)
+    min_b = (f32(0) - lo).astype(np.float32)
     sb = scale_b.reshape(M // TILE_ROWS, 8, K)
     mb = min_b.reshape(M // TILE_ROWS, 8, K)
     d = (sb.max(axis=1) / f32(63)).astype(np.float16)              # [M/256, K]

@@ -32,4 +32,7 @@ from .binding import (  # noqa: F401
     spqt_cb_dequantize,
     spqt_cb_gemv,
     spqt_cb_gemv_fused,
+    spqt_cbk_quantize,
+    spqt_cbk_dequantize,
+    spqt_cbk_gemv,
 )

@@ -30,7 +30,7 @@ EXPORTS = [
 
 
 CB_EXPORTS = ["spqt_cb_packed_bytes", "spqt_cb_quantize", "spqt_cb_dequantize", "spqt_cb_gemv",
-              "spqt_cb_gemv_fused"]
+              "spqt_cb_gemv_fused", "spqt_cbk_quantize", "spqt_cbk_dequantize", "spqt_cbk_gemv"]
 CB_CHUNK_BYTES = 18432
 
 
@@ -73,6 +73,9 @@ def lib() -> ctypes.CDLL:
         L.spqt_cb_dequantize.argtypes = [vp, i64, i64, vp]
         L.spqt_cb_gemv.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_cb_gemv_fused.argtypes = [vp, i64, i64, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cbk_quantize.argtypes = [vp, i64, i64, vp, sz]
+        L.spqt_cbk_dequantize.argtypes = [vp, i64, i64, vp]
+        L.spqt_cbk_gemv.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         for name in EXPORTS[1:] + CB_EXPORTS:
             getattr(L, name).restype = i32
         _lib = L
@@ -289,3 +292,45 @@ def spqt_cb_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace
     cfg = LaunchCfg(int(splits), int(waves), 0)
     _check(lib().spqt_cb_gemv_fused(pp, M, K, xp, float(threshold), yp, wp, wbytes, _stream_ptr(stream),
                                     ctypes.byref(cfg)))
+
+
+# ---------------------------------------------------------------- K-quant flavour (spqt_colblock.h)
+
+def spqt_cbk_quantize(w: np.ndarray) -> np.ndarray:
+    """fp32 [M, K] -> packed K-quant column-block bytes (host)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if w.ndim != 2:
+        raise SpqtError("spqt_cbk_quantize: need float32[M, K]")
+    M, K = w.shape
+    out = np.empty(spqt_cb_packed_bytes(M, K), dtype=np.uint8)
+    _check(lib().spqt_cbk_quantize(_np_ptr(w), M, K, _np_ptr(out), out.nbytes))
+    return out
+
+
+def spqt_cbk_dequantize(packed: np.ndarray, M: int, K: int) -> np.ndarray:
+    p = np.ascontiguousarray(packed, dtype=np.uint8)
+    if p.nbytes < spqt_cb_packed_bytes(M, K):
+        raise SpqtError("spqt_cbk_dequantize: packed buffer too small")
+    out = np.empty((M, K), dtype=np.float32)
+    _check(lib().spqt_cbk_dequantize(_np_ptr(p), M, K, _np_ptr(out)))
+    return out
+
+
+def spqt_cbk_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
+                  waves: int = 0) -> None:
+    """K-quant column-block GEMV, batch 1 (idx/count None/None for the dense kernel)."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp = _dev(y, torch.float32, "y")
+    if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb_packed_bytes(M, K):
+        raise SpqtError("spqt_cbk_gemv: x / y / packed sizes do not match M, K (batch 1 only)")
+    ip = cp = None
+    if idx is not None:
+        ip = _dev(idx, torch.int32, "idx")
+        cp = _dev(count, torch.int32, "count")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    cfg = LaunchCfg(int(splits), int(waves), 0)
+    _check(lib().spqt_cbk_gemv(pp, M, K, xp, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))

@@ -49,7 +49,13 @@ __device__ __forceinline__ float sum_over_columns(float v) {
 // and the kept columns are staged in rank order.
 // BATCH activation rows share the (union) index list and ONE pass over the weights; every row has
 // its own staged products, accumulators and bias sum.
-template <int WAVES, bool DENSE, bool FUSED, int BATCH>
+//
+// KQ: the K-quant flavour of the format (Section 4.1.1): the 16 header bytes of a column hold two
+// fp16 superblock scales d, dmin and eight 6-bit block scales and minima; a weight is
+// (d * sc_b) * q - dmin * m_b with a plain code q in 0..15.  The owner of a list entry decodes the
+// header into the 8 effective scales and the 8 effective minima of its column, both times x; the
+// multiply is unchanged, and the minima take the place of the offset-binary bias.
+template <int WAVES, bool DENSE, bool FUSED, int BATCH, bool KQ = false>
 __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
@@ -58,6 +64,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     // stage, products inside a MULTIPLY stage, and a wavefront runs its stages one after the other.
     __shared__ uint32_t stage_off[WAVES][kPassCols];                               // byte offset of each column
     __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][BATCH][kPassCols][8];  // x * scale * 2^24 per block
+    __shared__ __attribute__((aligned(16))) float stage_xm[KQ ? WAVES : 1][BATCH][KQ ? kPassCols : 1][8];  // x * minimum * 2^24
     __shared__ __attribute__((aligned(16))) float red[WAVES][BATCH][kTileRows];
 
     const int tid = threadIdx.x;
@@ -135,33 +142,58 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
         // MULTIPLY stage of a fetched pass: the lane that owns list entry `ent` stages the 8
         // products x * s_b * 2^24 of its column (xf = x * 2^24, or 0 for a filler entry), per row.
         auto multiply = [&](int n, const float(&xf)[BATCH], int ent, u32x4 sv, int slot, const u32x4(&w)[8]) {
-            float sc[8];
-            sc[0] = half_bits_to_float(sv.x & 0xFFFFu);
-            sc[1] = half_bits_to_float(sv.x >> 16);
-            sc[2] = half_bits_to_float(sv.y & 0xFFFFu);
-            sc[3] = half_bits_to_float(sv.y >> 16);
-            sc[4] = half_bits_to_float(sv.z & 0xFFFFu);
-            sc[5] = half_bits_to_float(sv.z >> 16);
-            sc[6] = half_bits_to_float(sv.w & 0xFFFFu);
-            sc[7] = half_bits_to_float(sv.w >> 16);
+            float sc[8], mn[8];
+            if (KQ) {
+                const float d = half_bits_to_float(sv.x & 0xFFFFu), dm = half_bits_to_float(sv.x >> 16);
+                const uint64_t lo = (uint64_t)sv.y | ((uint64_t)sv.z << 32);
+                const uint32_t hi = sv.w;
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    const int ps = 6 * b, pm = 48 + 6 * b;      // compile-time bit positions
+                    const uint32_t fs = (uint32_t)(lo >> ps) & 63u;
+                    uint32_t fm;
+                    if (pm + 6 <= 64) fm = (uint32_t)(lo >> pm) & 63u;
+                    else if (pm >= 64) fm = (hi >> (pm - 64)) & 63u;
+                    else fm = ((uint32_t)(lo >> pm) | (hi << (64 - pm))) & 63u;
+                    sc[b] = d * (float)fs;
+                    mn[b] = dm * (float)fm;
+                }
+            } else {
+                sc[0] = half_bits_to_float(sv.x & 0xFFFFu);
+                sc[1] = half_bits_to_float(sv.x >> 16);
+                sc[2] = half_bits_to_float(sv.y & 0xFFFFu);
+                sc[3] = half_bits_to_float(sv.y >> 16);
+                sc[4] = half_bits_to_float(sv.z & 0xFFFFu);
+                sc[5] = half_bits_to_float(sv.z >> 16);
+                sc[6] = half_bits_to_float(sv.w & 0xFFFFu);
+                sc[7] = half_bits_to_float(sv.w >> 16);
+            }
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
                 f32x4 *dst = reinterpret_cast<f32x4 *>(stage_xs[wave][b][ent]);
                 dst[0] = f32x4{xf[b] * sc[0], xf[b] * sc[1], xf[b] * sc[2], xf[b] * sc[3]};
                 dst[1] = f32x4{xf[b] * sc[4], xf[b] * sc[5], xf[b] * sc[6], xf[b] * sc[7]};
+                if (KQ) {
+                    f32x4 *dm4 = reinterpret_cast<f32x4 *>(stage_xm[wave][b][ent]);
+                    dm4[0] = f32x4{xf[b] * mn[0], xf[b] * mn[1], xf[b] * mn[2], xf[b] * mn[3]};
+                    dm4[1] = f32x4{xf[b] * mn[4], xf[b] * mn[5], xf[b] * mn[6], xf[b] * mn[7]};
+                }
             }
             __builtin_amdgcn_wave_barrier();
             if (BATCH == 1) {
                 float xl[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) xl[u] = stage_xs[wave][0][u * 8 + cg][seg];
+                float xb[8];     // what step u adds to the bias sum: the product itself, or x * minimum
+#pragma unroll
+                for (int u = 0; u < 8; ++u) xb[u] = KQ ? stage_xm[wave][0][u * 8 + cg][seg] : xl[u];
                 fma_step<false>(w[0], xl[0], acc[0]);
-                bsum[0] += xl[0];
+                bsum[0] += xb[0];
 #pragma unroll
                 for (int u = 1; u < 8; ++u)
                     if (u * 8 < n) {
                         fma_step<false>(w[u], xl[u], acc[0]);
-                        bsum[0] += xl[u];
+                        bsum[0] += xb[u];
                     }
             } else {
 #pragma unroll
@@ -171,7 +203,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
                         for (int b = 0; b < BATCH; ++b) {
                             const float xl = stage_xs[wave][b][u * 8 + cg][seg];
                             fma_step<false>(w[u], xl, acc[b]);
-                            bsum[b] += xl;
+                            bsum[b] += KQ ? stage_xm[wave][b][u * 8 + cg][seg] : xl;
                         }
                     }
             }
@@ -268,7 +300,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     for (int b = 0; b < BATCH; ++b) {
         float r4[4];
         fold_columns(acc[b], r4);
-        const float bias = sum_over_columns(bsum[b]) * (8.0f / kTwo24);
+        const float bias = sum_over_columns(bsum[b]) * ((KQ ? 1.0f : 8.0f) / kTwo24);
         reinterpret_cast<f32x4 *>(red[wave][b])[8 * seg + cgr] =
             f32x4{r4[0] - bias, r4[1] - bias, r4[2] - bias, r4[3] - bias};
     }
@@ -294,6 +326,15 @@ template <int WAVES>
 hipError_t launch_cb(int mode, int batch, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                      const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
                      int K, int NC, int S, int T, int M, float thr) {
+    if (mode == 3 || mode == 4) {      // K-quant flavour, batch 1: index list / dense
+        if (mode == 3)
+            hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, 0.0f);
+        else
+            hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
+                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, 0.0f);
+        return hipGetLastError();
+    }
     if (mode == 2) {      // threshold inside the kernel (batch 1)
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true, 1>), dim3(grid), dim3(WAVES * 64), 0, stream, packed,
                            x, idx, count, y, partials, epochs, K, NC, S, T, M, thr);
@@ -316,7 +357,7 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
         return SPQT_EALIGN;
     spqt_launch_cfg c;
-    if (int rc = spqt_default_cfg(M, K, batch, mode != 1, &c)) return rc;
+    if (int rc = spqt_default_cfg(M, K, batch, mode != 1 && mode != 4, &c)) return rc;
     {
         // Measured on MI355X (sweep of S per shape, 50 % and dense): this kernel has no per-group
         // work, so on matrices large enough to be bandwidth-bound (>= 64 MB packed) fewer, longer
@@ -373,5 +414,14 @@ extern "C" int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, 
                                   void *stream, const spqt_launch_cfg *cfg) {
     if (threshold != threshold) return SPQT_EINVAL;
     return run_cb(2, 1, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev,
+                  workspace_bytes, stream, cfg);
+}
+
+extern "C" int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
+                             const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                             void *workspace_dev, size_t workspace_bytes, void *stream,
+                             const spqt_launch_cfg *cfg) {
+    if (idx_dev && !count_dev) return SPQT_EINVAL;
+    return run_cb(idx_dev ? 3 : 4, 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
                   workspace_bytes, stream, cfg);
 }

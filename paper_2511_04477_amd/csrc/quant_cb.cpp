@@ -160,3 +160,131 @@ extern "C" int spqt_cb_dequantize(const void *packed, int64_t M, int64_t K, floa
     });
     return SPQT_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// K-quant flavour (paper Section 4.1.1: Q4_K's superblock of eight 32-weight blocks with 6-bit block
+// scales and minima under two 16-bit superblock scales), on the same column-block geometry.  The
+// decode rule is the format's; the min/max quantizer is this build's own.  See spqt_colblock.h.
+
+namespace {
+
+// the 96-bit field string of a superblock header: sc_0..sc_7 then m_0..m_7, 6 bits each
+void put_fields(uint8_t *dst12, const int *sc, const int *m) {
+    uint64_t lo = 0, hi = 0;      // bits 0..63 and 64..95
+    auto put = [&](int pos, uint64_t v) {
+        if (pos < 64) {
+            lo |= v << pos;
+            if (pos > 58) hi |= v >> (64 - pos);
+        } else {
+            hi |= v << (pos - 64);
+        }
+    };
+    for (int b = 0; b < 8; ++b) put(6 * b, (uint64_t)sc[b]);
+    for (int b = 0; b < 8; ++b) put(48 + 6 * b, (uint64_t)m[b]);
+    for (int i = 0; i < 8; ++i) dst12[i] = (uint8_t)(lo >> (8 * i));
+    for (int i = 0; i < 4; ++i) dst12[8 + i] = (uint8_t)(hi >> (8 * i));
+}
+
+void get_fields(const uint8_t *src12, int *sc, int *m) {
+    uint64_t lo = 0, hi = 0;
+    for (int i = 0; i < 8; ++i) lo |= (uint64_t)src12[i] << (8 * i);
+    for (int i = 0; i < 4; ++i) hi |= (uint64_t)src12[8 + i] << (8 * i);
+    auto get = [&](int pos) -> int {
+        uint64_t v = pos < 64 ? (lo >> pos) : (hi >> (pos - 64));
+        if (pos < 64 && pos > 58) v |= hi << (64 - pos);
+        return (int)(v & 63u);
+    };
+    for (int b = 0; b < 8; ++b) sc[b] = get(6 * b);
+    for (int b = 0; b < 8; ++b) m[b] = get(48 + 6 * b);
+}
+
+}  // namespace
+
+extern "C" int spqt_cbk_quantize(const float *w, int64_t M, int64_t K, void *out_packed, size_t out_bytes) {
+    if (!w || !out_packed) return SPQT_EINVAL;
+    size_t need = 0;
+    if (int rc = spqt_cb_packed_bytes(M, K, &need)) return rc;
+    if (out_bytes < need) return SPQT_ESIZE;
+    const int64_t T = M / kTileRows, NC = K / kGroup;
+    uint8_t *out = (uint8_t *)out_packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        std::vector<float> se_v((size_t)kBlocksPerTile * kGroup), me_v((size_t)kBlocksPerTile * kGroup);
+        for (int64_t c = 0; c < NC; ++c) {
+            uint8_t *chunk = out + (size_t)(t * NC + c) * kCbChunkBytes;
+            const float *tile = w + (size_t)t * kTileRows * K + (size_t)c * kGroup;
+            for (int j = 0; j < kGroup; ++j) {
+                float scale_b[kBlocksPerTile], min_b[kBlocksPerTile];
+                float smax = 0.0f, mmax = 0.0f;
+                for (int b = 0; b < kBlocksPerTile; ++b) {
+                    float lo = 0.0f, hi = 0.0f;
+                    for (int r = 0; r < kBlockRows; ++r) {
+                        const float v = tile[(size_t)(b * kBlockRows + r) * K + j];
+                        lo = std::min(lo, v);
+                        hi = std::max(hi, v);
+                    }
+                    scale_b[b] = (hi - lo) / 15.0f;
+                    min_b[b] = 0.0f - lo;      // +0 for an all-zero block
+                    smax = std::max(smax, scale_b[b]);
+                    mmax = std::max(mmax, min_b[b]);
+                }
+                const uint16_t dh = float_to_half_bits(smax / 63.0f), mh = float_to_half_bits(mmax / 63.0f);
+                const float d = half_bits_to_float(dh), dm = half_bits_to_float(mh);
+                int sc[kBlocksPerTile], mq[kBlocksPerTile];
+                for (int b = 0; b < kBlocksPerTile; ++b) {
+                    sc[b] = d > 0.0f ? (int)std::min(63.0f, std::max(0.0f, std::nearbyintf(scale_b[b] / d))) : 0;
+                    mq[b] = dm > 0.0f ? (int)std::min(63.0f, std::max(0.0f, std::nearbyintf(min_b[b] / dm))) : 0;
+                    se_v[(size_t)b * kGroup + j] = d * (float)sc[b];
+                    me_v[(size_t)b * kGroup + j] = dm * (float)mq[b];
+                }
+                uint8_t *head = chunk + 16 * j;
+                head[0] = (uint8_t)(dh & 0xFF);
+                head[1] = (uint8_t)(dh >> 8);
+                head[2] = (uint8_t)(mh & 0xFF);
+                head[3] = (uint8_t)(mh >> 8);
+                put_fields(head + 4, sc, mq);
+            }
+            uint8_t *codes = chunk + kCbScaleBytes;
+            for (int r = 0; r < kTileRows; ++r) {
+                const float *row = tile + (size_t)r * K;
+                const float *se = &se_v[(size_t)(r / kBlockRows) * kGroup], *me = &me_v[(size_t)(r / kBlockRows) * kGroup];
+                for (int j = 0; j < kGroup; ++j) {
+                    int q = 0;
+                    if (se[j] > 0.0f) {
+                        const float v = std::nearbyintf((row[j] + me[j]) / se[j]);
+                        q = (int)std::min(15.0f, std::max(0.0f, v));
+                    }
+                    uint8_t &byte = codes[128 * j + r / 2];
+                    byte = (r & 1) ? (uint8_t)((byte & 0x0F) | (q << 4)) : (uint8_t)q;
+                }
+            }
+        }
+    });
+    return SPQT_OK;
+}
+
+extern "C" int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, float *w_out) {
+    if (!packed || !w_out) return SPQT_EINVAL;
+    if (int rc = check_cb_shape(M, K)) return rc;
+    const int64_t T = M / kTileRows, NC = K / kGroup;
+    const uint8_t *in = (const uint8_t *)packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        for (int64_t c = 0; c < NC; ++c) {
+            const uint8_t *chunk = in + (size_t)(t * NC + c) * kCbChunkBytes;
+            float *tile = w_out + (size_t)t * kTileRows * K + (size_t)c * kGroup;
+            for (int j = 0; j < kGroup; ++j) {
+                const uint8_t *head = chunk + 16 * j;
+                const float d = half_bits_to_float((uint16_t)(head[0] | (head[1] << 8)));
+                const float dm = half_bits_to_float((uint16_t)(head[2] | (head[3] << 8)));
+                int sc[kBlocksPerTile], mq[kBlocksPerTile];
+                get_fields(head + 4, sc, mq);
+                for (int r = 0; r < kTileRows; ++r) {
+                    const int b = r / kBlockRows;
+                    const uint8_t byte = chunk[kCbScaleBytes + 128 * j + r / 2];
+                    const int q = (byte >> (4 * (r & 1))) & 15;
+                    tile[(size_t)r * K + j] = (d * (float)sc[b]) * (float)q - dm * (float)mq[b];
+                }
+            }
+        }
+    });
+    return SPQT_OK;
+}

@@ -290,3 +290,94 @@ def test_cb_hip_graph_replay_matches_eager(gpu):
     assert_close(eager[1][None, :], cb.gemv(q, s, x_np, 0.0), "graph: cb dense")
     assert_close(eager[2][None, :], cb.gemv(q, s, x_np, thr), "graph: cb fused")
     assert_close(eager[3][None, :], oracle.gemv(gw["q_rowmajor"], gw["scales"], x_np, thr), "graph: group fused")
+
+
+# ------------------------------------------------------------------ K-quant flavour (spqt_cbk_*)
+
+def gpu_cbk_gemv(gpu, W, x_np, thr, dense=False, splits=0, waves=0, packed=None):
+    torch, spqt, dev = gpu
+    M, K = W.shape
+    if packed is None:
+        packed = torch.from_numpy(spqt.spqt_cbk_quantize(W)).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)[0]
+    y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K)
+    if dense:
+        spqt.spqt_cbk_gemv(packed, M, K, x, None, None, y, ws, splits=splits, waves=waves)
+    else:
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        spqt.spqt_cbk_gemv(packed, M, K, x, idx, cnt, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()[None, :]
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 1024), (1024, 4096), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (7, 2), (16, 4), (64, 1)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_cbk_sparse_gemv(gpu, M, K, splits, waves, sparsity):
+    from oracle import colblock_k as ck
+    W = make_fp_weights(M, K, 9400 + M + K)
+    W += np.float32(0.01)          # off-centre weights: the minima matter
+    x = make_x(K, "laplace", 9401 + M + K)
+    thr = quantile_threshold(x, sparsity)
+    say(f"cbk M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    ref = ck.gemv(ck.quantize(W), x, thr)
+    assert_close(gpu_cbk_gemv(gpu, W, x, thr, splits=splits, waves=waves), ref, "cbk sparse")
+
+
+def test_cbk_dense_exact_and_probe(gpu):
+    from oracle import colblock_k as ck
+    torch, spqt, dev = gpu
+    M, K = 512, 384
+    W = make_fp_weights(M, K, 9500) - np.float32(0.02)
+    p = ck.quantize(W)
+    x = make_x(K, "normal", 9501)
+    for splits, waves in [(0, 0), (3, 4)]:
+        d = gpu_cbk_gemv(gpu, W, x, 0.0, dense=True, splits=splits, waves=waves)
+        z = gpu_cbk_gemv(gpu, W, x, 0.0, dense=False, splits=splits, waves=waves)
+        assert_close(d, ck.gemv(p, x, 0.0), "cbk dense")
+        assert np.array_equal(d, z)
+    # column probe: x = c e_k gives c * value[:, k] exactly (one product, one subtraction per row)
+    Wd = ck.dequant(p)
+    packed = torch.from_numpy(spqt.spqt_cbk_quantize(W)).to(dev)
+    for k in list(range(0, K, 11)) + [K - 1]:
+        e = np.zeros((1, K), dtype=np.float16)
+        e[0, k] = 2.0
+        got = gpu_cbk_gemv(gpu, W, e, 1.0, packed=packed)[0].astype(np.float64)
+        assert np.array_equal(got, (2.0 * Wd[:, k]).astype(np.float32).astype(np.float64)), k
+    # exactly representable superblocks and small integer x: bit-exact whatever the summation order
+    rng = np.random.default_rng(9502)
+    T = M // 256
+    d16 = (2.0 ** rng.integers(-10, -6, size=(T, K))).astype(np.float32)
+    sc = rng.integers(16, 64, size=(M // 32, K)); sc.reshape(T, 8, K)[:, 0, :] = 63
+    mq = rng.integers(0, 64, size=(M // 32, K)); mq.reshape(T, 8, K)[:, 1, :] = 63
+    q = rng.integers(0, 16, size=(M, K)); q.reshape(M // 32, 32, K)[:, 0, :] = 0; q.reshape(M // 32, 32, K)[:, 1, :] = 15
+    se = np.repeat(d16, 8, axis=0) * sc
+    me = np.repeat(d16 / 4, 8, axis=0) * mq
+    We = (np.repeat(se, 32, axis=0) * q - np.repeat(me, 32, axis=0)).astype(np.float32)
+    xi = rng.integers(-4, 5, size=(1, K)).astype(np.float16)
+    pe = ck.quantize(We)
+    assert np.array_equal(pe["q"], q)
+    got = gpu_cbk_gemv(gpu, We, xi, 2.0)
+    assert np.array_equal(got.astype(np.float64), ck.gemv(pe, xi, 2.0))
+
+
+def test_cbk_full_size_sampled_tiles(gpu):
+    from oracle import colblock_k as ck
+    torch, spqt, dev = gpu
+    for M, K in [(4096, 4096), (28672, 8192)]:
+        say(f"cbk full size {M}x{K}")
+        W = make_fp_weights(M, K, 9600 + M) + np.float32(0.005)
+        x = make_x(K, "laplace", 9601 + M)
+        thr = quantile_threshold(x, 0.5)
+        packed = torch.from_numpy(spqt.spqt_cbk_quantize(W)).to(dev)
+        got = gpu_cbk_gemv(gpu, W, x, thr, packed=packed)[0]
+        gotd = gpu_cbk_gemv(gpu, W, x, thr, dense=True, packed=packed)[0]
+        tiles = np.unique(np.array([0, M // 512, M // 256 - 1]))
+        rows = (tiles[:, None] * 256 + np.arange(256)[None, :]).ravel()
+        p = ck.quantize(W[rows])
+        assert_close(got[rows][None, :], ck.gemv(p, x, thr), f"cbk {M}x{K} sparse")
+        assert_close(gotd[rows][None, :], ck.gemv(p, x, 0.0), f"cbk {M}x{K} dense")
+        del W, packed

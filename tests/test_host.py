@@ -44,7 +44,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_colblock_header_symbols_are_exported():
     L = spqt.lib()
-    names = [n for n in declared_functions("spqt_colblock.h") if n.startswith("spqt_cb_")]
+    names = [n for n in declared_functions("spqt_colblock.h") if n.startswith("spqt_cb")]
     assert set(names) == set(spqt.CB_EXPORTS)
     for n in names:
         assert getattr(L, n) is not None
@@ -69,6 +69,27 @@ def test_colblock_quantizer_matches_oracle_bit_exact(M, K):
     assert np.array_equal(back.astype(np.float64), cb.dequant(q, s))
 
 
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 384), (1024, 512)])
+def test_kquant_quantizer_matches_oracle_bit_exact(M, K):
+    """K-quant flavour: every header bit and every code of the library's quantizer equals the
+    oracle's (independent NumPy code, same fp32 rule); the library's dequantizer gives the
+    oracle's values rounded to fp32."""
+    from oracle import colblock_k as ck
+    from workloads import make_fp_weights
+    W = make_fp_weights(M, K, 600 + M + K)
+    W[:, 3] = 0.0                                          # a zero superblock
+    W[0:32, 7] = np.abs(W[0:32, 7]) + 0.01                 # all-positive block
+    W[32:64, 7] = -np.abs(W[32:64, 7]) - 0.01              # all-negative block
+    W[64:96, 11] = np.float32(1e-9)                        # scale underflows to zero
+    got = spqt.spqt_cbk_quantize(W)
+    p = ck.quantize(W)
+    want = ck.pack(p)
+    assert got.nbytes == want.nbytes == spqt.spqt_cb_packed_bytes(M, K)
+    assert np.array_equal(got, want)
+    back = spqt.spqt_cbk_dequantize(got, M, K)
+    assert np.array_equal(back, ck.dequant(p).astype(np.float32))
+
+
 def test_colblock_bad_arguments():
     L = spqt.lib()
     out = ctypes.c_size_t()
@@ -84,6 +105,10 @@ def test_colblock_bad_arguments():
     assert L.spqt_cb_gemv(64, 256, 128, 16, 1, None, None, 16, None, 0, None, None) == -3
     assert L.spqt_cb_gemv(128, 256, 128, 16, 1, 16, None, 16, None, 0, None, None) == -1
     assert L.spqt_cb_gemv(128, 256, 128, 16, 5, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cbk_quantize(None, 256, 128, vp(small), small.nbytes) == -1
+    assert L.spqt_cbk_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
+    assert L.spqt_cbk_gemv(None, 256, 128, 16, None, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cbk_gemv(128, 256, 100, 16, None, None, 16, None, 0, None, None) == -2
 
 
 def test_status_strings():

@@ -64,7 +64,7 @@ def test_special_blocks():
     W[0:32, 9] = np.abs(W[0:32, 9]) + 0.01          # an all-positive block: minimum 0
     W[32:64, 9] = -np.abs(W[32:64, 9]) - 0.01       # an all-negative block: its top code stands for <= 0
     p = ck.quantize(W)
-    assert p["d"][0, 5] == 0 and p["dmin"][0, 5] == 0 and np.all(p["q"][:, 5] == 0)
+    assert p["d"].view(np.uint16)[0, 5] == 0 and p["dmin"].view(np.uint16)[0, 5] == 0 and np.all(p["q"][:, 5] == 0)
     assert np.all(ck.dequant(p)[:, 5] == 0)
     assert p["m"][0, 9] == 0
     d = ck.dequant(p)
