@@ -243,7 +243,7 @@ def ablations(torch, spqt, use_graph, cpu):
     return rows
 
 
-def colblock_rows(torch, spqt, use_graph, cpu):
+def colblock_rows(torch, spqt, use_graph, cpu, full=True):
     """The column-block variant of the layout (the paper's own grouping, Section 4.1.2: 32-row
     blocks along a column, scales skipped with their column) on the headline and 70B shapes.
     Copy 0 is quantized from seeded fp32 weights by the library and checked against the
@@ -253,8 +253,9 @@ def colblock_rows(torch, spqt, use_graph, cpu):
     dev = torch.device("cuda:0")
     rows = []
     L, C = "laplace", "laplace_clustered"     # C: 7 of 8 kept columns in the first half of K
-    for M, K, sps in ((4096, 4096, ((0.5, L),)), (28672, 8192, ((0.3, L), (0.5, L), (0.7, L), (0.5, C))),
-                      (8192, 28672, ((0.5, L),))):
+    shapes = ((4096, 4096, ((0.5, L),)), (28672, 8192, ((0.3, L), (0.5, L), (0.7, L), (0.5, C))),
+              (8192, 28672, ((0.5, L),)))
+    for M, K, sps in (shapes if full else shapes[:1]):
         pbytes = spqt.spqt_cb_packed_bytes(M, K)
         copies = max(2, -(-ROTATE_BYTES // pbytes))
         T, NC = M // 256, K // 128
@@ -842,6 +843,8 @@ def main():
                 del w
                 torch.cuda.empty_cache()
         out["sweep"] = sweep
+        if not args.full:       # the paper's own grouping on the headline shape (all shapes with --full)
+            out["colblock_layout"] = colblock_rows(torch, spqt, use_graph, cpu, full=False)
         if args.full:
             # decoder-layer sequences: Llama-2-7B MLP over 16 layers (config 3), Llama-3-8B full layer
             # over 32 layers (config 4); spqt_gather time included
