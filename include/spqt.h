@@ -17,8 +17,10 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device calls
  *     are asynchronous on that stream and never read device results back to the host:
  *     the kept count n_ns stays on the device between spqt_gather and spqt_gemv.
- *   - Shapes: W is M (outputs) x K (inputs).  M % 256 == 0, K % 128 == 0, group == 128,
- *     batch in 1..4; anything else is SPQT_ESHAPE.
+ *   - Shapes: W is M (outputs) x K (inputs).  1 <= M <= 2^24, K % 128 == 0, group == 128,
+ *     batch in 1..4; anything else is SPQT_ESHAPE.  M need not be a multiple of the block
+ *     height: the last block-row is zero-padded in the packed form (the paper's claim of
+ *     generality, Section 4.1.2, fixes no rule for a ragged edge; padding is this build's).
  *
  * Packed layout ("zigzag", paper Section 4.1.2: weights are grouped along a column - one
  * block is 256 consecutive rows of ONE column - and the blocks are stored row-major: all
@@ -26,13 +28,14 @@
  * (the source is row-major group-128 int4 and is not requantized), so the unit of storage
  * is one chunk per (block-row t, group g):
  *
- *     T = M/256, NG = K/128, chunk (t, g) at byte offset (t*NG + g) * 16896
+ *     T = ceil(M/256), NG = K/128, chunk (t, g) at byte offset (t*NG + g) * 16896
  *       bytes [0, 512)          fp16 bits of scale[256t + r][g], r = 0..255, little endian
  *       bytes [512 + 128c + j]  column k = 128g + c, c = 0..127, j = 0..127:
  *                               low nibble  = code of row 256t + 2j
  *                               high nibble = code of row 256t + 2j + 1
  *                               stored code = (q + 8) & 15  (offset binary, q in [-8, 7])
- *     total = T*NG*16896 = M*K/2 + M*NG*2 bytes, no padding.
+ *     rows M .. 256T-1 (when M % 256 != 0): stored code 8 (weight 0) and scale bits 0
+ *     total = T*NG*16896 bytes (= M*K/2 + M*NG*2 when M % 256 == 0).
  *
  * One activation column's 256 weights of a block-row are therefore one aligned 128-byte
  * run (a skipped column is a skipped cache line), and the scales of its group sit at the

@@ -15,15 +15,17 @@
  *            q = 0 for every weight of a block whose scale rounds to zero
  *     value  q * float(s)
  *
- * Packed form ("ZZ-CB32"): T = M/256 superblock-rows, NC = K/128 chunks of 128 columns;
+ * Packed form ("ZZ-CB32"): T = ceil(M/256) superblock-rows, NC = K/128 chunks of 128 columns;
  * chunk (t, c) at byte offset (t*NC + c) * 18432:
  *     bytes [16 j + 2 b], j = 0..127, b = 0..7   fp16 scale (little endian) of rows
  *                                                256t + 32b .. +31 of column 128c + j
  *     bytes [2048 + 128 j + i], i = 0..127       column 128c + j: low nibble = code of row
  *                                                256t + 2i, high nibble = row 256t + 2i + 1,
  *                                                stored code = q + 8
- * total = M*K/2 + M*K/16 bytes.  Conventions (status codes, HOST/DEVICE, streams, shapes
- * M % 256 == 0 and K % 128 == 0) are those of spqt.h.
+ * total = T*NC*18432 bytes (= M*K/2 + M*K/16 when M % 256 == 0).  When M is not a multiple of
+ * 256 the quantizers treat the missing rows of the last superblock-row as zero weights and the
+ * dequantizers and kernels never write them back.  Conventions (status codes, HOST/DEVICE,
+ * streams, shapes M >= 1 and K % 128 == 0) are those of spqt.h.
  */
 #ifndef SPQT_COLBLOCK_H
 #define SPQT_COLBLOCK_H

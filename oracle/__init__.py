@@ -163,7 +163,7 @@ def pack(q_rowmajor: np.ndarray, scales: np.ndarray) -> np.ndarray:
     out = np.empty(packed_bytes(M, K), dtype=np.uint8)
     rc = _load().spqt_oracle_pack(_ptr(q_rowmajor), _ptr(s), M, K, _ptr(out))
     if rc != 0:
-        raise ValueError("shape not packable: M % 256 or K % 128 nonzero")
+        raise ValueError("shape not packable: K % 128 nonzero")
     return out
 
 

@@ -49,6 +49,17 @@ def check_shape(M: int, K: int) -> None:
         raise ValueError("column-block layout needs M % 256 == 0 and K % 128 == 0")
 
 
+def pad_rows(W: np.ndarray) -> np.ndarray:
+    """A matrix whose M is not a multiple of 256 is handled as the same matrix with zero rows
+    appended up to the next multiple (the paper states no rule for a ragged edge; this is the
+    build's).  Everything below works on the padded matrix; outputs past row M are ignored."""
+    W = np.asarray(W)
+    extra = (-W.shape[0]) % TILE_ROWS
+    if extra == 0:
+        return W
+    return np.concatenate([W, np.zeros((extra, W.shape[1]), dtype=W.dtype)], axis=0)
+
+
 def packed_bytes(M: int, K: int) -> int:
     check_shape(M, K)
     return (M // TILE_ROWS) * (K // CHUNK_COLS) * CHUNK_BYTES

@@ -176,7 +176,9 @@ void spqt_oracle_partition(int64_t n_ns, int64_t parts, int64_t j, int64_t *begi
  * choice, because the quantization groups stay along K (no requantization):
  *
  *   R = 256 rows per tile, G = 128 columns per quantization group,
- *   T = M / R block-rows, NG = K / G groups.
+ *   T = ceil(M / R) block-rows, NG = K / G groups.  When M is not a multiple of R the rows
+ *   M .. R*T-1 of the last block-row do not exist; they are stored as weight 0 (code 8) under
+ *   scale bits 0 (the paper states no rule for a ragged edge; zero padding is this build's).
  *   One chunk per (t, g), at byte offset (t*NG + g) * CH, CH = 2*R + G*R/2 = 16896.
  *     bytes [0, 512):              fp16 bits of scale[256 t + r][g], r = 0..255, little endian
  *     bytes [512 + 128 c + j]:     column k = 128 g + c (c = 0..127), j = 0..127:
@@ -193,7 +195,7 @@ void spqt_oracle_partition(int64_t n_ns, int64_t parts, int64_t j, int64_t *begi
 
 int64_t spqt_oracle_packed_bytes(int64_t M, int64_t K)
 {
-    return (M / ZZ_R) * (K / ZZ_G) * (int64_t)ZZ_CH;
+    return ((M + ZZ_R - 1) / ZZ_R) * (K / ZZ_G) * (int64_t)ZZ_CH;
 }
 
 static void set_nibble(uint8_t *byte, int high, int value)
@@ -212,15 +214,15 @@ static int get_nibble(uint8_t byte, int high)
 int spqt_oracle_pack(const uint8_t *q_rowmajor, const uint16_t *scales, int64_t M, int64_t K,
                      uint8_t *out)
 {
-    if (M <= 0 || K <= 0 || M % ZZ_R || K % ZZ_G)
+    if (M <= 0 || K <= 0 || K % ZZ_G)
         return -1;
-    int64_t T = M / ZZ_R, NG = K / ZZ_G;
+    int64_t T = (M + ZZ_R - 1) / ZZ_R, NG = K / ZZ_G;
     memset(out, 0, (size_t)spqt_oracle_packed_bytes(M, K));
     for (int64_t t = 0; t < T; ++t)
         for (int64_t g = 0; g < NG; ++g) {
             uint8_t *chunk = out + (t * NG + g) * ZZ_CH;
             for (int r = 0; r < ZZ_R; ++r) {
-                uint16_t s = scales[(t * ZZ_R + r) * NG + g];
+                uint16_t s = (t * ZZ_R + r < M) ? scales[(t * ZZ_R + r) * NG + g] : 0;
                 chunk[2 * r] = (uint8_t)(s & 0xFF);
                 chunk[2 * r + 1] = (uint8_t)(s >> 8);
             }
@@ -229,7 +231,7 @@ int spqt_oracle_pack(const uint8_t *q_rowmajor, const uint16_t *scales, int64_t 
                     for (int half = 0; half < 2; ++half) {
                         int64_t m = t * ZZ_R + 2 * j + half;
                         int64_t k = g * ZZ_G + c;
-                        int q = source_code(q_rowmajor, K, m, k);
+                        int q = (m < M) ? source_code(q_rowmajor, K, m, k) : 0;
                         set_nibble(&chunk[512 + 128 * c + j], half, q + 8);
                     }
         }
@@ -239,14 +241,14 @@ int spqt_oracle_pack(const uint8_t *q_rowmajor, const uint16_t *scales, int64_t 
 int spqt_oracle_unpack(const uint8_t *packed, int64_t M, int64_t K, uint8_t *q_rowmajor,
                        uint16_t *scales)
 {
-    if (M <= 0 || K <= 0 || M % ZZ_R || K % ZZ_G)
+    if (M <= 0 || K <= 0 || K % ZZ_G)
         return -1;
-    int64_t T = M / ZZ_R, NG = K / ZZ_G;
+    int64_t T = (M + ZZ_R - 1) / ZZ_R, NG = K / ZZ_G;
     memset(q_rowmajor, 0, (size_t)(M * (K / 2)));
     for (int64_t t = 0; t < T; ++t)
         for (int64_t g = 0; g < NG; ++g) {
             const uint8_t *chunk = packed + (t * NG + g) * ZZ_CH;
-            for (int r = 0; r < ZZ_R; ++r)
+            for (int r = 0; r < ZZ_R && t * ZZ_R + r < M; ++r)
                 scales[(t * ZZ_R + r) * NG + g] =
                     (uint16_t)(chunk[2 * r] | ((uint16_t)chunk[2 * r + 1] << 8));
             for (int c = 0; c < ZZ_G; ++c)
@@ -254,6 +256,8 @@ int spqt_oracle_unpack(const uint8_t *packed, int64_t M, int64_t K, uint8_t *q_r
                     for (int half = 0; half < 2; ++half) {
                         int64_t m = t * ZZ_R + 2 * j + half;
                         int64_t k = g * ZZ_G + c;
+                        if (m >= M)
+                            continue; /* padding row */
                         int q = get_nibble(chunk[512 + 128 * c + j], half) - 8; /* [-8,7] */
                         set_nibble(&q_rowmajor[m * (K / 2) + k / 2], (int)(k % 2), q);
                     }

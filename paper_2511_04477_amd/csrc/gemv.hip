@@ -423,7 +423,7 @@ extern "C" int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out
     if (!out_bytes) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    *out_bytes = counter_bytes(M) + (size_t)M * SPQT_MAX_SPLITS * 2 * sizeof(float) * (size_t)batch;
+    *out_bytes = counter_bytes(M) + (size_t)tiles(M) * kTileRows * SPQT_MAX_SPLITS * 2 * sizeof(float) * (size_t)batch;
     return SPQT_OK;
 }
 
@@ -442,7 +442,7 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
     if (!out) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    const int64_t T = M / kTileRows, NG = K / kGroup;
+    const int64_t T = tiles(M), NG = K / kGroup;
     int waves = 4;
     // Measured on MI355X over the benchmark shapes (sweep of S at 50 % sparsity and dense):
     // the fastest launch has about 512 (sparse) / 1024 (dense) workgroups of 4 wavefronts in
@@ -493,7 +493,7 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
 
-    const int T = (int)(M / kTileRows), NG = (int)(K / kGroup);
+    const int T = (int)tiles(M), NG = (int)(K / kGroup);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
     const bool dense = idx_dev == nullptr;
     hipStream_t st = (hipStream_t)stream;
@@ -536,7 +536,7 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
         epochs = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
-    const int T = (int)(M / kTileRows), NG = (int)(K / kGroup);
+    const int T = (int)tiles(M), NG = (int)(K / kGroup);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
     const bool compact = !(cfg && (cfg->flags & SPQT_CFG_NO_COMPACTION));
     hipStream_t st = (hipStream_t)stream;

@@ -362,7 +362,7 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
         // Measured on MI355X (sweep of S per shape, 50 % and dense): this kernel has no per-group
         // work, so on matrices large enough to be bandwidth-bound (>= 64 MB packed) fewer, longer
         // slices win for the batch-1 list-driven and dense kernels: about 256 workgroups instead of 512 / 1024.
-        const int64_t T64 = M / kTileRows;
+        const int64_t T64 = tiles(M);
         if (mode != 2 && batch == 1 && (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20))
             while (c.splits > 1 && (int64_t)c.splits * T64 > 256) c.splits /= 2;
     }
@@ -384,7 +384,7 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
         epochs = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
-    const int T = (int)(M / kTileRows), NC = (int)(K / kGroup);
+    const int T = (int)tiles(M), NC = (int)(K / kGroup);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
     hipStream_t st = (hipStream_t)stream;
     const uint8_t *pk = (const uint8_t *)packed_dev;

@@ -161,9 +161,11 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
         float sum = 0.0f;
 #pragma unroll
         for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2 * kOut + r];
-        float *y_out = y + (size_t)(r / kTileRows) * M + (size_t)t * kTileRows + (r % kTileRows);
+        const int row = t * kTileRows + (r % kTileRows);
+        const bool real = row < M;                   // rows past M are the last block-row's zero padding
+        float *y_out = y + (size_t)(r / kTileRows) * M + row;
         if (S == 1) {
-            *y_out = sum;
+            if (real) *y_out = sum;
         } else if (s != S - 1) {
             const unsigned long long word = ((unsigned long long)tag << 32) | as_u32(sum);
             __hip_atomic_store(slots + (size_t)s * kOut + r, word, __ATOMIC_RELAXED,
@@ -194,7 +196,7 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
                     if (p0 + j < S - 1) total += as_float((uint32_t)v[j]);
             }
             total += sum;
-            *y_out = gave_up ? __builtin_nanf("") : total;
+            if (real) *y_out = gave_up ? __builtin_nanf("") : total;
         }
     }
     if (S > 1 && s == S - 1 && tid == 0)

@@ -83,12 +83,23 @@ void for_each_tile_row(int64_t T, F fn) {
 
 int check_cb_shape(int64_t M, int64_t K) { return check_shape(M, K, kGroup); }
 
+// When M is not a multiple of 256 the last block-row is quantized as if the missing rows
+// held zero weights: a zero-filled copy [256][K] of that block-row (empty otherwise).
+std::vector<float> padded_last_tile(const float *w, int64_t M, int64_t K) {
+    std::vector<float> p;
+    const int64_t have = M % kTileRows;
+    if (have == 0) return p;
+    p.assign((size_t)kTileRows * K, 0.0f);
+    std::memcpy(p.data(), w + (size_t)(M - have) * K, (size_t)have * K * sizeof(float));
+    return p;
+}
+
 }  // namespace
 
 extern "C" int spqt_cb_packed_bytes(int64_t M, int64_t K, size_t *out_bytes) {
     if (!out_bytes) return SPQT_EINVAL;
     if (int rc = check_cb_shape(M, K)) return rc;
-    *out_bytes = (size_t)(M / kTileRows) * (size_t)(K / kGroup) * (size_t)kCbChunkBytes;
+    *out_bytes = (size_t)tiles(M) * (size_t)(K / kGroup) * (size_t)kCbChunkBytes;
     return SPQT_OK;
 }
 
@@ -97,13 +108,15 @@ extern "C" int spqt_cb_quantize(const float *w, int64_t M, int64_t K, void *out_
     size_t need = 0;
     if (int rc = spqt_cb_packed_bytes(M, K, &need)) return rc;
     if (out_bytes < need) return SPQT_ESIZE;
-    const int64_t T = M / kTileRows, NC = K / kGroup;
+    const int64_t T = tiles(M), NC = K / kGroup;
     uint8_t *out = (uint8_t *)out_packed;
+    const std::vector<float> padded = padded_last_tile(w, M, K);
+    const float *last = padded.empty() ? nullptr : padded.data();
     for_each_tile_row(T, [=](int64_t t) {
         float scale[kBlocksPerTile][kGroup];
         for (int64_t c = 0; c < NC; ++c) {
             uint8_t *chunk = out + (size_t)(t * NC + c) * kCbChunkBytes;
-            const float *tile = w + (size_t)t * kTileRows * K + (size_t)c * kGroup;   // row stride K
+            const float *tile = (last && t == T - 1 ? last : w + (size_t)t * kTileRows * K) + (size_t)c * kGroup;   // row stride K
             for (int b = 0; b < kBlocksPerTile; ++b) {
                 float amax[kGroup];
                 for (int j = 0; j < kGroup; ++j) amax[j] = 0.0f;
@@ -141,14 +154,14 @@ extern "C" int spqt_cb_quantize(const float *w, int64_t M, int64_t K, void *out_
 extern "C" int spqt_cb_dequantize(const void *packed, int64_t M, int64_t K, float *w_out) {
     if (!packed || !w_out) return SPQT_EINVAL;
     if (int rc = check_cb_shape(M, K)) return rc;
-    const int64_t T = M / kTileRows, NC = K / kGroup;
+    const int64_t T = tiles(M), NC = K / kGroup;
     const uint8_t *in = (const uint8_t *)packed;
     for_each_tile_row(T, [=](int64_t t) {
         for (int64_t c = 0; c < NC; ++c) {
             const uint8_t *chunk = in + (size_t)(t * NC + c) * kCbChunkBytes;
             float *tile = w_out + (size_t)t * kTileRows * K + (size_t)c * kGroup;
             for (int j = 0; j < kGroup; ++j) {
-                for (int r = 0; r < kTileRows; ++r) {
+                for (int r = 0; r < kTileRows && t * kTileRows + r < M; ++r) {
                     const int b = r / kBlockRows;
                     const uint16_t h = (uint16_t)(chunk[16 * j + 2 * b] | (chunk[16 * j + 2 * b + 1] << 8));
                     const uint8_t byte = chunk[kCbScaleBytes + 128 * j + r / 2];
@@ -205,13 +218,15 @@ extern "C" int spqt_cbk_quantize(const float *w, int64_t M, int64_t K, void *out
     size_t need = 0;
     if (int rc = spqt_cb_packed_bytes(M, K, &need)) return rc;
     if (out_bytes < need) return SPQT_ESIZE;
-    const int64_t T = M / kTileRows, NC = K / kGroup;
+    const int64_t T = tiles(M), NC = K / kGroup;
     uint8_t *out = (uint8_t *)out_packed;
+    const std::vector<float> padded = padded_last_tile(w, M, K);
+    const float *last = padded.empty() ? nullptr : padded.data();
     for_each_tile_row(T, [=](int64_t t) {
         std::vector<float> se_v((size_t)kBlocksPerTile * kGroup), me_v((size_t)kBlocksPerTile * kGroup);
         for (int64_t c = 0; c < NC; ++c) {
             uint8_t *chunk = out + (size_t)(t * NC + c) * kCbChunkBytes;
-            const float *tile = w + (size_t)t * kTileRows * K + (size_t)c * kGroup;
+            const float *tile = (last && t == T - 1 ? last : w + (size_t)t * kTileRows * K) + (size_t)c * kGroup;
             for (int j = 0; j < kGroup; ++j) {
                 float scale_b[kBlocksPerTile], min_b[kBlocksPerTile];
                 float smax = 0.0f, mmax = 0.0f;
@@ -265,7 +280,7 @@ extern "C" int spqt_cbk_quantize(const float *w, int64_t M, int64_t K, void *out
 extern "C" int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, float *w_out) {
     if (!packed || !w_out) return SPQT_EINVAL;
     if (int rc = check_cb_shape(M, K)) return rc;
-    const int64_t T = M / kTileRows, NC = K / kGroup;
+    const int64_t T = tiles(M), NC = K / kGroup;
     const uint8_t *in = (const uint8_t *)packed;
     for_each_tile_row(T, [=](int64_t t) {
         for (int64_t c = 0; c < NC; ++c) {
@@ -277,7 +292,7 @@ extern "C" int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, flo
                 const float dm = half_bits_to_float((uint16_t)(head[2] | (head[3] << 8)));
                 int sc[kBlocksPerTile], mq[kBlocksPerTile];
                 get_fields(head + 4, sc, mq);
-                for (int r = 0; r < kTileRows; ++r) {
+                for (int r = 0; r < kTileRows && t * kTileRows + r < M; ++r) {
                     const int b = r / kBlockRows;
                     const uint8_t byte = chunk[kCbScaleBytes + 128 * j + r / 2];
                     const int q = (byte >> (4 * (r & 1))) & 15;

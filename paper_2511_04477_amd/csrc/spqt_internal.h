@@ -15,15 +15,18 @@ constexpr int kColBytes = kTileRows / 2;           // one column of one tile: 12
 constexpr int kChunkBytes = SPQT_CHUNK_BYTES;      // kScaleBytes + kGroup * kColBytes
 static_assert(kChunkBytes == kScaleBytes + kGroup * kColBytes, "chunk size");
 
+// Block-rows of a matrix with M rows; the last one is zero-padded when M is not a multiple of 256.
+inline int64_t tiles(int64_t M) { return (M + kTileRows - 1) / kTileRows; }
+
 // Bytes reserved at the head of the workspace for the per-block-row epoch counters.
 inline size_t counter_bytes(int64_t M) {
-    size_t n = (size_t)(M / kTileRows) * sizeof(int32_t);
+    size_t n = (size_t)tiles(M) * sizeof(int32_t);
     return (n + 255) & ~(size_t)255;
 }
 
 inline int check_shape(int64_t M, int64_t K, int group) {
     if (group != kGroup) return SPQT_ESHAPE;
-    if (M <= 0 || K <= 0 || M % kTileRows != 0 || K % kGroup != 0) return SPQT_ESHAPE;
+    if (M <= 0 || K <= 0 || K % kGroup != 0) return SPQT_ESHAPE;
     if (M > (int64_t)1 << 24 || K > (int64_t)1 << 24) return SPQT_ESHAPE;
     return SPQT_OK;
 }

@@ -93,7 +93,7 @@ def test_kquant_quantizer_matches_oracle_bit_exact(M, K):
 def test_colblock_bad_arguments():
     L = spqt.lib()
     out = ctypes.c_size_t()
-    assert L.spqt_cb_packed_bytes(255, 128, ctypes.byref(out)) == -2
+    assert L.spqt_cb_packed_bytes(256, 100, ctypes.byref(out)) == -2
     assert L.spqt_cb_packed_bytes(256, 128, None) == -1
     w = np.zeros((256, 128), dtype=np.float32)
     small = np.zeros(16, dtype=np.uint8)
@@ -101,7 +101,7 @@ def test_colblock_bad_arguments():
     assert L.spqt_cb_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
     assert L.spqt_cb_quantize(None, 256, 128, vp(small), small.nbytes) == -1
     assert L.spqt_cb_gemv(None, 256, 128, 16, 1, None, None, 16, None, 0, None, None) == -1
-    assert L.spqt_cb_gemv(128, 100, 128, 16, 1, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb_gemv(128, 256, 100, 16, 1, None, None, 16, None, 0, None, None) == -2
     assert L.spqt_cb_gemv(64, 256, 128, 16, 1, None, None, 16, None, 0, None, None) == -3
     assert L.spqt_cb_gemv(128, 256, 128, 16, 1, 16, None, 16, None, 0, None, None) == -1
     assert L.spqt_cb_gemv(128, 256, 128, 16, 5, None, None, 16, None, 0, None, None) == -2
@@ -147,13 +147,57 @@ def test_unpack_is_exact_inverse():
     assert np.array_equal(q3, w["q_rowmajor"]) and np.array_equal(s3.view(np.uint16), s2.view(np.uint16))
 
 
+@pytest.mark.parametrize("M", [1, 2, 255, 257, 300, 701])
+def test_ragged_row_count_is_zero_padded(M):
+    """M need not be a multiple of the block height: the last block-row is stored with weight 0
+    (code 8) and scale bits 0 in the missing rows.  Pinned three ways: library == oracle packer;
+    both == the ordinary path fed the explicitly zero-padded matrix; unpack gives the M rows back."""
+    K = 256
+    w = make_weights(256 * ((M + 255) // 256), K, 4000 + M)
+    q, sc = w["q_rowmajor"][:M].copy(), w["scales"][:M].copy()
+    got = spqt.spqt_pack(q, sc)
+    assert got.nbytes == spqt.spqt_packed_bytes(M, K) == ((M + 255) // 256) * 2 * spqt.CHUNK_BYTES
+    assert np.array_equal(got, oracle.pack(q, sc))
+    Mp = 256 * ((M + 255) // 256)
+    qp = np.zeros((Mp, K // 2), dtype=np.uint8)
+    sp = np.zeros((Mp, K // 128), dtype=np.float16)
+    qp[:M], sp[:M] = q, sc
+    assert np.array_equal(got, spqt.spqt_pack(qp, sp))
+    q2, s2 = spqt.spqt_unpack(got, M, K)
+    assert np.array_equal(q2, q) and np.array_equal(s2.view(np.uint16), sc.view(np.uint16))
+    q3, s3 = oracle.unpack(got, M, K)
+    assert np.array_equal(q3, q) and np.array_equal(s3.view(np.uint16), sc.view(np.uint16))
+
+
+@pytest.mark.parametrize("M", [1, 31, 33, 255, 300, 513])
+def test_ragged_row_count_column_block_quantizers(M):
+    """Column-block quantizers on a ragged M: the missing rows of the last superblock-row count as
+    zero weights (they cannot change a block's max |w|, nor a min/max that already includes 0), so the
+    real rows' values equal those of quantizing the padded matrix, and library == oracle bytes."""
+    from oracle import colblock as cb, colblock_k as ck
+    from workloads import make_fp_weights
+    K = 256
+    W = make_fp_weights(256 * ((M + 255) // 256), K, 4100 + M)[:M].copy()
+    got = spqt.spqt_cb_quantize(W)
+    q, s = cb.quantize(cb.pad_rows(W))
+    assert np.array_equal(got, cb.pack(q, s))
+    back = spqt.spqt_cb_dequantize(got, M, K)
+    assert back.shape == (M, K) and np.array_equal(back.astype(np.float64), cb.dequant(q, s)[:M])
+    assert np.all(q[M:] == 0)
+    gotk = spqt.spqt_cbk_quantize(W)
+    p = ck.quantize(ck.pad_rows(W))
+    assert np.array_equal(gotk, ck.pack(p))
+    backk = spqt.spqt_cbk_dequantize(gotk, M, K)
+    assert np.array_equal(backk, ck.dequant(p).astype(np.float32)[:M])
+
+
 def test_sizes():
     assert spqt.spqt_packed_bytes(4096, 4096) == 4096 * 4096 // 2 + 4096 * 32 * 2
     assert spqt.spqt_packed_bytes(256, 128) == spqt.CHUNK_BYTES
     assert spqt.spqt_workspace_bytes(4096, 4096) >= 4096 * 4 * spqt.MAX_SPLITS
 
 
-@pytest.mark.parametrize("M,K,group", [(255, 128, 128), (256, 127, 128), (256, 128, 64), (0, 128, 128),
+@pytest.mark.parametrize("M,K,group", [(256, 127, 128), (256, 128, 64), (0, 128, 128), ((1 << 24) + 1, 128, 128),
                                        (256, 0, 128), (-256, 128, 128)])
 def test_bad_shapes_are_rejected(M, K, group):
     out = ctypes.c_size_t()
@@ -178,7 +222,7 @@ def test_null_and_small_buffers_are_rejected_on_the_host():
     assert L.spqt_gather(16, 128, 1, ctypes.c_float(float("nan")), 16, 16, None) == -1
     assert L.spqt_gather(18, 128, 1, ctypes.c_float(0.0), 16, 16, None) == -3
     assert L.spqt_gemv(None, 256, 128, 128, 16, 1, None, None, 16, None, 0, None) == -1
-    assert L.spqt_gemv(128, 100, 128, 128, 16, 1, None, None, 16, None, 0, None) == -2
+    assert L.spqt_gemv(128, 256, 100, 128, 16, 1, None, None, 16, None, 0, None) == -2
     assert L.spqt_gemv(64, 256, 128, 128, 16, 1, None, None, 16, None, 0, None) == -3
     assert L.spqt_gemv(128, 256, 128, 128, 16, 1, 16, None, 16, None, 0, None) == -1  # idx without count
     assert L.spqt_gemv(128, 256, 128, 128, 16, 7, None, None, 16, None, 0, None) == -2

@@ -332,6 +332,29 @@ def test_pack_position_encoding_matrix():
 
 
 def test_pack_rejects_bad_shapes():
-    raw = np.zeros((100, 64), dtype=np.uint8)
+    raw = np.zeros((256, 50), dtype=np.uint8)          # K = 100 is not a multiple of the group
     with pytest.raises(ValueError):
-        oracle.pack(raw, np.zeros((100, 1), dtype=np.float16))
+        oracle.pack(raw, np.zeros((256, 1), dtype=np.float16))
+
+
+@pytest.mark.parametrize("M", [1, 100, 257, 300])
+def test_pack_ragged_rows_closed_form_and_padding(M):
+    """A ragged M keeps the closed-form place of every real code and scale; every nibble of a
+    missing row holds code 8 (weight 0) and every missing scale is 0 bits; size = ceil(M/256) tiles."""
+    K, NG = 256, 2
+    rng = np.random.default_rng(900 + M)
+    code = rng.integers(-8, 8, size=(M, K))
+    raw = ((code[:, 0::2] & 0xF) | ((code[:, 1::2] & 0xF) << 4)).astype(np.uint8)
+    sc = rng.integers(1, 65536, size=(M, NG), dtype=np.uint16)
+    p = oracle.pack(raw, sc)
+    T = (M + 255) // 256
+    assert p.size == T * NG * 16896 == oracle.packed_bytes(M, K)
+    for m, k in itertools.product(range(256 * T), range(0, K, 7)):
+        off, high = closed_form_code_pos(m, k, NG)
+        nib = (p[off] >> 4) if high else (p[off] & 0xF)
+        assert nib == (code[m, k] + 8 if m < M else 8), (m, k)
+    for m, g in itertools.product(range(256 * T), range(NG)):
+        off = closed_form_scale_pos(m, g, NG)
+        assert int(p[off]) | (int(p[off + 1]) << 8) == (int(sc[m, g]) if m < M else 0)
+    q2, s2 = oracle.unpack(p, M, K)
+    assert np.array_equal(q2, raw) and np.array_equal(s2.view(np.uint16), sc)
