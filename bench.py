@@ -77,6 +77,7 @@ class Workload:
         self.cnt = torch.zeros((self.copies, 1), dtype=torch.int32, device=dev)
         self.y = torch.zeros((self.copies, M) if batch == 1 else (self.copies, batch, M), dtype=torch.float32, device=dev)
         self.ws = spqt.new_workspace(M, K, batch)
+        self.x_masked = torch.zeros_like(self.x) if batch > 1 else None
         for i in range(self.copies):
             spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
         torch.cuda.synchronize()
@@ -88,6 +89,11 @@ class Workload:
     def step(self, i):
         self.spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
         self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
+
+    def step_own_sets(self, i):
+        """Several rows, each keeping its own set: union list + per-row zeroed copy of x."""
+        self.spqt.spqt_gather_rows(self.x[i], self.thr[i], self.idx[i], self.cnt[i], self.x_masked[i])
+        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x_masked[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
 
     def gemv_only(self, i):
         self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
@@ -176,6 +182,7 @@ class Calib:
         L.spqt_calib_read.argtypes = [vp, sz, vp, i32, i32, vp]
         L.spqt_calib_copy.argtypes = [vp, vp, sz, i32, vp]
         L.spqt_calib_empty.argtypes = [vp]
+        L.spqt_calib_rowmajor_gemv.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_float, i32, vp, vp]
         self.L = L
         self.sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
 
@@ -187,6 +194,12 @@ class Calib:
 
     def read(self, buf, offset, nbytes, blocks=0, unroll=4):
         self.L.spqt_calib_read(buf.data_ptr() + offset, nbytes, self.sink.data_ptr(), blocks, unroll, self.stream())
+
+    def rowmajor_gemv(self, q, scales, M, K, x, thr, skip, y):
+        rc = self.L.spqt_calib_rowmajor_gemv(q.data_ptr(), scales.data_ptr(), M, K, x.data_ptr(), float(thr), int(skip),
+                                             y.data_ptr(), self.stream())
+        if rc != 0:
+            raise RuntimeError(f"spqt_calib_rowmajor_gemv failed ({rc})")
 
     def copy(self, dst, src, nbytes):
         self.L.spqt_calib_copy(dst.data_ptr(), src.data_ptr(), nbytes, 0, self.stream())
@@ -239,6 +252,57 @@ def ablations(torch, spqt, use_graph, cpu):
                      "us": {k: round(v, 3) for k, v in t.items()},
                      "speedup_vs_dense": {k: round(t["dense"] / v, 3) for k, v in t.items() if k != "dense"}})
         del w
+        torch.cuda.empty_cache()
+    return rows
+
+
+def rowmajor_baseline(torch, spqt, use_graph, cpu):
+    """Sections 6.1 and 6.3 on this hardware: the same int4 GEMV read from the ROW-MAJOR source
+    layout - dense (the row-wise baseline the zigzag dense kernel should be on par with) and with
+    the naive per-weight sparsity test (no byte of a row-major line can be skipped) - next to the
+    zigzag kernels, at 50 % on the headline and the 70B gate shape.  Copy 0 of every mode is
+    checked against the oracle."""
+    import numpy as np
+    from workloads import CONFIG_SCALE_RANGE
+    calib = Calib(torch)
+    dev = torch.device("cuda:0")
+    rows = []
+    for config, tensor, M, K in ((2, "q", 4096, 4096), (5, "gate", 28672, 8192)):
+        w = Workload(torch, spqt, M, K, "laplace", CONFIG_SCALE_RANGE[config], config, tensor, 0.5)
+        lo, hi = CONFIG_SCALE_RANGE[config]
+        # row-major copies: copy 0 is the seeded source of the packed copy 0, the others random codes
+        q = [torch.from_numpy(w.case0["q_rowmajor"]).to(dev)]
+        sc = [torch.from_numpy(np.ascontiguousarray(w.case0["scales"])).to(dev)]
+        g = torch.Generator(device=dev)
+        g.manual_seed(4242 + M)
+        for _ in range(1, w.copies):
+            q.append(torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device=dev, generator=g))
+            sc.append((torch.rand((M, K // 128), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16))
+        y = torch.zeros((w.copies, M), dtype=torch.float32, device=dev)
+
+        def rm_dense(i):
+            calib.rowmajor_gemv(q[i], sc[i], M, K, w.x[i], 0.0, 0, y[i])
+
+        def rm_skip(i):
+            calib.rowmajor_gemv(q[i], sc[i], M, K, w.x[i], w.thr[i], 1, y[i])
+
+        if cpu.enabled:
+            for fn, thr in ((rm_dense, 0.0), (rm_skip, w.thr[0])):
+                y[0].fill_(float("nan"))
+                fn(0)
+                torch.cuda.synchronize()
+                if not cpu.close(y[0].cpu().numpy(), cpu.gemv(w.case0, w.x_np[0:1], thr))[0]:
+                    print(f"bench.py: row-major baseline parity check FAILED ({fn.__name__})", file=sys.stderr)
+                    sys.exit(1)
+        steps = max(w.copies * 8, 400)
+        t = {name: time_sequence(torch, fn, w.copies, steps, w.copies, use_graph)
+             for name, fn in (("rowmajor_dense", rm_dense), ("rowmajor_naive_skip", rm_skip),
+                              ("zigzag_dense", w.dense_only), ("zigzag_static_ranges_no_compaction", w.fused_no_compaction),
+                              ("zigzag_list_balanced_gemv", w.gemv_only), ("zigzag_gather_plus_gemv", w.step))}
+        rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(float(np.mean(w.n_ns)) / K, 4),
+                     "us": {k: round(v, 3) for k, v in t.items()},
+                     "speedup_vs_rowmajor_dense": {k: round(t["rowmajor_dense"] / v, 3) for k, v in t.items() if k != "rowmajor_dense"}})
+        del w, q, sc, y
         torch.cuda.empty_cache()
     return rows
 
@@ -835,10 +899,12 @@ def main():
                 t_d = time_sequence(torch, w.dense_only, w.copies, steps, w.copies, use_graph)
                 t_s = time_sequence(torch, w.step, w.copies, steps, w.copies, use_graph)
                 t_f = time_sequence(torch, w.fused, w.copies, steps, w.copies, use_graph) if batch == 1 else None
+                t_r = time_sequence(torch, w.step_own_sets, w.copies, steps, w.copies, use_graph) if batch > 1 else None
                 gb = w.mean_kept_bytes / (t_g * 1e-6) / 1e9
                 sweep.append({"config": config, "tensor": tensor, "M": m, "K": k, "batch": batch, "sparsity_per_row": s,
                               "kept_frac": round(float(np.mean(w.n_ns)) / k, 4),
                               "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3), "us_fused": None if t_f is None else round(t_f, 3),
+                              "us_gather_rows_plus_gemv": None if t_r is None else round(t_r, 3),
                               "GBps_kept": round(gb, 1), "frac_of_8TBps": round(gb / HBM_PEAK_GBPS, 4),
                               "dense_GBps": round(w.dense_bytes / (t_d * 1e-6) / 1e9, 1),
                               "speedup_vs_dense": round(t_d / t_g, 3)})
@@ -852,6 +918,7 @@ def main():
             # over 32 layers (config 4); spqt_gather time included
             out["colblock_layout"] = colblock_rows(torch, spqt, use_graph, cpu)
             out["ablations"] = ablations(torch, spqt, use_graph, cpu)
+            out["rowmajor_baseline"] = rowmajor_baseline(torch, spqt, use_graph, cpu)
             out["dense_shape_sweep"] = dense_shape_sweep(torch, spqt, use_graph)
             out["speedup_grid"] = speedup_grid(torch, spqt, use_graph)
             out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),

@@ -117,6 +117,18 @@ int spqt_unpack(const void *packed, int64_t M, int64_t K, int group, uint8_t *q_
 int spqt_gather(const void *x_dev, int64_t K, int batch, float threshold, int32_t *idx_out_dev,
                 int32_t *count_out_dev, void *stream);
 
+/* DEVICE, async.  spqt_gather for several activation rows that each keep their OWN set (the
+ * paper expects a small beam to work, Section 3.2, without saying how the rows' sets combine;
+ * spqt_gather's union lets every listed column contribute to every row).  Same idx and count
+ * as spqt_gather (the union), and in the same launch a copy of x in which row b has the
+ * entries it drops itself, |x[b][k]| < threshold, replaced by +0:
+ *   x_masked_out_dev  fp16[batch][K], 16-byte aligned, must not overlap x (else SPQT_EINVAL).
+ * Passing the copy instead of x to any GEMV entry point with this idx / count gives
+ * y[b] = sum over the columns ROW b keeps - the batch-1 result of every row - at the cost of
+ * one pass over the union of columns. */
+int spqt_gather_rows(const void *x_dev, int64_t K, int batch, float threshold, int32_t *idx_out_dev,
+                     int32_t *count_out_dev, void *x_masked_out_dev, void *stream);
+
 /* Optional launch shape for spqt_gemv_ex (the two hyper-parameters of Section 4.2.2: how
  * many workgroups share a block-row, and how many wavefronts each holds).  0 = choose. */
 typedef struct {
@@ -130,6 +142,10 @@ typedef struct {
  * column is NOT compacted away - it keeps its slot in the wavefront's step with x = 0.
  * Skipping then saves memory traffic but no issue slots.  Same results as the default. */
 #define SPQT_CFG_NO_COMPACTION 1
+
+/* y_dev is IEEE fp16 [batch][M] instead of fp32: the fp32 result rounded to nearest even at the
+ * final store (2-byte aligned).  Accumulation and the exchange of partial sums stay fp32. */
+#define SPQT_CFG_Y_FP16 4
 
 /* DEVICE, async.  y[b][m] = sum over the listed columns k of scale[m][k/128] * q[m][k] *
  * x[b][k], fp32 accumulation (Section 4.2.2 for the dense kernel, Section 4.2.3 for the
@@ -151,9 +167,10 @@ int spqt_gemv(const void *packed_dev, int64_t M, int64_t K, int group, const voi
               int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
               void *workspace_dev, size_t workspace_bytes, void *stream);
 
-/* Same, with an explicit launch shape (NULL cfg == spqt_gemv). */
+/* Same, with an explicit launch shape and options (NULL cfg == spqt_gemv).  y_dev is fp32
+ * [batch][M] unless cfg->flags has SPQT_CFG_Y_FP16. */
 int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
-                 int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                 int batch, const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                  void *workspace_dev, size_t workspace_bytes, void *stream,
                  const spqt_launch_cfg *cfg);
 
@@ -166,9 +183,9 @@ int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const 
  * (Section 4.2.3): balanced when the kept columns are spread evenly, as with iid activations.
  * This is the combination the paper's threshold sharing aims at (Section 5: fewer index
  * collections per layer), taken to one collection per GEMV at no extra launch.
- * Arguments as for spqt_gemv; cfg may be NULL. */
+ * Arguments as for spqt_gemv_ex; cfg may be NULL. */
 int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
-                    float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                    float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                     void *stream, const spqt_launch_cfg *cfg);
 
 /* The launch shape spqt_gemv would pick for this shape (host only, no device access). */

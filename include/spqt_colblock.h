@@ -67,7 +67,7 @@ int spqt_cb_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
  *   cfg            launch shape or NULL (flags must be 0).
  * Deterministic; same bounded wait and NaN-on-give-up behaviour as spqt_gemv. */
 int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
-                 const int32_t *idx_dev, const int32_t *count_dev, float *y_dev, void *workspace_dev,
+                 const int32_t *idx_dev, const int32_t *count_dev, void *y_dev, void *workspace_dev,
                  size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg);
 
 /* DEVICE, async.  Gather and GEMV in ONE launch (the column-block counterpart of
@@ -75,7 +75,7 @@ int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev
  * 64-column ranges, compacts the kept columns with a wavefront ballot and multiplies; no index
  * list exists.  Same y as spqt_gather followed by spqt_cb_gemv up to summation order. */
 int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, float threshold,
-                       float *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
+                       void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
                        const spqt_launch_cfg *cfg);
 
 /* ---- K-quant flavour of the column-block layout --------------------------------------------
@@ -98,7 +98,7 @@ int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 
 /* DEVICE, async.  As spqt_cb_gemv with batch 1, on spqt_cbk_quantize's output. */
 int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
-                  const int32_t *count_dev, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                  const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                   void *stream, const spqt_launch_cfg *cfg);
 
 #ifdef __cplusplus

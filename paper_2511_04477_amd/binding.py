@@ -21,10 +21,11 @@ GROUP = 128
 CHUNK_BYTES = 16896
 MAX_SPLITS = 64
 CFG_NO_COMPACTION = 1
+CFG_Y_FP16 = 4
 
 EXPORTS = [
     "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",
-    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gemv", "spqt_gemv_ex", "spqt_gemv_fused",
+    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gather_rows", "spqt_gemv", "spqt_gemv_ex", "spqt_gemv_fused",
     "spqt_default_cfg",
 ]
 
@@ -63,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.spqt_pack.argtypes = [vp, vp, i64, i64, i32, vp, sz]
         L.spqt_unpack.argtypes = [vp, i64, i64, i32, vp, vp]
         L.spqt_gather.argtypes = [vp, i64, i32, c.c_float, vp, vp, vp]
+        L.spqt_gather_rows.argtypes = [vp, i64, i32, c.c_float, vp, vp, vp, vp]
         L.spqt_gemv.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         L.spqt_gemv_ex.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp,
                                    c.POINTER(LaunchCfg)]
@@ -157,6 +159,18 @@ def _dev(t, dtype, what):
     return t.data_ptr()
 
 
+def _y_out(y):
+    """(device pointer, flag bits) of an output tensor: fp32, or fp16 with SPQT_CFG_Y_FP16."""
+    import torch
+    if isinstance(y, torch.Tensor) and y.dtype == torch.float16:
+        return _dev(y, torch.float16, "y"), CFG_Y_FP16
+    return _dev(y, torch.float32, "y"), 0
+
+
+def _cfg(splits, waves, flags) -> LaunchCfg:
+    return LaunchCfg(int(splits), int(waves), int(flags))
+
+
 def spqt_workspace_init(workspace, stream=None) -> None:
     import torch
     p = _dev(workspace, torch.uint8, "workspace")
@@ -183,14 +197,28 @@ def spqt_gather(x, threshold: float, idx_out, count_out, stream=None) -> None:
     _check(lib().spqt_gather(xp, K, batch, float(threshold), ip, cp, _stream_ptr(stream)))
 
 
+def spqt_gather_rows(x, threshold: float, idx_out, count_out, x_masked_out, stream=None) -> None:
+    """spqt_gather plus x_masked_out (fp16, same shape as x): every row with its own dropped
+    entries zeroed; feed it to a GEMV with idx_out / count_out for per-row kept sets."""
+    import torch
+    xp = _dev(x, torch.float16, "x")
+    batch, K = (1, x.shape[0]) if x.dim() == 1 else (x.shape[0], x.shape[1])
+    ip = _dev(idx_out, torch.int32, "idx_out")
+    cp = _dev(count_out, torch.int32, "count_out")
+    mp = _dev(x_masked_out, torch.float16, "x_masked_out")
+    if idx_out.numel() < K or count_out.numel() < 1 or x_masked_out.numel() != x.numel():
+        raise SpqtError("spqt_gather_rows: idx_out needs K entries, count_out one, x_masked_out the size of x")
+    _check(lib().spqt_gather_rows(xp, K, batch, float(threshold), ip, cp, mp, _stream_ptr(stream)))
+
+
 def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, group: int = GROUP,
               splits: int = 0, waves: int = 0) -> None:
     """packed uint8 (device); x fp16[K] or [batch,K]; idx/count from spqt_gather or None/None
-    for the dense kernel; y fp32[M] or [batch,M]; workspace from new_workspace()."""
+    for the dense kernel; y fp32 (or fp16) [M] or [batch,M]; workspace from new_workspace()."""
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
-    yp = _dev(y, torch.float32, "y")
+    yp, yflags = _y_out(y)
     batch = 1 if x.dim() == 1 else x.shape[0]
     if x.shape[-1] != K or y.numel() != batch * M or packed.numel() < spqt_packed_bytes(M, K, group):
         raise SpqtError("spqt_gemv: x / y / packed sizes do not match M, K, batch")
@@ -201,8 +229,8 @@ def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, 
     wp, wbytes = None, 0
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
-    if splits or waves:
-        cfg = LaunchCfg(int(splits), int(waves), 0)
+    if splits or waves or yflags:
+        cfg = _cfg(splits, waves, yflags)
         rc = lib().spqt_gemv_ex(pp, M, K, group, xp, batch, ip, cp, yp, wp, wbytes,
                                 _stream_ptr(stream), ctypes.byref(cfg))
     else:
@@ -212,17 +240,17 @@ def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, 
 
 def spqt_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, stream=None,
                     group: int = GROUP, splits: int = 0, waves: int = 0, flags: int = 0) -> None:
-    """Threshold + compaction + GEMV in one launch (batch 1): x fp16[K], y fp32[M]."""
+    """Threshold + compaction + GEMV in one launch (batch 1): x fp16[K], y fp32 (or fp16) [M]."""
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
-    yp = _dev(y, torch.float32, "y")
+    yp, yflags = _y_out(y)
     if x.numel() != K or y.numel() != M or packed.numel() < spqt_packed_bytes(M, K, group):
         raise SpqtError("spqt_gemv_fused: x / y / packed sizes do not match M, K (batch 1 only)")
     wp, wbytes = None, 0
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
-    cfg = LaunchCfg(int(splits), int(waves), int(flags))
+    cfg = _cfg(splits, waves, int(flags) | yflags)
     _check(lib().spqt_gemv_fused(pp, M, K, group, xp, float(threshold), yp, wp, wbytes,
                                  _stream_ptr(stream), ctypes.byref(cfg)))
 
@@ -258,11 +286,12 @@ def spqt_cb_dequantize(packed: np.ndarray, M: int, K: int) -> np.ndarray:
 def spqt_cb_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
                  waves: int = 0) -> None:
     """Column-block GEMV: packed uint8 (device), x fp16[K] or [batch, K], idx/count from spqt_gather
-    or None/None for the dense kernel, y fp32[M] or [batch, M], workspace from new_workspace()."""
+    or None/None for the dense kernel, y fp32 (or fp16) [M] or [batch, M], workspace from
+    new_workspace()."""
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
-    yp = _dev(y, torch.float32, "y")
+    yp, yflags = _y_out(y)
     batch = 1 if x.dim() == 1 else x.shape[0]
     if x.shape[-1] != K or y.numel() != batch * M or packed.numel() < spqt_cb_packed_bytes(M, K):
         raise SpqtError("spqt_cb_gemv: x / y / packed sizes do not match M, K, batch")
@@ -273,7 +302,7 @@ def spqt_cb_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=Non
     wp, wbytes = None, 0
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
-    cfg = LaunchCfg(int(splits), int(waves), 0)
+    cfg = _cfg(splits, waves, yflags)
     _check(lib().spqt_cb_gemv(pp, M, K, xp, batch, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
 
 
@@ -283,13 +312,13 @@ def spqt_cb_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
-    yp = _dev(y, torch.float32, "y")
+    yp, yflags = _y_out(y)
     if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb_packed_bytes(M, K):
         raise SpqtError("spqt_cb_gemv_fused: x / y / packed sizes do not match M, K (batch 1 only)")
     wp, wbytes = None, 0
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
-    cfg = LaunchCfg(int(splits), int(waves), 0)
+    cfg = _cfg(splits, waves, yflags)
     _check(lib().spqt_cb_gemv_fused(pp, M, K, xp, float(threshold), yp, wp, wbytes, _stream_ptr(stream),
                                     ctypes.byref(cfg)))
 
@@ -322,7 +351,7 @@ def spqt_cbk_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=No
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
-    yp = _dev(y, torch.float32, "y")
+    yp, yflags = _y_out(y)
     if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb_packed_bytes(M, K):
         raise SpqtError("spqt_cbk_gemv: x / y / packed sizes do not match M, K (batch 1 only)")
     ip = cp = None
@@ -332,5 +361,5 @@ def spqt_cbk_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=No
     wp, wbytes = None, 0
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
-    cfg = LaunchCfg(int(splits), int(waves), 0)
+    cfg = _cfg(splits, waves, yflags)
     _check(lib().spqt_cbk_gemv(pp, M, K, xp, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))

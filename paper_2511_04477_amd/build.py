@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libspqt.so")
 SOURCES = ["pack.cpp", "quant_cb.cpp", "gather.hip", "gemv.hip", "gemv_cb.hip"]
 CALIB_LIB = os.path.join(PKG, "libspqt_calib.so")       # benchmark-only helper kernels
-CALIB_SOURCES = ["calib.hip"]
+CALIB_SOURCES = ["calib.hip", "baseline_rowmajor.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

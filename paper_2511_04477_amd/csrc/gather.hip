@@ -56,10 +56,26 @@ __device__ __forceinline__ uint32_t mask_at(const uint16_t *__restrict__ x, int 
     return m;
 }
 
-template <int BATCH>
+// The eight fp16 values of v with the entries whose bit in `keep` is clear replaced by +0.
+__device__ __forceinline__ u32x4 zero_dropped(u32x4 v, uint32_t keep) {
+    u32x4 out;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t lo = (keep >> (2 * d)) & 1u ? 0x0000FFFFu : 0u;
+        const uint32_t hi = (keep >> (2 * d + 1)) & 1u ? 0xFFFF0000u : 0u;
+        out[d] = v[d] & (lo | hi);
+    }
+    return out;
+}
+
+// MASKED: besides the union list, write a copy of x in which every row has ITS OWN dropped
+// entries set to zero.  A GEMV over the union list fed this copy gives each row the sum over
+// that row's kept columns only (a dropped entry of a listed column contributes 0 * w).
+template <int BATCH, bool MASKED = false>
 __global__ __launch_bounds__(kThreads) void spqt_gather_kernel(const uint16_t *__restrict__ x, int K,
                                                                float thr, int32_t *__restrict__ idx,
-                                                               int32_t *__restrict__ count) {
+                                                               int32_t *__restrict__ count,
+                                                               uint16_t *__restrict__ x_masked = nullptr) {
     __shared__ int wave_total[kWaves];
     __shared__ int wave_before[kWaves];
     const int lane = threadIdx.x & 63;
@@ -71,7 +87,20 @@ __global__ __launch_bounds__(kThreads) void spqt_gather_kernel(const uint16_t *_
     // ranks follow (wave, lane, bit) order = ascending index.
     const int first = seg * kSegment + lane_first;
     // K % 8 == 0, so a lane's eight entries are all inside x or all past its end
-    const uint32_t m = first < K ? mask_at<BATCH>(x, K, first, thr) : 0u;
+    uint32_t m = 0u;
+    if (MASKED) {
+        if (first < K) {
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)b * K + first);
+                const uint32_t kb = keep_bits(v, thr);
+                *reinterpret_cast<u32x4 *>(x_masked + (size_t)b * K + first) = zero_dropped(v, kb);
+                m |= kb;
+            }
+        }
+    } else {
+        m = first < K ? mask_at<BATCH>(x, K, first, thr) : 0u;
+    }
 
     // Kept entries of all earlier segments, counted by this workgroup itself.
     // (Earlier segments are complete - only the last one can be ragged - so these loads need no
@@ -109,24 +138,52 @@ __global__ __launch_bounds__(kThreads) void spqt_gather_kernel(const uint16_t *_
         if ((m >> j) & 1u) idx[pos++] = first + j;
 }
 
-}  // namespace
-
-extern "C" int spqt_gather(const void *x_dev, int64_t K, int batch, float threshold,
-                           int32_t *idx_out_dev, int32_t *count_out_dev, void *stream) {
+int run_gather(const void *x_dev, int64_t K, int batch, float threshold, int32_t *idx_out_dev,
+               int32_t *count_out_dev, void *x_masked_dev, void *stream) {
     if (!x_dev || !idx_out_dev || !count_out_dev) return SPQT_EINVAL;
     if (K <= 0 || K % spqt::kGroup != 0 || K > SPQT_GATHER_MAX_K) return SPQT_ESHAPE;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
     if (threshold != threshold) return SPQT_EINVAL;   // NaN threshold has no meaning
     if ((uintptr_t)x_dev % 16 != 0 || (uintptr_t)idx_out_dev % 4 != 0) return SPQT_EALIGN;
+    if ((uintptr_t)x_masked_dev % 16 != 0) return SPQT_EALIGN;
     const int segments = (int)((K + kSegment - 1) / kSegment);
     const dim3 grid(segments), block(kThreads);
     hipStream_t st = (hipStream_t)stream;
     const uint16_t *x = (const uint16_t *)x_dev;
+    if (x_masked_dev) {
+        uint16_t *xm = (uint16_t *)x_masked_dev;
+        switch (batch) {
+            case 1: hipLaunchKernelGGL((spqt_gather_kernel<1, true>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, xm); break;
+            case 2: hipLaunchKernelGGL((spqt_gather_kernel<2, true>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, xm); break;
+            case 3: hipLaunchKernelGGL((spqt_gather_kernel<3, true>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, xm); break;
+            default: hipLaunchKernelGGL((spqt_gather_kernel<4, true>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, xm); break;
+        }
+        return hipGetLastError() == hipSuccess ? SPQT_OK : SPQT_EHIP;
+    }
     switch (batch) {
-        case 1: hipLaunchKernelGGL(spqt_gather_kernel<1>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
-        case 2: hipLaunchKernelGGL(spqt_gather_kernel<2>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
-        case 3: hipLaunchKernelGGL(spqt_gather_kernel<3>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
-        default: hipLaunchKernelGGL(spqt_gather_kernel<4>, grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev); break;
+        case 1: hipLaunchKernelGGL((spqt_gather_kernel<1, false>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, (uint16_t *)nullptr); break;
+        case 2: hipLaunchKernelGGL((spqt_gather_kernel<2, false>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, (uint16_t *)nullptr); break;
+        case 3: hipLaunchKernelGGL((spqt_gather_kernel<3, false>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, (uint16_t *)nullptr); break;
+        default: hipLaunchKernelGGL((spqt_gather_kernel<4, false>), grid, block, 0, st, x, (int)K, threshold, idx_out_dev, count_out_dev, (uint16_t *)nullptr); break;
     }
     return hipGetLastError() == hipSuccess ? SPQT_OK : SPQT_EHIP;
+}
+
+}  // namespace
+
+extern "C" int spqt_gather(const void *x_dev, int64_t K, int batch, float threshold,
+                           int32_t *idx_out_dev, int32_t *count_out_dev, void *stream) {
+    return run_gather(x_dev, K, batch, threshold, idx_out_dev, count_out_dev, nullptr, stream);
+}
+
+extern "C" int spqt_gather_rows(const void *x_dev, int64_t K, int batch, float threshold,
+                                int32_t *idx_out_dev, int32_t *count_out_dev, void *x_masked_out_dev,
+                                void *stream) {
+    if (!x_masked_out_dev || !x_dev) return SPQT_EINVAL;
+    if (K > 0 && batch > 0) {   // the copy may not overlap x: other workgroups are still reading it
+        const uintptr_t a = (uintptr_t)x_dev, b = (uintptr_t)x_masked_out_dev;
+        const uintptr_t bytes = (uintptr_t)K * (uintptr_t)batch * 2u;
+        if (a < b + bytes && b < a + bytes) return SPQT_EINVAL;
+    }
+    return run_gather(x_dev, K, batch, threshold, idx_out_dev, count_out_dev, x_masked_out_dev, stream);
 }

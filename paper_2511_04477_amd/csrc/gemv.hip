@@ -381,39 +381,40 @@ __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
 template <int WAVES, int BATCH>
 hipError_t launch(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                   const int32_t *idx, const int32_t *count, float *y, void *partials,
-                  int32_t *epochs, int K, int NG, int S, int T, int M) {
+                  int32_t *epochs, int K, int NG, int S, int T, int M, int y_half) {
     if (dense)
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true, BATCH, 0>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, 0.0f);
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     else
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, BATCH, 0>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, 0.0f);
+                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     return hipGetLastError();
 }
 
 template <int WAVES>
 hipError_t launch_fused(bool compact, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                        float thr, float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
+                        float thr, float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int M,
+                        int y_half) {
     if (compact)
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, 1>), dim3(grid), dim3(WAVES * 64), 0, stream,
                            packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K,
-                           NG, S, T, M, thr);
+                           NG, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
     else
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, 2>), dim3(grid), dim3(WAVES * 64), 0, stream,
                            packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K,
-                           NG, S, T, M, thr);
+                           NG, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
     return hipGetLastError();
 }
 
 template <int WAVES>
 hipError_t launch_batch(int batch, bool dense, int grid, hipStream_t stream, const uint8_t *packed,
                         const uint16_t *x, const int32_t *idx, const int32_t *count, float *y,
-                        void *partials, int32_t *epochs, int K, int NG, int S, int T, int M) {
+                        void *partials, int32_t *epochs, int K, int NG, int S, int T, int M, int y_half) {
     switch (batch) {
-        case 1: return launch<WAVES, 1>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
-        case 2: return launch<WAVES, 2>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
-        case 3: return launch<WAVES, 3>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
-        default: return launch<WAVES, 4>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M);
+        case 1: return launch<WAVES, 1>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
+        case 2: return launch<WAVES, 2>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
+        case 3: return launch<WAVES, 3>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
+        default: return launch<WAVES, 4>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
     }
 }
 
@@ -462,14 +463,15 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
 }
 
 extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
-                            int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                            int batch, const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                             void *workspace_dev, size_t workspace_bytes, void *stream,
                             const spqt_launch_cfg *cfg) {
     if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
     if (idx_dev && !count_dev) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, group)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
+    const int y_half = cfg && (cfg->flags & SPQT_CFG_Y_FP16) ? 1 : 0;
+    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
         return SPQT_EALIGN;
 
     spqt_launch_cfg c;
@@ -501,21 +503,22 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
     switch (c.waves) {
-        case 1: err = launch_batch<1>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
-        case 2: err = launch_batch<2>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
-        default: err = launch_batch<4>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        case 1: err = launch_batch<1>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        case 2: err = launch_batch<2>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        default: err = launch_batch<4>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
     }
     if (err != hipSuccess) return SPQT_EHIP;
     return SPQT_OK;
 }
 
 extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
-                               float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                               float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                                void *stream, const spqt_launch_cfg *cfg) {
     if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
     if (threshold != threshold) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, group)) return rc;
-    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
+    const int y_half = cfg && (cfg->flags & SPQT_CFG_Y_FP16) ? 1 : 0;
+    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
         return SPQT_EALIGN;
     spqt_launch_cfg c;
     if (int rc = spqt_default_cfg(M, K, 1, 1, &c)) return rc;
@@ -544,9 +547,9 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
     switch (c.waves) {
-        case 1: err = launch_fused<1>(compact, grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
-        case 2: err = launch_fused<2>(compact, grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
-        default: err = launch_fused<4>(compact, grid, st, pk, xp, threshold, y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M); break;
+        case 1: err = launch_fused<1>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        case 2: err = launch_fused<2>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        default: err = launch_fused<4>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }

@@ -311,50 +311,52 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
 template <int WAVES, int BATCH>
 hipError_t launch_cb_batch(int mode, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                            const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
-                           int K, int NC, int S, int T, int M) {
+                           int K, int NC, int S, int T, int M, int y_half) {
     const dim3 g(grid), b(WAVES * 64);
     if (mode == 0)        // index list
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, BATCH>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M, 0.0f);
+                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     else                  // dense
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, BATCH>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M, 0.0f);
+                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     return hipGetLastError();
 }
 
 template <int WAVES>
 hipError_t launch_cb(int mode, int batch, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                      const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
-                     int K, int NC, int S, int T, int M, float thr) {
+                     int K, int NC, int S, int T, int M, float thr, int y_half) {
     if (mode == 3 || mode == 4) {      // K-quant flavour, batch 1: index list / dense
         if (mode == 3)
             hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, 0.0f);
+                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
         else
             hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, 0.0f);
+                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
         return hipGetLastError();
     }
     if (mode == 2) {      // threshold inside the kernel (batch 1)
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true, 1>), dim3(grid), dim3(WAVES * 64), 0, stream, packed,
-                           x, idx, count, y, partials, epochs, K, NC, S, T, M, thr);
+                           x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
         return hipGetLastError();
     }
     switch (batch) {
-        case 1: return launch_cb_batch<WAVES, 1>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
-        case 2: return launch_cb_batch<WAVES, 2>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
-        case 3: return launch_cb_batch<WAVES, 3>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
-        default: return launch_cb_batch<WAVES, 4>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M);
+        case 1: return launch_cb_batch<WAVES, 1>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
+        case 2: return launch_cb_batch<WAVES, 2>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
+        case 3: return launch_cb_batch<WAVES, 3>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
+        default: return launch_cb_batch<WAVES, 4>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
     }
 }
 
 int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
-           const int32_t *count_dev, float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+           const int32_t *count_dev, float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
            void *stream, const spqt_launch_cfg *cfg) {
     if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % 4 != 0)
+    if (cfg && (cfg->flags & ~SPQT_CFG_Y_FP16)) return SPQT_EINVAL;
+    const int y_half = cfg && (cfg->flags & SPQT_CFG_Y_FP16) ? 1 : 0;
+    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
         return SPQT_EALIGN;
     spqt_launch_cfg c;
     if (int rc = spqt_default_cfg(M, K, batch, mode != 1 && mode != 4, &c)) return rc;
@@ -367,7 +369,6 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
             while (c.splits > 1 && (int64_t)c.splits * T64 > 256) c.splits /= 2;
     }
     if (cfg) {
-        if (cfg->flags) return SPQT_EINVAL;
         if (cfg->splits) c.splits = cfg->splits;
         if (cfg->waves) c.waves = cfg->waves;
     }
@@ -391,9 +392,9 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
     switch (c.waves) {
-        case 1: err = launch_cb<1>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
-        case 2: err = launch_cb<2>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
-        default: err = launch_cb<4>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold); break;
+        case 1: err = launch_cb<1>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
+        case 2: err = launch_cb<2>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
+        default: err = launch_cb<4>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }
@@ -401,7 +402,7 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
 }  // namespace
 
 extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
-                            const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                            const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                             void *workspace_dev, size_t workspace_bytes, void *stream,
                             const spqt_launch_cfg *cfg) {
     if (idx_dev && !count_dev) return SPQT_EINVAL;
@@ -410,7 +411,7 @@ extern "C" int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const 
 }
 
 extern "C" int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
-                                  float threshold, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                                  float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                                   void *stream, const spqt_launch_cfg *cfg) {
     if (threshold != threshold) return SPQT_EINVAL;
     return run_cb(2, 1, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev,
@@ -418,7 +419,7 @@ extern "C" int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, 
 }
 
 extern "C" int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
-                             const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                             const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                              void *workspace_dev, size_t workspace_bytes, void *stream,
                              const spqt_launch_cfg *cfg) {
     if (idx_dev && !count_dev) return SPQT_EINVAL;

@@ -18,6 +18,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPassCols = 64;                  // most columns one pass covers (8 steps)
 constexpr float kTwo24 = 16777216.0f;          // 2^24: undoes the fp16 subnormal exponent
+constexpr int kHalfOutputBit = 1 << 30;        // in the kernels' M argument: y is fp16, not fp32
 constexpr int kMaxPolls = 1 << 18;             // bound on the reducer's wait for one batch of partials
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
@@ -154,7 +155,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int WAVES, int BATCH>
 __device__ __forceinline__ void combine_block_row(const float *red, int tid, int t, int s, int S, uint32_t tag,
                                                   void *partials, int32_t *epochs, float *__restrict__ y,
-                                                  int M) {
+                                                  int m_and_flags) {
+    // One kernel argument carries both (M <= 2^24): every extra scalar argument costs the
+    // four-row kernels, which sit at the register limit, a spill.
+    const int M = m_and_flags & (kHalfOutputBit - 1);
+    const bool y_half = (m_and_flags & kHalfOutputBit) != 0;
     constexpr int kOut = BATCH * kTileRows;      // values one workgroup contributes: [BATCH][256]
     unsigned long long *slots = reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kOut;
     for (int r = tid; r < kOut; r += WAVES * 64) {
@@ -163,9 +168,14 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
         for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2 * kOut + r];
         const int row = t * kTileRows + (r % kTileRows);
         const bool real = row < M;                   // rows past M are the last block-row's zero padding
-        float *y_out = y + (size_t)(r / kTileRows) * M + row;
+        const size_t y_at = (size_t)(r / kTileRows) * M + row;
+        // fp32 output, or the same value rounded to fp16 (nearest even) when the caller asked for it
+        auto store_y = [&](float v) {
+            if (y_half) reinterpret_cast<_Float16 *>(y)[y_at] = (_Float16)v;
+            else y[y_at] = v;
+        };
         if (S == 1) {
-            if (real) *y_out = sum;
+            if (real) store_y(sum);
         } else if (s != S - 1) {
             const unsigned long long word = ((unsigned long long)tag << 32) | as_u32(sum);
             __hip_atomic_store(slots + (size_t)s * kOut + r, word, __ATOMIC_RELAXED,
@@ -196,7 +206,7 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
                     if (p0 + j < S - 1) total += as_float((uint32_t)v[j]);
             }
             total += sum;
-            if (real) *y_out = gave_up ? __builtin_nanf("") : total;
+            if (real) store_y(gave_up ? __builtin_nanf("") : total);
         }
     }
     if (S > 1 && s == S - 1 && tid == 0)

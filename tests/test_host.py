@@ -25,12 +25,18 @@ def test_calibration_library_exports_every_declared_symbol():
     L = ctypes.CDLL(os.path.join(ROOT, "paper_2511_04477_amd", "libspqt_calib.so"))
     names = declared_functions("spqt_calib.h")
     assert names == ["spqt_calib_copy", "spqt_calib_empty", "spqt_calib_read", "spqt_calib_read_blocked",
-                     "spqt_calib_read_lines"]
+                     "spqt_calib_read_lines", "spqt_calib_rowmajor_gemv"]
     for n in names:
         assert getattr(L, n) is not None
     # argument checks happen before any launch
     L.spqt_calib_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     assert L.spqt_calib_read(None, 16, None, 0, 4, None) == -1
+    L.spqt_calib_rowmajor_gemv.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                           ctypes.c_void_p, ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    assert L.spqt_calib_rowmajor_gemv(None, 16, 256, 128, 16, 0.0, 0, 16, None) == -1
+    assert L.spqt_calib_rowmajor_gemv(16, 16, 256, 100, 16, 0.0, 0, 16, None) == -1
+    assert L.spqt_calib_rowmajor_gemv(16, 16, 256, 65536, 16, 0.0, 0, 16, None) == -1     # x would not fit LDS
+    assert L.spqt_calib_rowmajor_gemv(8, 16, 256, 128, 16, 0.0, 0, 16, None) == -1        # misaligned codes
     assert L.spqt_calib_read(16, 24, 16, 0, 4, None) == -1
 
 
@@ -221,6 +227,11 @@ def test_null_and_small_buffers_are_rejected_on_the_host():
     assert L.spqt_gather(16, 128, 5, ctypes.c_float(0.0), 16, 16, None) == -2
     assert L.spqt_gather(16, 128, 1, ctypes.c_float(float("nan")), 16, 16, None) == -1
     assert L.spqt_gather(18, 128, 1, ctypes.c_float(0.0), 16, 16, None) == -3
+    assert L.spqt_gather_rows(4096, 128, 2, ctypes.c_float(0.0), 16, 16, None, None) == -1     # no copy buffer
+    assert L.spqt_gather_rows(4096, 128, 2, ctypes.c_float(0.0), 16, 16, 4096, None) == -1     # copy == x
+    assert L.spqt_gather_rows(4096, 128, 2, ctypes.c_float(0.0), 16, 16, 4096 + 256, None) == -1  # overlaps row 1
+    assert L.spqt_gather_rows(4096, 128, 2, ctypes.c_float(0.0), 16, 16, 8192 + 8, None) == -3  # misaligned copy
+    assert L.spqt_gather_rows(4096, 100, 2, ctypes.c_float(0.0), 16, 16, 8192, None) == -2
     assert L.spqt_gemv(None, 256, 128, 128, 16, 1, None, None, 16, None, 0, None) == -1
     assert L.spqt_gemv(128, 256, 100, 128, 16, 1, None, None, 16, None, 0, None) == -2
     assert L.spqt_gemv(64, 256, 128, 128, 16, 1, None, None, 16, None, 0, None) == -3
