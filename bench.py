@@ -307,6 +307,66 @@ def rowmajor_baseline(torch, spqt, use_graph, cpu):
     return rows
 
 
+def eight_bit_rows(torch, spqt, use_graph, cpu):
+    """The 8-bit flavour of the column-block layout (128-row block-rows, one column still one
+    128-byte run) on the headline and the 70B gate shape at 50 % and dense.  Copy 0 is quantized
+    from seeded fp32 weights by the library and checked against the NumPy oracle on sampled
+    block-rows; the other copies are random codes under valid fp16 scales."""
+    import numpy as np
+    from workloads import make_fp_weights, make_x, quantile_threshold
+    dev = torch.device("cuda:0")
+    rows = []
+    for M, K in ((4096, 4096), (28672, 8192)):
+        pbytes = spqt.spqt_cb8_packed_bytes(M, K)
+        copies = max(2, -(-ROTATE_BYTES // pbytes))
+        T, NC = M // 128, K // 128
+        W0 = make_fp_weights(M, K, 9100 + M)
+        packed = [torch.from_numpy(spqt.spqt_cb8_quantize(W0)).to(dev)]
+        g = torch.Generator(device=dev)
+        g.manual_seed(9101 + M)
+        for _ in range(1, copies):
+            buf = torch.randint(0, 256, (T * NC, spqt.CB8_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NC, 512), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
+            buf[:, :1024] = sc.view(torch.uint8)
+            packed.append(buf.reshape(-1))
+        tiles = np.unique(np.array([0, T // 2, T - 1]))
+        sample = (tiles[:, None] * 128 + np.arange(128)[None, :]).ravel()
+        W0_sample = W0[sample].copy()
+        del W0
+        x_np = make_x(K, "laplace", 9102 + M)
+        thr = quantile_threshold(x_np, 0.5)
+        x = torch.from_numpy(x_np[0]).to(dev)
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        y = torch.empty(M, dtype=torch.float32, device=dev)
+        ws = spqt.new_workspace(M, K)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        torch.cuda.synchronize()
+        n = int(cnt.item())
+        if cpu.enabled:
+            y.fill_(float("nan"))
+            spqt.spqt_cb8_gemv(packed[0], M, K, x, idx, cnt, y, ws)
+            torch.cuda.synchronize()
+            if not cpu.close(y.cpu().numpy()[sample], cpu.colblock_w8(W0_sample, x_np, thr))[0]:
+                print(f"bench.py: 8-bit column-block parity check FAILED ({M}x{K})", file=sys.stderr)
+                sys.exit(1)
+        fns = {"us_gemv": lambda i: spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws),
+               "us_dense": lambda i: spqt.spqt_cb8_gemv(packed[i], M, K, x, None, None, y, ws),
+               "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
+                                                 spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws))}
+        t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
+        kept = n * (M + M // 16)
+        rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(n / K, 4), "bits_per_weight": 8.5,
+                     "kept_bytes": kept, **{k: round(v, 3) for k, v in t.items()},
+                     "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
+                     "frac_of_8TBps": round(kept / (t["us_gemv"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "dense_GBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9, 1),
+                     "speedup_vs_dense": round(t["us_dense"] / t["us_gemv"], 3)})
+        del packed
+        torch.cuda.empty_cache()
+    return rows
+
+
 def colblock_rows(torch, spqt, use_graph, cpu, full=True):
     """The column-block variant of the layout (the paper's own grouping, Section 4.1.2: 32-row
     blocks along a column, scales skipped with their column) on the headline and 70B shapes.
@@ -691,6 +751,12 @@ class CpuBaseline:
         q, s = cb.quantize(W_rows)
         return cb.gemv(q, s, x_np, thr)[0]
 
+    def colblock_w8(self, W_rows, x_np, thr):
+        """8-bit column-block reference on a subset of whole 128-row block-rows of fp32 weights."""
+        from oracle import colblock_w8 as c8
+        q, s = c8.quantize(W_rows)
+        return c8.gemv(q, s, x_np, thr)[0]
+
     def colblock_k(self, W_rows, x_np, thr):
         """K-quant column-block reference on a subset of whole 256-row tiles of fp32 weights."""
         from oracle import colblock_k as ck
@@ -919,6 +985,7 @@ def main():
             out["colblock_layout"] = colblock_rows(torch, spqt, use_graph, cpu)
             out["ablations"] = ablations(torch, spqt, use_graph, cpu)
             out["rowmajor_baseline"] = rowmajor_baseline(torch, spqt, use_graph, cpu)
+            out["eight_bit_layout"] = eight_bit_rows(torch, spqt, use_graph, cpu)
             out["dense_shape_sweep"] = dense_shape_sweep(torch, spqt, use_graph)
             out["speedup_grid"] = speedup_grid(torch, spqt, use_graph)
             out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),

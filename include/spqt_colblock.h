@@ -61,10 +61,10 @@ int spqt_cb_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
  *   idx_dev        int32 kept-column list from spqt_gather (ascending), or NULL for the
  *                  dense kernel, which visits every column and reads neither idx nor count.
  *   count_dev      int32[1] n_ns on the device (ignored when idx_dev == NULL).
- *   y_dev          fp32[batch][M], fully overwritten.
+ *   y_dev          fp32[batch][M] (fp16 with SPQT_CFG_Y_FP16), fully overwritten.
  *   workspace_dev  as for spqt_gemv: >= spqt_workspace_bytes(M, K, batch), prepared once by
  *                  spqt_workspace_init.
- *   cfg            launch shape or NULL (flags must be 0).
+ *   cfg            launch shape or NULL (flags: 0 or SPQT_CFG_Y_FP16).
  * Deterministic; same bounded wait and NaN-on-give-up behaviour as spqt_gemv. */
 int spqt_cb_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
                  const int32_t *idx_dev, const int32_t *count_dev, void *y_dev, void *workspace_dev,
@@ -98,6 +98,30 @@ int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 
 /* DEVICE, async.  As spqt_cb_gemv with batch 1, on spqt_cbk_quantize's output. */
 int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+                  const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
+                  void *stream, const spqt_launch_cfg *cfg);
+
+/* ---- 8-bit flavour of the column-block layout ("ZZ-CB32-W8") --------------------------------
+ * Section 4.1.2 states that the layout carries over to other bit-widths without giving one.  This
+ * reading keeps one activation column's weights of a block-row in ONE 128-byte run, so a
+ * block-row is 128 rows high; blocks stay 32 rows with one fp16 scale (fp32, round to nearest even):
+ *     s = fp16(max|w| / 127),  q = clamp(rint(w / float(s)), -128, 127)  (0 if s is 0),  value q * float(s)
+ * Packed form: T = ceil(M/128), NC = K/128, chunk (t, c) at (t*NC + c) * 17408:
+ *     bytes [8 j + 2 b], b = 0..3         fp16 scale of rows 128t + 32b .. +31 of column 128c + j
+ *     bytes [1024 + 128 j + i], i < 128   code of row 128t + i of column 128c + j, stored q + 128
+ * Rows past M in the last block-row are quantized as zero weights and never written back. */
+#define SPQT_CB8_TILE_ROWS 128
+#define SPQT_CB8_CHUNK_BYTES 17408
+int spqt_cb8_packed_bytes(int64_t M, int64_t K, size_t *out_bytes);
+/* HOST, offline.  As spqt_cb_quantize, by the 8-bit rule above. */
+int spqt_cb8_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_packed, size_t out_bytes);
+/* HOST.  w_out[m][k] = q * float(s), float[M][K]. */
+int spqt_cb8_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
+/* DEVICE, async.  As spqt_cb_gemv with batch 1, on spqt_cb8_quantize's output.  The workspace
+ * has the size spqt_workspace_bytes(M, K, 1) gives, but its contents are laid out for 128-row
+ * block-rows: do not share one workspace between this entry point and the 4-bit ones without a
+ * spqt_workspace_init in between. */
+int spqt_cb8_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
                   const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                   void *stream, const spqt_launch_cfg *cfg);
 

@@ -35,14 +35,6 @@ constexpr int kCbScaleBytes = kGroup * 16;                 // 128 columns x 8 fp
 constexpr int kCbChunkBytes = SPQT_CB_CHUNK_BYTES;
 static_assert(kCbChunkBytes == kCbScaleBytes + kGroup * kColBytes, "chunk size");
 
-// Sum over the 8 lanes that read the same 32 rows (lanes seg, seg + 8, ..., seg + 56).
-__device__ __forceinline__ float sum_over_columns(float v) {
-    v += dpp_move<0x128>(v);   // row_ror:8 - the lane 8 further inside the row of 16
-    v = fold16(v, v);
-    v = fold32(v, v);
-    return v;
-}
-
 // FUSED: the kernel applies the sparsity test itself instead of reading an index list (as
 // spqt_gemv_fused does for the group layout): a wavefront's slice is a static range of
 // 64-column units; lane l tests column 64u + l, a ballot gives the kept set, mbcnt the rank,

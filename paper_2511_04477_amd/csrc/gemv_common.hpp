@@ -140,10 +140,19 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Sum over the 8 lanes that read the same rows of a column run (lanes seg, seg + 8, ..., seg + 56).
+__device__ __forceinline__ float sum_over_columns(float v) {
+    v += dpp_move<0x128>(v);   // row_ror:8 - the lane 8 further inside the row of 16
+    v = fold16(v, v);
+    v = fold32(v, v);
+    return v;
+}
+
 // Combine the S workgroups of block-row t (paper Section 4.2.2: the partial sums of the
 // threadgroups that share a superblock row are reduced once at the end, without atomics on y).
-// `red` holds this workgroup's [WAVES][BATCH][256] partial sums in LDS (already synchronised).
-// Every workgroup but the last (s == S-1) publishes its 256 partial sums as 64-bit words
+// `red` holds this workgroup's [WAVES][BATCH][ROWS] partial sums in LDS (already synchronised);
+// ROWS is the height of a block-row (256 for the 4-bit layouts).
+// Every workgroup but the last (s == S-1) publishes its ROWS partial sums as 64-bit words
 // {value, tag} with device-scope stores and is done: no wait, no counter.  The last one adds
 // the others' words in index order, polling a word until its tag equals this call's tag,
 // then its own sums, and writes y.  The tag is the block-row's epoch + 1; the epoch lives in
@@ -152,7 +161,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // access: value and tag arrive together.  The reducer has the highest index of its block-row
 // and workgroups are dispatched in index order, so everything it waits for is running or
 // finished; the wait is bounded anyway and a give-up poisons y with NaN instead of hanging.
-template <int WAVES, int BATCH>
+template <int WAVES, int BATCH, int ROWS = kTileRows>
 __device__ __forceinline__ void combine_block_row(const float *red, int tid, int t, int s, int S, uint32_t tag,
                                                   void *partials, int32_t *epochs, float *__restrict__ y,
                                                   int m_and_flags) {
@@ -160,15 +169,15 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
     // four-row kernels, which sit at the register limit, a spill.
     const int M = m_and_flags & (kHalfOutputBit - 1);
     const bool y_half = (m_and_flags & kHalfOutputBit) != 0;
-    constexpr int kOut = BATCH * kTileRows;      // values one workgroup contributes: [BATCH][256]
+    constexpr int kOut = BATCH * ROWS;           // values one workgroup contributes: [BATCH][ROWS]
     unsigned long long *slots = reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kOut;
     for (int r = tid; r < kOut; r += WAVES * 64) {
         float sum = 0.0f;
 #pragma unroll
         for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2 * kOut + r];
-        const int row = t * kTileRows + (r % kTileRows);
+        const int row = t * ROWS + (r % ROWS);
         const bool real = row < M;                   // rows past M are the last block-row's zero padding
-        const size_t y_at = (size_t)(r / kTileRows) * M + row;
+        const size_t y_at = (size_t)(r / ROWS) * M + row;
         // fp32 output, or the same value rounded to fp16 (nearest even) when the caller asked for it
         auto store_y = [&](float v) {
             if (y_half) reinterpret_cast<_Float16 *>(y)[y_at] = (_Float16)v;

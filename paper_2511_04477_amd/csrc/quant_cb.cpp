@@ -303,3 +303,81 @@ extern "C" int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, flo
     });
     return SPQT_OK;
 }
+
+// ---- 8-bit flavour: block-rows of 128 rows, codes stored as q + 128 ---------------------------------
+
+namespace {
+
+constexpr int kRows8 = SPQT_CB8_TILE_ROWS;
+constexpr int kBlocks8 = kRows8 / kBlockRows;                    // 4
+constexpr int kScaleBytes8 = kGroup * 2 * kBlocks8;              // 1024
+constexpr int kChunkBytes8 = SPQT_CB8_CHUNK_BYTES;
+static_assert(kChunkBytes8 == kScaleBytes8 + kGroup * kRows8, "8-bit chunk size");
+
+inline int64_t tiles8(int64_t M) { return (M + kRows8 - 1) / kRows8; }
+
+}  // namespace
+
+extern "C" int spqt_cb8_packed_bytes(int64_t M, int64_t K, size_t *out_bytes) {
+    if (!out_bytes) return SPQT_EINVAL;
+    if (int rc = check_cb_shape(M, K)) return rc;
+    *out_bytes = (size_t)tiles8(M) * (size_t)(K / kGroup) * (size_t)kChunkBytes8;
+    return SPQT_OK;
+}
+
+extern "C" int spqt_cb8_quantize(const float *w, int64_t M, int64_t K, void *out_packed, size_t out_bytes) {
+    if (!w || !out_packed) return SPQT_EINVAL;
+    size_t need = 0;
+    if (int rc = spqt_cb8_packed_bytes(M, K, &need)) return rc;
+    if (out_bytes < need) return SPQT_ESIZE;
+    const int64_t T = tiles8(M), NC = K / kGroup;
+    uint8_t *out = (uint8_t *)out_packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        for (int64_t c = 0; c < NC; ++c) {
+            uint8_t *chunk = out + (size_t)(t * NC + c) * kChunkBytes8;
+            for (int j = 0; j < kGroup; ++j) {
+                const int64_t k = c * kGroup + j;
+                for (int b = 0; b < kBlocks8; ++b) {
+                    // rows past M count as zero weights
+                    float v[kBlockRows];
+                    float amax = 0.0f;
+                    for (int r = 0; r < kBlockRows; ++r) {
+                        const int64_t m = t * kRows8 + b * kBlockRows + r;
+                        v[r] = m < M ? w[(size_t)m * K + k] : 0.0f;
+                        amax = std::max(amax, std::fabs(v[r]));
+                    }
+                    const uint16_t h = float_to_half_bits(amax / 127.0f);
+                    chunk[8 * j + 2 * b] = (uint8_t)(h & 0xFF);
+                    chunk[8 * j + 2 * b + 1] = (uint8_t)(h >> 8);
+                    const float sc = half_bits_to_float(h);
+                    for (int r = 0; r < kBlockRows; ++r) {
+                        int q = 0;
+                        if (sc > 0.0f) q = (int)std::min(127.0f, std::max(-128.0f, std::nearbyintf(v[r] / sc)));
+                        chunk[kScaleBytes8 + 128 * j + b * kBlockRows + r] = (uint8_t)(q + 128);
+                    }
+                }
+            }
+        }
+    });
+    return SPQT_OK;
+}
+
+extern "C" int spqt_cb8_dequantize(const void *packed, int64_t M, int64_t K, float *w_out) {
+    if (!packed || !w_out) return SPQT_EINVAL;
+    if (int rc = check_cb_shape(M, K)) return rc;
+    const int64_t T = tiles8(M), NC = K / kGroup;
+    const uint8_t *in = (const uint8_t *)packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        for (int64_t c = 0; c < NC; ++c) {
+            const uint8_t *chunk = in + (size_t)(t * NC + c) * kChunkBytes8;
+            for (int j = 0; j < kGroup; ++j)
+                for (int r = 0; r < kRows8 && t * kRows8 + r < M; ++r) {
+                    const int b = r / kBlockRows;
+                    const uint16_t h = (uint16_t)(chunk[8 * j + 2 * b] | (chunk[8 * j + 2 * b + 1] << 8));
+                    const int q = (int)chunk[kScaleBytes8 + 128 * j + r] - 128;
+                    w_out[(size_t)(t * kRows8 + r) * K + c * kGroup + j] = (float)q * half_bits_to_float(h);
+                }
+        }
+    });
+    return SPQT_OK;
+}

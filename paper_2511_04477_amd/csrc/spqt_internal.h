@@ -18,9 +18,10 @@ static_assert(kChunkBytes == kScaleBytes + kGroup * kColBytes, "chunk size");
 // Block-rows of a matrix with M rows; the last one is zero-padded when M is not a multiple of 256.
 inline int64_t tiles(int64_t M) { return (M + kTileRows - 1) / kTileRows; }
 
-// Bytes reserved at the head of the workspace for the per-block-row epoch counters.
+// Bytes reserved at the head of the workspace for the per-block-row epoch counters (two per
+// 256 rows: the 8-bit layout's block-rows are 128 rows high).
 inline size_t counter_bytes(int64_t M) {
-    size_t n = (size_t)tiles(M) * sizeof(int32_t);
+    size_t n = (size_t)tiles(M) * 2 * sizeof(int32_t);
     return (n + 255) & ~(size_t)255;
 }
 

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions(header="spqt.h"):
     text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spqt_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(spqt_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_calibration_library_exports_every_declared_symbol():
@@ -96,6 +96,27 @@ def test_kquant_quantizer_matches_oracle_bit_exact(M, K):
     assert np.array_equal(back, ck.dequant(p).astype(np.float32))
 
 
+@pytest.mark.parametrize("M,K", [(128, 128), (384, 384), (1024, 512), (1, 128), (130, 256), (255, 128)])
+def test_eight_bit_quantizer_matches_oracle_bit_exact(M, K):
+    """8-bit flavour: every scale bit and every code of the library's quantizer equals the oracle's
+    (independent NumPy code, same fp32 rule), also on a ragged M (missing rows count as zero weights);
+    the library's dequantizer gives the oracle's values."""
+    from oracle import colblock_w8 as c8
+    from workloads import make_fp_weights
+    W = make_fp_weights(128 * ((M + 127) // 128), K, 700 + M + K)[:M].copy()
+    if M >= 96:
+        W[0:32, 3] = 0.0                      # an all-zero block
+        W[32:64, 7] = np.float32(1e-9)        # a block whose scale underflows to zero
+        W[64:96, 11] = [(-1) ** r * 0.5 * (r % 255) for r in range(32)]   # exact ties under scale 2^-k
+    got = spqt.spqt_cb8_quantize(W)
+    q, s = c8.quantize(c8.pad_rows(W))
+    want = c8.pack(q, s)
+    assert got.nbytes == want.nbytes == spqt.spqt_cb8_packed_bytes(M, K) == ((M + 127) // 128) * (K // 128) * spqt.CB8_CHUNK_BYTES
+    assert np.array_equal(got, want)
+    back = spqt.spqt_cb8_dequantize(got, M, K)
+    assert back.shape == (M, K) and np.array_equal(back.astype(np.float64), c8.dequant(q, s)[:M])
+
+
 def test_colblock_bad_arguments():
     L = spqt.lib()
     out = ctypes.c_size_t()
@@ -115,6 +136,13 @@ def test_colblock_bad_arguments():
     assert L.spqt_cbk_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
     assert L.spqt_cbk_gemv(None, 256, 128, 16, None, None, 16, None, 0, None, None) == -1
     assert L.spqt_cbk_gemv(128, 256, 100, 16, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb8_packed_bytes(128, 100, ctypes.byref(out)) == -2
+    assert L.spqt_cb8_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
+    assert L.spqt_cb8_quantize(None, 256, 128, vp(small), small.nbytes) == -1
+    assert L.spqt_cb8_gemv(None, 256, 128, 16, None, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cb8_gemv(128, 256, 100, 16, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb8_gemv(64, 256, 128, 16, None, None, 16, None, 0, None, None) == -3
+    assert L.spqt_cb8_gemv(128, 256, 128, 16, 16, None, 16, None, 0, None, None) == -1   # idx without count
 
 
 def test_status_strings():
