@@ -801,6 +801,32 @@ def pmc_pass_large(torch, spqt, which):
             for i in range(wl.copies):
                 fn(i)
         kept, dense, copies = wl.mean_kept_bytes, wl.dense_bytes, wl.copies
+    elif which == "gate70b_w8":
+        pbytes = spqt.spqt_cb8_packed_bytes(M, K)
+        copies = max(2, -(-ROTATE_BYTES // pbytes))
+        T, NC = M // 128, K // 128
+        g = torch.Generator(device=dev)
+        g.manual_seed(9201)
+        packed = []
+        for _ in range(copies):
+            buf = torch.randint(0, 256, (T * NC, spqt.CB8_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NC, 512), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
+            buf[:, :1024] = sc.view(torch.uint8)
+            packed.append(buf.reshape(-1))
+        x_np = make_x(K, "laplace", 9202)
+        thr = quantile_threshold(x_np, s)
+        x = torch.from_numpy(x_np[0]).to(dev)
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        y = torch.empty(M, dtype=torch.float32, device=dev)
+        ws = spqt.new_workspace(M, K)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        torch.cuda.synchronize()
+        for i in range(copies):
+            spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws)
+        for i in range(copies):
+            spqt.spqt_cb8_gemv(packed[i], M, K, x, None, None, y, ws)
+        kept, dense = int(cnt.item()) * (M + M // 16), pbytes
     else:
         pbytes = spqt.spqt_cb_packed_bytes(M, K)
         copies = max(2, -(-ROTATE_BYTES // pbytes))
@@ -846,7 +872,7 @@ def main():
     ap.add_argument("--pmc-pass", action="store_true",
                     help="for hardware-counter runs: launch only a 64 MiB calibration copy (x8) and the "
                          "headline sparse GEMV once per weight copy, eagerly, and exit")
-    ap.add_argument("--pmc-workload", choices=["headline", "gate70b", "gate70b_colblock"], default="headline",
+    ap.add_argument("--pmc-workload", choices=["headline", "gate70b", "gate70b_colblock", "gate70b_w8"], default="headline",
                     help="with --pmc-pass: which sparse GEMV to launch (4096x4096 group layout, 28672x8192 group "
                          "layout, 28672x8192 column-block layout), all at 50 %%")
     args = ap.parse_args()
