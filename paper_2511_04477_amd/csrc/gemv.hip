@@ -22,8 +22,19 @@
 //     step.  The index entries of the next pass are requested before the weights of this one.
 //   - int4 -> float costs no conversion instruction: a stored code n in 0..15 masked in
 //     place at bit 0..3 (or 4..7) of a 16-bit half IS the fp16 subnormal n*2^-24 (or
-//     16n*2^-24), which v_fma_mix_f32 multiplies by a pre-scaled x*2^24 (x*2^20) into the fp32
-//     accumulator - exact products, fp32 accumulation.
+//     16n*2^-24).
+//   - the multiply-accumulate runs on the matrix cores, used as 4-wide dot-product units rather
+//     than for a tiled GEMM: v_mfma_f32_4x4x4_16B_f16 computes, per group of 4 adjacent lanes
+//     (which read the same columns), D[m][n] += sum over 4 k of A[m][k] * B[k][n] with n = the
+//     lane (its own rows), k = four of the pass's columns, m = the activation row.  B is one
+//     row's codes at 4 columns (the subnormals above, two columns per register after one
+//     v_perm_b32), A the raw fp16 x of those columns - exact products, fp32 accumulation.  The
+//     kernel was bound by VALU issue (8 multiply-adds + 5 unpack instructions per 8 codes and
+//     activation row); on the matrix cores 8 codes cost 6 VALU instructions and 2 matrix
+//     instructions for ALL activation rows.  With one activation row, x sits in row v of A for
+//     the v-th of 4 consecutive rows of W, so the 4 results share one accumulator tuple.
+//     (Building with -DSPQT_SINGLE_ROW_ON_MATRIX_CORES=0 gives the plain v_fma_mix_f32 multiply
+//     for one activation row: x pre-scaled by 2^24 or 2^20, one instruction per code.)
 //   - per pass: the 8 column-lanes are folded with a transposing butterfly (bank-masked DPP
 //     adds, then permlane16/32 swaps), leaving each lane 4 rows that are added to the group's
 //     running sums.  Folding every pass instead of once per group keeps the 32 accumulators
@@ -43,6 +54,11 @@
 namespace {
 
 using namespace spqt;
+
+#ifndef SPQT_SINGLE_ROW_ON_MATRIX_CORES
+#define SPQT_SINGLE_ROW_ON_MATRIX_CORES 1
+#endif
+constexpr bool kMatrixCoreSingleRow = SPQT_SINGLE_ROW_ON_MATRIX_CORES != 0;
 
 // BATCH activation rows share one pass over the weights: the index list is the union of the
 // rows' kept columns, every dequantized code is multiplied by each row's own x, and each row
@@ -65,6 +81,11 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     __shared__ uint32_t stage_off[WAVES][2][kPassCols];      // byte offset of each column of the pass
     __shared__ float stage_x[WAVES][2][BATCH][kPassCols];    // its x per batch row, pre-scaled by 2^24
     __shared__ __attribute__((aligned(16))) float red[WAVES][BATCH][kTileRows];
+    // Several activation rows: x as fp16, laid out [column group cg][row b, padded to 4][step u] so that a
+    // lane fetches the 8 values of its column group and its matrix-core row with one 16-byte read.
+    __shared__ __attribute__((aligned(16))) uint16_t stage_xh[BATCH > 1 ? WAVES : 1][2][8][4][8];
+    // One activation row on the matrix cores: x as fp16, [column group cg][step u].
+    __shared__ __attribute__((aligned(16))) uint16_t stage_x1[kMatrixCoreSingleRow && BATCH == 1 ? WAVES : 1][2][8][8];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -99,6 +120,10 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const int end = (int)(((int64_t)n_ns * (part + 1)) / parts);
 
     const uint8_t *row_base = packed + (size_t)t * NG * kChunkBytes;
+    if (BATCH > 1) {   // rows BATCH..3 of the fp16 staging area are never written: they must read as zero
+        reinterpret_cast<u32x4 *>(&stage_xh[wave][0][0][0][0])[lane] = u32x4{0u, 0u, 0u, 0u};
+        __builtin_amdgcn_wave_barrier();
+    }
 
     float yacc[BATCH][4];   // rows 32 seg + 4 rev(cg) + j, scaled and summed over groups
 #pragma unroll
@@ -166,12 +191,148 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                     reinterpret_cast<const u32x4 *>(chunk + kScaleBytes + (size_t)off[u]));
         };
 
+        // MULTIPLY stage for several activation rows, on the matrix cores.  v_mfma_f32_4x4x4_16B_f16 runs
+        // 16 independent 4x4x4 products, one per group of 4 adjacent lanes; those 4 lanes share their
+        // column group cg, so for them "k" can be 4 of the pass's steps (4 columns), "n" the lane itself
+        // (its own 32 rows, one row per instruction) and "m" the activation row: A = x of row (lane & 3)
+        // at the 4 columns (raw fp16 bits, exact), B = this lane's code of one row at the 4 columns as
+        // fp16 subnormals (code * 2^-24, or 16 * code * 2^-24 from the upper bits of a byte), D = the
+        // 4 activation rows' partial sums for that row of W.  Two such quads of steps make a pass.
+        // With chunk_next != nullptr the registers of a quad are refilled with the next pass's
+        // weights as soon as the quad has been consumed.
+        auto multiply_rows = [&](int n, const uint32_t(&xraw)[BATCH], int slot, u32x4(&w)[8],
+                                 const uint8_t *chunk_next, const uint32_t *off_next) {
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const uint32_t hb = lane < n ? xraw[b] : 0u;
+                xsum[b] += half_bits_to_float(hb) * kTwo24;
+                stage_xh[wave][slot][lane & 7][b][lane >> 3] = (uint16_t)hb;
+            }
+            __builtin_amdgcn_wave_barrier();
+            const u32x4 xa = *reinterpret_cast<const u32x4 *>(&stage_xh[wave][slot][cg][lane & 3][0]);
+            f32x4 accq[32];     // accq[8 d + p][b]: row 8 d + p of the lane's 32, activation row b
+#pragma unroll
+            for (int quad = 0; quad < 2; ++quad) {
+                if (quad == 0 || n > 32) {
+                    const f16x4 a = as_f16x4(quad == 0 ? u32x2{xa.x, xa.y} : u32x2{xa.z, xa.w});
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const uint32_t w0 = w[4 * quad + 0][d], w1 = w[4 * quad + 1][d];
+                        const uint32_t w2 = w[4 * quad + 2][d], w3 = w[4 * quad + 3][d];
+#pragma unroll
+                        for (int half = 0; half < 2; ++half) {
+                            // the same 16 bits (4 codes, rows 4 half .. 4 half + 3 of the dword) of two columns side by side
+                            const uint32_t sel = half ? 0x07060302u : 0x05040100u;
+                            const uint32_t t01 = __builtin_amdgcn_perm(w1, w0, sel);
+                            const uint32_t t23 = __builtin_amdgcn_perm(w3, w2, sel);
+                            const uint32_t s01 = t01 >> 8, s23 = t23 >> 8;
+                            const u32x2 b0 = {t01 & 0x000F000Fu, t23 & 0x000F000Fu};
+                            const u32x2 b1 = {t01 & 0x00F000F0u, t23 & 0x00F000F0u};
+                            const u32x2 b2 = {s01 & 0x000F000Fu, s23 & 0x000F000Fu};
+                            const u32x2 b3 = {s01 & 0x00F000F0u, s23 & 0x00F000F0u};
+                            const int q = 8 * d + 4 * half;
+                            const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+                            accq[q + 0] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b0), quad ? accq[q + 0] : zero, 0, 0, 0);
+                            accq[q + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b1), quad ? accq[q + 1] : zero, 0, 0, 0);
+                            accq[q + 2] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b2), quad ? accq[q + 2] : zero, 0, 0, 0);
+                            accq[q + 3] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b3), quad ? accq[q + 3] : zero, 0, 0, 0);
+                        }
+                    }
+                }
+                if (chunk_next) {
+#pragma unroll
+                    for (int u = 4 * quad; u < 4 * quad + 4; ++u)
+                        w[u] = __builtin_nontemporal_load(
+                            reinterpret_cast<const u32x4 *>(chunk_next + kScaleBytes + (size_t)off_next[u]));
+                }
+            }
+            // the products are code * 2^-24 * x (16 times that in the odd rows of a byte)
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                float col[32], r4[4];
+#pragma unroll
+                for (int q = 0; q < 32; ++q) col[q] = accq[q][b];
+                fold_columns(col, r4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gacc[b][j] = __builtin_fmaf(r4[j], (j & 1) ? kTwo24 * 0.0625f : kTwo24, gacc[b][j]);
+            }
+            fresh = false;
+            __builtin_amdgcn_wave_barrier();
+        };
+
+        // MULTIPLY stage for ONE activation row on the matrix cores.  Same operands as multiply_rows, but
+        // a 4x4x4 product has room for 4 rows of A and only one is needed: x is placed in row v of A
+        // (zeros elsewhere) for the v-th of four consecutive rows of W, so the four results land in the
+        // four registers of ONE accumulator tuple and the 32 rows of a lane need 8 tuples = 32 registers.
+        auto multiply_one = [&](int n, uint32_t xraw, int slot, u32x4(&w)[8]) {
+            if (FUSED) {    // the fused fetch stage has already staged x; xraw carries this lane's share
+                xsum[0] += as_float(xraw);
+            } else {
+                const uint32_t hb = lane < n ? xraw : 0u;
+                xsum[0] += half_bits_to_float(hb) * kTwo24;
+                stage_x1[wave][slot][lane & 7][lane >> 3] = (uint16_t)hb;
+            }
+            __builtin_amdgcn_wave_barrier();
+            const u32x4 xa = *reinterpret_cast<const u32x4 *>(&stage_x1[wave][slot][cg][0]);
+            f32x4 accq[8];      // accq[2 d + half][p]: row 8 d + 4 half + p of the lane's 32
+#pragma unroll
+            for (int quad = 0; quad < 2; ++quad) {
+                if (quad == 0 || n > 32) {
+                    f16x4 a[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const bool mine = (lane & 3) == v;
+                        a[v] = as_f16x4(u32x2{mine ? (quad ? xa.z : xa.x) : 0u, mine ? (quad ? xa.w : xa.y) : 0u});
+                    }
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const uint32_t w0 = w[4 * quad + 0][d], w1 = w[4 * quad + 1][d];
+                        const uint32_t w2 = w[4 * quad + 2][d], w3 = w[4 * quad + 3][d];
+#pragma unroll
+                        for (int half = 0; half < 2; ++half) {
+                            const uint32_t sel = half ? 0x07060302u : 0x05040100u;
+                            const uint32_t t01 = __builtin_amdgcn_perm(w1, w0, sel);
+                            const uint32_t t23 = __builtin_amdgcn_perm(w3, w2, sel);
+                            const uint32_t s01 = t01 >> 8, s23 = t23 >> 8;
+                            const u32x2 b0 = {t01 & 0x000F000Fu, t23 & 0x000F000Fu};
+                            const u32x2 b1 = {t01 & 0x00F000F0u, t23 & 0x00F000F0u};
+                            const u32x2 b2 = {s01 & 0x000F000Fu, s23 & 0x000F000Fu};
+                            const u32x2 b3 = {s01 & 0x00F000F0u, s23 & 0x00F000F0u};
+                            const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+                            f32x4 c = quad ? accq[2 * d + half] : zero;
+                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[0], as_f16x4(b0), c, 0, 0, 0);
+                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[1], as_f16x4(b1), c, 0, 0, 0);
+                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[2], as_f16x4(b2), c, 0, 0, 0);
+                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[3], as_f16x4(b3), c, 0, 0, 0);
+                            accq[2 * d + half] = c;
+                        }
+                    }
+                }
+            }
+            float col[32], r4[4];
+#pragma unroll
+            for (int q = 0; q < 32; ++q) col[q] = accq[q >> 2][q & 3];
+            fold_columns(col, r4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) gacc[0][j] = __builtin_fmaf(r4[j], (j & 1) ? kTwo24 * 0.0625f : kTwo24, gacc[0][j]);
+            fresh = false;
+            __builtin_amdgcn_wave_barrier();
+        };
+
         // MULTIPLY stage of a fetched pass.
         // With chunk_next != nullptr the stage is "rolling": as soon as step u has been consumed, the
         // registers of w[u] receive step u of the NEXT pass (whose FETCH head has already run), so
         // the next pass's weights fly during this pass's arithmetic without a second buffer.
         auto multiply = [&](int n, const uint32_t(&xraw)[BATCH], int slot, u32x4(&w)[8],
                             const uint8_t *chunk_next = nullptr, const uint32_t *off_next = nullptr) {
+            if (BATCH > 1) {
+                multiply_rows(n, xraw, slot, w, chunk_next, off_next);
+                return;
+            }
+            if (kMatrixCoreSingleRow) {
+                multiply_one(n, xraw[0], slot, w);
+                return;
+            }
             if (FUSED) {    // the fused fetch stage has already staged x; xraw carries this lane's share
                 xsum[0] += as_float(xraw[0]);
             } else {
@@ -186,7 +347,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             // The pass's products live only inside this stage: the first step overwrites the 32
             // accumulators, the others add to them, and the fold at the end leaves 4 sums per lane.
             float acc[BATCH][32];
-            if (BATCH == 1) {
+            {
                 float xl[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) xl[u] = stage_x[wave][slot][0][u * 8 + cg];
@@ -194,23 +355,6 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
 #pragma unroll
                 for (int u = 1; u < 8; ++u)
                     if (u * 8 < n) fma_step<false>(w[u], xl[u], acc[0]);
-            } else {
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if (u == 0 || u * 8 < n) {
-                        float xl[BATCH];
-#pragma unroll
-                        for (int b = 0; b < BATCH; ++b) xl[b] = stage_x[wave][slot][b][u * 8 + cg];
-#pragma unroll
-                        for (int b = 0; b < BATCH; ++b) {
-                            if (u == 0) fma_step<true>(w[u], xl[b], acc[b]);
-                            else fma_step<false>(w[u], xl[b], acc[b]);
-                        }
-                    }
-                    if (chunk_next)
-                        w[u] = __builtin_nontemporal_load(
-                            reinterpret_cast<const u32x4 *>(chunk_next + kScaleBytes + (size_t)off_next[u]));
-                }
             }
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
@@ -274,6 +418,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                 xs_bits = as_u32(xs);   // added to the group's bias sum when the unit is multiplied
                 stage_off[wave][slot][entry] = keep ? koff_own : koff_first;
                 stage_x[wave][slot][0][entry] = xs;
+                if (kMatrixCoreSingleRow) stage_x1[wave][slot][entry & 7][entry >> 3] = keep ? (uint16_t)xr : (uint16_t)0;
                 const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;   // wave-uniform base
                 __builtin_amdgcn_wave_barrier();
                 uint32_t off[8];
@@ -452,7 +597,10 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
     // parallelism.  Keep at least a quarter of a quantization group per wavefront.
     // Four activation rows need enough accumulator registers that two wavefronts fit per SIMD
     // instead of three: 512 workgroups of 4 wavefronts is then the whole chip, once.
-    const int64_t target = batch == 4 ? 512 : (sparse ? 512 : 1024);
+    // The dense batch-1 kernel on matrices large enough to be bandwidth-bound (>= 64 MB packed) is
+    // fastest with one wavefront per SIMD: about 256 workgroups.
+    const bool big = (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20);
+    const int64_t target = batch == 4 ? 512 : (sparse ? 512 : (big ? 256 : 1024));
     int64_t S = 1;
     while (S * 2 <= 16 && S * 2 * T <= target) S *= 2;
     while (S > 1 && S * waves > 4 * NG) S /= 2;

@@ -12,6 +12,7 @@
 namespace spqt {
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -30,6 +31,7 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
 __device__ __forceinline__ float as_float(uint32_t bits) { return __builtin_bit_cast(float, bits); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t bits) { return __builtin_bit_cast(f16x2, bits); }
+__device__ __forceinline__ f16x4 as_f16x4(u32x2 bits) { return __builtin_bit_cast(f16x4, bits); }
 
 // Eight codes of one dword: acc[i] (+)= n_i * x for nibble i (row 8d+i of the lane's 32 rows).
 // xlo = x * 2^24 pairs with nibbles sitting at bits 0..3 of a half, xhi = x * 2^20 with
