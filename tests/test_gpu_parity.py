@@ -176,6 +176,32 @@ def test_exact_arithmetic_case_is_bit_exact(gpu):
     assert np.array_equal(got.astype(np.float64), oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0))
 
 
+@pytest.mark.parametrize("batch", [1, 4])
+def test_subnormal_and_extreme_activations(gpu, batch):
+    """fp16 subnormal x must count exactly (2^-24 times a small integer times a code is exact in
+    fp32, and with power-of-two scales so is every partial sum), and x near the fp16 maximum must
+    neither overflow nor lose more than fp32 accumulation must (the bound scales with the size of
+    the terms, offset-binary bias included: 16 * scale * |x| per weight): the multiply stage feeds
+    raw fp16 bits to the matrix cores."""
+    M, K = 512, 512
+    rng = np.random.default_rng(77 + batch)
+    w = make_weights(M, K, 33)
+    w["scales"] = (2.0 ** rng.integers(-6, -2, size=(M, K // 128))).astype(np.float16)
+    tiny = (rng.integers(-7, 8, size=(batch, K)).astype(np.float64) * 2.0 ** -24).astype(np.float16)
+    assert np.all(np.abs(tiny.astype(np.float64)) < 6.2e-5)      # all subnormal (or zero)
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], tiny, 0.0)
+    for dense in (False, True):
+        got = gpu_gemv(gpu, w, tiny, 0.0, dense=dense)
+        assert np.array_equal(got.astype(np.float64), ref), dense
+    big = make_x(K, "laplace", 78, batch=batch)
+    big[:, ::17] = np.float16(60000.0) * np.sign(big[:, ::17].astype(np.float32) + 0.5).astype(np.float16)
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], big, 0.5)
+    got = gpu_gemv(gpu, w, big, 0.5)
+    err = np.abs(got.astype(np.float64) - ref)
+    terms = (16.0 * np.repeat(w["scales"].astype(np.float64), 128, axis=1)) @ np.abs(big.astype(np.float64)).T   # [M, batch]
+    assert np.all(np.isfinite(got)) and np.all(err <= ATOL + 1e-5 * terms.T), (err / terms.T).max()
+
+
 def test_column_probe(gpu):
     """x = c * e_k  =>  y = c * dequant(W[:, k]) exactly; catches any address-mapping error."""
     torch, spqt, dev = gpu
