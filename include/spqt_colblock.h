@@ -96,10 +96,16 @@ int spqt_cbk_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_p
 /* HOST.  w_out[m][k] = (d * sc_b) * q - dmin * m_b, float[M][K]. */
 int spqt_cbk_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 
-/* DEVICE, async.  As spqt_cb_gemv with batch 1, on spqt_cbk_quantize's output. */
-int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
-                  const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
-                  void *stream, const spqt_launch_cfg *cfg);
+/* DEVICE, async.  As spqt_cb_gemv (batch 1..SPQT_MAX_BATCH), on spqt_cbk_quantize's output. */
+int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
+                  const int32_t *idx_dev, const int32_t *count_dev, void *y_dev, void *workspace_dev,
+                  size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg);
+
+/* DEVICE, async.  As spqt_cb_gemv_fused (gather and GEMV in one launch, batch 1), on
+ * spqt_cbk_quantize's output. */
+int spqt_cbk_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, float threshold,
+                        void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
+                        const spqt_launch_cfg *cfg);
 
 /* ---- 8-bit flavour of the column-block layout ("ZZ-CB32-W8") --------------------------------
  * Section 4.1.2 states that the layout carries over to other bit-widths without giving one.  This

@@ -31,7 +31,7 @@ EXPORTS = [
 
 
 CB_EXPORTS = ["spqt_cb_packed_bytes", "spqt_cb_quantize", "spqt_cb_dequantize", "spqt_cb_gemv",
-              "spqt_cb_gemv_fused", "spqt_cbk_quantize", "spqt_cbk_dequantize", "spqt_cbk_gemv",
+              "spqt_cb_gemv_fused", "spqt_cbk_quantize", "spqt_cbk_dequantize", "spqt_cbk_gemv", "spqt_cbk_gemv_fused",
               "spqt_cb8_packed_bytes", "spqt_cb8_quantize", "spqt_cb8_dequantize", "spqt_cb8_gemv"]
 CB_CHUNK_BYTES = 18432
 CB8_CHUNK_BYTES = 17408
@@ -79,7 +79,8 @@ def lib() -> ctypes.CDLL:
         L.spqt_cb_gemv_fused.argtypes = [vp, i64, i64, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_cbk_quantize.argtypes = [vp, i64, i64, vp, sz]
         L.spqt_cbk_dequantize.argtypes = [vp, i64, i64, vp]
-        L.spqt_cbk_gemv.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cbk_gemv.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cbk_gemv_fused.argtypes = [vp, i64, i64, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_cb8_packed_bytes.argtypes = [i64, i64, c.POINTER(sz)]
         L.spqt_cb8_quantize.argtypes = [vp, i64, i64, vp, sz]
         L.spqt_cb8_dequantize.argtypes = [vp, i64, i64, vp]
@@ -353,13 +354,14 @@ def spqt_cbk_dequantize(packed: np.ndarray, M: int, K: int) -> np.ndarray:
 
 def spqt_cbk_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
                   waves: int = 0) -> None:
-    """K-quant column-block GEMV, batch 1 (idx/count None/None for the dense kernel)."""
+    """K-quant column-block GEMV: x fp16[K] or [batch, K] (idx/count None/None for the dense kernel)."""
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
     yp, yflags = _y_out(y)
-    if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb_packed_bytes(M, K):
-        raise SpqtError("spqt_cbk_gemv: x / y / packed sizes do not match M, K (batch 1 only)")
+    batch = 1 if x.dim() == 1 else x.shape[0]
+    if x.shape[-1] != K or y.numel() != batch * M or packed.numel() < spqt_cb_packed_bytes(M, K):
+        raise SpqtError("spqt_cbk_gemv: x / y / packed sizes do not match M, K, batch")
     ip = cp = None
     if idx is not None:
         ip = _dev(idx, torch.int32, "idx")
@@ -368,7 +370,24 @@ def spqt_cbk_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=No
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
     cfg = _cfg(splits, waves, yflags)
-    _check(lib().spqt_cbk_gemv(pp, M, K, xp, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
+    _check(lib().spqt_cbk_gemv(pp, M, K, xp, batch, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
+
+
+def spqt_cbk_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, stream=None,
+                        splits: int = 0, waves: int = 0) -> None:
+    """Threshold + compaction + K-quant column-block GEMV in one launch (batch 1)."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp, yflags = _y_out(y)
+    if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb_packed_bytes(M, K):
+        raise SpqtError("spqt_cbk_gemv_fused: x / y / packed sizes do not match M, K (batch 1 only)")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    cfg = _cfg(splits, waves, yflags)
+    _check(lib().spqt_cbk_gemv_fused(pp, M, K, xp, float(threshold), yp, wp, wbytes, _stream_ptr(stream),
+                                     ctypes.byref(cfg)))
 
 
 # ------------------------------------------------------------------ 8-bit flavour (spqt_colblock.h)

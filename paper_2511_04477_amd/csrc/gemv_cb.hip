@@ -305,7 +305,13 @@ hipError_t launch_cb_batch(int mode, int grid, hipStream_t stream, const uint8_t
                            const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
                            int K, int NC, int S, int T, int M, int y_half) {
     const dim3 g(grid), b(WAVES * 64);
-    if (mode == 0)        // index list
+    if (mode == 3)        // K-quant flavour, index list
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, BATCH, true>), g, b, 0, stream, packed, x, idx, count, y,
+                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+    else if (mode == 4)   // K-quant flavour, dense
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, BATCH, true>), g, b, 0, stream, packed, x, idx, count, y,
+                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+    else if (mode == 0)   // index list
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, BATCH>), g, b, 0, stream, packed, x, idx, count, y,
                            partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     else                  // dense
@@ -318,13 +324,9 @@ template <int WAVES>
 hipError_t launch_cb(int mode, int batch, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                      const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
                      int K, int NC, int S, int T, int M, float thr, int y_half) {
-    if (mode == 3 || mode == 4) {      // K-quant flavour, batch 1: index list / dense
-        if (mode == 3)
-            hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
-        else
-            hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                               packed, x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+    if (mode == 5) {      // K-quant flavour, threshold inside the kernel (batch 1)
+        hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream, packed,
+                           x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
         return hipGetLastError();
     }
     if (mode == 2) {      // threshold inside the kernel (batch 1)
@@ -357,7 +359,7 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
         // work, so on matrices large enough to be bandwidth-bound (>= 64 MB packed) fewer, longer
         // slices win for the batch-1 list-driven and dense kernels: about 256 workgroups instead of 512 / 1024.
         const int64_t T64 = tiles(M);
-        if (mode != 2 && batch == 1 && (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20))
+        if (mode != 2 && mode != 5 && batch == 1 && (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20))
             while (c.splits > 1 && (int64_t)c.splits * T64 > 256) c.splits /= 2;
     }
     if (cfg) {
@@ -410,11 +412,19 @@ extern "C" int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, 
                   workspace_bytes, stream, cfg);
 }
 
-extern "C" int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
+extern "C" int spqt_cbk_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev,
+                                   float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
+                                   void *stream, const spqt_launch_cfg *cfg) {
+    if (threshold != threshold) return SPQT_EINVAL;
+    return run_cb(5, 1, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev,
+                  workspace_bytes, stream, cfg);
+}
+
+extern "C" int spqt_cbk_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
                              const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                              void *workspace_dev, size_t workspace_bytes, void *stream,
                              const spqt_launch_cfg *cfg) {
     if (idx_dev && !count_dev) return SPQT_EINVAL;
-    return run_cb(idx_dev ? 3 : 4, 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
+    return run_cb(idx_dev ? 3 : 4, batch, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
                   workspace_bytes, stream, cfg);
 }

@@ -381,3 +381,52 @@ def test_cbk_full_size_sampled_tiles(gpu):
         assert_close(got[rows][None, :], ck.gemv(p, x, thr), f"cbk {M}x{K} sparse")
         assert_close(gotd[rows][None, :], ck.gemv(p, x, 0.0), f"cbk {M}x{K} dense")
         del W, packed
+
+
+@pytest.mark.parametrize("batch", [2, 3, 4])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 4), (5, 2), (16, 4)])
+def test_cbk_batch_rows_share_one_pass(gpu, batch, splits, waves):
+    """K-quant flavour with several activation rows: the union list, every row its own values."""
+    from oracle import colblock_k as ck
+    torch, spqt, dev = gpu
+    M, K = 768, 1024
+    W = make_fp_weights(M, K, 9700) + np.float32(0.01)
+    x_np = make_x(K, "laplace", 9701 + batch, batch=batch)
+    thr = quantile_threshold(x_np, 0.6)
+    say(f"cbk batch={batch} splits={splits} waves={waves}")
+    packed = torch.from_numpy(spqt.spqt_cbk_quantize(W)).to(dev)
+    x = torch.from_numpy(x_np).to(dev)
+    y = torch.full((batch, M), float("nan"), dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K, batch)
+    idx = torch.empty(K, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    spqt.spqt_gather(x, thr, idx, cnt)
+    spqt.spqt_cbk_gemv(packed, M, K, x, idx, cnt, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    p = ck.quantize(W)
+    assert_close(y.cpu().numpy(), ck.gemv(p, x_np, thr), "cbk batch")
+    y.fill_(float("nan"))
+    spqt.spqt_cbk_gemv(packed, M, K, x, None, None, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), ck.gemv(p, x_np, 0.0), "cbk batch dense")
+
+
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 1024), (1024, 4096), (300, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (7, 2), (16, 4)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9])
+def test_cbk_fused_gemv(gpu, M, K, splits, waves, sparsity):
+    """K-quant flavour, threshold inside the kernel: same result as gather + list-driven GEMV."""
+    from oracle import colblock_k as ck
+    torch, spqt, dev = gpu
+    W = make_fp_weights(256 * ((M + 255) // 256), K, 9800 + M + K)[:M].copy() + np.float32(0.01)
+    x_np = make_x(K, "laplace", 9801 + M + K)
+    thr = quantile_threshold(x_np, sparsity)
+    say(f"cbk fused M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    packed = torch.from_numpy(spqt.spqt_cbk_quantize(W)).to(dev)
+    x = torch.from_numpy(x_np[0].copy()).to(dev)
+    y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K)
+    spqt.spqt_cbk_gemv_fused(packed, M, K, x, thr, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    ref = ck.gemv(ck.quantize(ck.pad_rows(W)), x_np, thr)[:, :M]
+    assert_close(y.cpu().numpy()[None, :], ref, "cbk fused")

@@ -134,8 +134,11 @@ def test_colblock_bad_arguments():
     assert L.spqt_cb_gemv(128, 256, 128, 16, 5, None, None, 16, None, 0, None, None) == -2
     assert L.spqt_cbk_quantize(None, 256, 128, vp(small), small.nbytes) == -1
     assert L.spqt_cbk_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
-    assert L.spqt_cbk_gemv(None, 256, 128, 16, None, None, 16, None, 0, None, None) == -1
-    assert L.spqt_cbk_gemv(128, 256, 100, 16, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cbk_gemv(None, 256, 128, 16, 1, None, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cbk_gemv(128, 256, 100, 16, 1, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cbk_gemv(128, 256, 128, 16, 5, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cbk_gemv_fused(128, 256, 128, 16, ctypes.c_float(float("nan")), 16, None, 0, None, None) == -1
+    assert L.spqt_cbk_gemv_fused(None, 256, 128, 16, ctypes.c_float(0.5), 16, None, 0, None, None) == -1
     assert L.spqt_cb8_packed_bytes(128, 100, ctypes.byref(out)) == -2
     assert L.spqt_cb8_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
     assert L.spqt_cb8_quantize(None, 256, 128, vp(small), small.nbytes) == -1
