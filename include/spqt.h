@@ -17,7 +17,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device calls
  *     are asynchronous on that stream and never read device results back to the host:
  *     the kept count n_ns stays on the device between spqt_gather and spqt_gemv.
- *   - Shapes: W is M (outputs) x K (inputs).  1 <= M <= 2^24, K % 128 == 0, group == 128,
+ *   - Shapes: W is M (outputs) x K (inputs).  1 <= M <= 2^24, K % 128 == 0, group 128 or 64,
  *     batch in 1..4; anything else is SPQT_ESHAPE.  M need not be a multiple of the block
  *     height: the last block-row is zero-padded in the packed form (the paper's claim of
  *     generality, Section 4.1.2, fixes no rule for a ragged edge; padding is this build's).
@@ -28,6 +28,9 @@
  * (the source is row-major group-128 int4 and is not requantized), so the unit of storage
  * is one chunk per (block-row t, group g):
  *
+ *   (written for group = 128; with group = 64 - the paper's claim that other group sizes work the
+ *    same way, Section 4.1.2 - read G = 64 for 128 in NG, in the column range of a chunk and in
+ *    its size, 512 + 128 G = 8704)
  *     T = ceil(M/256), NG = K/128, chunk (t, g) at byte offset (t*NG + g) * 16896
  *       bytes [0, 512)          fp16 bits of scale[256t + r][g], r = 0..255, little endian
  *       bytes [512 + 128c + j]  column k = 128g + c, c = 0..127, j = 0..127:

@@ -57,6 +57,12 @@ def _load():
         lib.spqt_oracle_pack.argtypes = [p, p, c.c_int64, c.c_int64, p]
         lib.spqt_oracle_unpack.restype = c.c_int
         lib.spqt_oracle_unpack.argtypes = [p, c.c_int64, c.c_int64, p, p]
+        lib.spqt_oracle_packed_bytes_g.restype = c.c_int64
+        lib.spqt_oracle_packed_bytes_g.argtypes = [c.c_int64, c.c_int64, c.c_int]
+        lib.spqt_oracle_pack_g.restype = c.c_int
+        lib.spqt_oracle_pack_g.argtypes = [p, p, c.c_int64, c.c_int64, c.c_int, p]
+        lib.spqt_oracle_unpack_g.restype = c.c_int
+        lib.spqt_oracle_unpack_g.argtypes = [p, c.c_int64, c.c_int64, c.c_int, p, p]
         lib.spqt_oracle_threads.restype = c.c_int
         lib.spqt_oracle_threads.argtypes = []
         _lib = lib
@@ -152,26 +158,29 @@ def partition(n_ns: int, parts: int):
     return out
 
 
-def packed_bytes(M: int, K: int) -> int:
-    return int(_load().spqt_oracle_packed_bytes(M, K))
+def packed_bytes(M: int, K: int, group: int = 128) -> int:
+    return int(_load().spqt_oracle_packed_bytes_g(M, K, group))
 
 
-def pack(q_rowmajor: np.ndarray, scales: np.ndarray) -> np.ndarray:
+def pack(q_rowmajor: np.ndarray, scales: np.ndarray, group: int = 128) -> np.ndarray:
     q_rowmajor = np.ascontiguousarray(q_rowmajor, dtype=np.uint8)
     s = _u16(scales)
     M, K = q_rowmajor.shape[0], q_rowmajor.shape[1] * 2
-    out = np.empty(packed_bytes(M, K), dtype=np.uint8)
-    rc = _load().spqt_oracle_pack(_ptr(q_rowmajor), _ptr(s), M, K, _ptr(out))
+    if group not in (64, 128) or K % group:
+        raise ValueError("shape not packable: group must be 64 or 128 and divide K")
+    assert s.shape == (M, K // group)
+    out = np.empty(packed_bytes(M, K, group), dtype=np.uint8)
+    rc = _load().spqt_oracle_pack_g(_ptr(q_rowmajor), _ptr(s), M, K, group, _ptr(out))
     if rc != 0:
-        raise ValueError("shape not packable: K % 128 nonzero")
+        raise ValueError("shape not packable")
     return out
 
 
-def unpack(packed: np.ndarray, M: int, K: int):
+def unpack(packed: np.ndarray, M: int, K: int, group: int = 128):
     packed = np.ascontiguousarray(packed, dtype=np.uint8)
     q = np.empty((M, K // 2), dtype=np.uint8)
-    s = np.empty((M, K // 128), dtype=np.uint16)
-    rc = _load().spqt_oracle_unpack(_ptr(packed), M, K, _ptr(q), _ptr(s))
+    s = np.empty((M, K // group), dtype=np.uint16)
+    rc = _load().spqt_oracle_unpack_g(_ptr(packed), M, K, group, _ptr(q), _ptr(s))
     if rc != 0:
         raise ValueError("shape not packable")
     return q, s.view(np.float16)

@@ -175,7 +175,9 @@ void spqt_oracle_partition(int64_t n_ns, int64_t parts, int64_t j, int64_t *begi
  * all columns of block-row 0, then block-row 1, ...).  Everything finer is this build's
  * choice, because the quantization groups stay along K (no requantization):
  *
- *   R = 256 rows per tile, G = 128 columns per quantization group,
+ *   R = 256 rows per tile, G columns per quantization group (128 in the workloads of record; the
+ *   paper says other group sizes work the same way, Section 4.1.2, and G = 64 is the second one
+ *   built: read 64 for 128 in the column range and the size of a chunk below),
  *   T = ceil(M / R) block-rows, NG = K / G groups.  When M is not a multiple of R the rows
  *   M .. R*T-1 of the last block-row do not exist; they are stored as weight 0 (code 8) under
  *   scale bits 0 (the paper states no rule for a ragged edge; zero padding is this build's).
@@ -193,9 +195,14 @@ void spqt_oracle_partition(int64_t n_ns, int64_t parts, int64_t j, int64_t *begi
 #define ZZ_G 128
 #define ZZ_CH (2 * ZZ_R + ZZ_G * ZZ_R / 2)
 
+int64_t spqt_oracle_packed_bytes_g(int64_t M, int64_t K, int G)
+{
+    return ((M + ZZ_R - 1) / ZZ_R) * (K / G) * (int64_t)(2 * ZZ_R + G * ZZ_R / 2);
+}
+
 int64_t spqt_oracle_packed_bytes(int64_t M, int64_t K)
 {
-    return ((M + ZZ_R - 1) / ZZ_R) * (K / ZZ_G) * (int64_t)ZZ_CH;
+    return spqt_oracle_packed_bytes_g(M, K, ZZ_G);
 }
 
 static void set_nibble(uint8_t *byte, int high, int value)
@@ -211,28 +218,61 @@ static int get_nibble(uint8_t byte, int high)
     return high ? (byte >> 4) : (byte & 0x0F);
 }
 
-int spqt_oracle_pack(const uint8_t *q_rowmajor, const uint16_t *scales, int64_t M, int64_t K,
-                     uint8_t *out)
+int spqt_oracle_pack_g(const uint8_t *q_rowmajor, const uint16_t *scales, int64_t M, int64_t K,
+                       int G, uint8_t *out)
 {
-    if (M <= 0 || K <= 0 || K % ZZ_G)
+    if (M <= 0 || K <= 0 || (G != 64 && G != 128) || K % G)
         return -1;
-    int64_t T = (M + ZZ_R - 1) / ZZ_R, NG = K / ZZ_G;
-    memset(out, 0, (size_t)spqt_oracle_packed_bytes(M, K));
+    int64_t T = (M + ZZ_R - 1) / ZZ_R, NG = K / G, CH = 2 * ZZ_R + G * ZZ_R / 2;
+    memset(out, 0, (size_t)spqt_oracle_packed_bytes_g(M, K, G));
     for (int64_t t = 0; t < T; ++t)
         for (int64_t g = 0; g < NG; ++g) {
-            uint8_t *chunk = out + (t * NG + g) * ZZ_CH;
+            uint8_t *chunk = out + (t * NG + g) * CH;
             for (int r = 0; r < ZZ_R; ++r) {
                 uint16_t s = (t * ZZ_R + r < M) ? scales[(t * ZZ_R + r) * NG + g] : 0;
                 chunk[2 * r] = (uint8_t)(s & 0xFF);
                 chunk[2 * r + 1] = (uint8_t)(s >> 8);
             }
-            for (int c = 0; c < ZZ_G; ++c)
+            for (int c = 0; c < G; ++c)
                 for (int j = 0; j < ZZ_R / 2; ++j)
                     for (int half = 0; half < 2; ++half) {
                         int64_t m = t * ZZ_R + 2 * j + half;
-                        int64_t k = g * ZZ_G + c;
+                        int64_t k = g * G + c;
                         int q = (m < M) ? source_code(q_rowmajor, K, m, k) : 0;
                         set_nibble(&chunk[512 + 128 * c + j], half, q + 8);
+                    }
+        }
+    return 0;
+}
+
+int spqt_oracle_pack(const uint8_t *q_rowmajor, const uint16_t *scales, int64_t M, int64_t K,
+                     uint8_t *out)
+{
+    return spqt_oracle_pack_g(q_rowmajor, scales, M, K, ZZ_G, out);
+}
+
+int spqt_oracle_unpack_g(const uint8_t *packed, int64_t M, int64_t K, int G, uint8_t *q_rowmajor,
+                         uint16_t *scales)
+{
+    if (M <= 0 || K <= 0 || (G != 64 && G != 128) || K % G)
+        return -1;
+    int64_t T = (M + ZZ_R - 1) / ZZ_R, NG = K / G, CH = 2 * ZZ_R + G * ZZ_R / 2;
+    memset(q_rowmajor, 0, (size_t)(M * (K / 2)));
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t g = 0; g < NG; ++g) {
+            const uint8_t *chunk = packed + (t * NG + g) * CH;
+            for (int r = 0; r < ZZ_R && t * ZZ_R + r < M; ++r)
+                scales[(t * ZZ_R + r) * NG + g] =
+                    (uint16_t)(chunk[2 * r] | ((uint16_t)chunk[2 * r + 1] << 8));
+            for (int c = 0; c < G; ++c)
+                for (int j = 0; j < ZZ_R / 2; ++j)
+                    for (int half = 0; half < 2; ++half) {
+                        int64_t m = t * ZZ_R + 2 * j + half;
+                        int64_t k = g * G + c;
+                        if (m >= M)
+                            continue; /* padding row */
+                        int q = get_nibble(chunk[512 + 128 * c + j], half) - 8; /* [-8,7] */
+                        set_nibble(&q_rowmajor[m * (K / 2) + k / 2], (int)(k % 2), q);
                     }
         }
     return 0;
@@ -241,28 +281,7 @@ int spqt_oracle_pack(const uint8_t *q_rowmajor, const uint16_t *scales, int64_t 
 int spqt_oracle_unpack(const uint8_t *packed, int64_t M, int64_t K, uint8_t *q_rowmajor,
                        uint16_t *scales)
 {
-    if (M <= 0 || K <= 0 || K % ZZ_G)
-        return -1;
-    int64_t T = (M + ZZ_R - 1) / ZZ_R, NG = K / ZZ_G;
-    memset(q_rowmajor, 0, (size_t)(M * (K / 2)));
-    for (int64_t t = 0; t < T; ++t)
-        for (int64_t g = 0; g < NG; ++g) {
-            const uint8_t *chunk = packed + (t * NG + g) * ZZ_CH;
-            for (int r = 0; r < ZZ_R && t * ZZ_R + r < M; ++r)
-                scales[(t * ZZ_R + r) * NG + g] =
-                    (uint16_t)(chunk[2 * r] | ((uint16_t)chunk[2 * r + 1] << 8));
-            for (int c = 0; c < ZZ_G; ++c)
-                for (int j = 0; j < ZZ_R / 2; ++j)
-                    for (int half = 0; half < 2; ++half) {
-                        int64_t m = t * ZZ_R + 2 * j + half;
-                        int64_t k = g * ZZ_G + c;
-                        if (m >= M)
-                            continue; /* padding row */
-                        int q = get_nibble(chunk[512 + 128 * c + j], half) - 8; /* [-8,7] */
-                        set_nibble(&q_rowmajor[m * (K / 2) + k / 2], (int)(k % 2), q);
-                    }
-        }
-    return 0;
+    return spqt_oracle_unpack_g(packed, M, K, ZZ_G, q_rowmajor, scales);
 }
 
 int spqt_oracle_threads(void)

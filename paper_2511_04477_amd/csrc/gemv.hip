@@ -119,7 +119,10 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     int pos = (int)(((int64_t)n_ns * part) / parts);
     const int end = (int)(((int64_t)n_ns * (part + 1)) / parts);
 
-    const uint8_t *row_base = packed + (size_t)t * NG * kChunkBytes;
+    // quantization groups of 128 or 64 columns: NG tells which (K % 128 == 0 either way)
+    const int log2g = (NG << 7) == K ? 7 : 6;
+    const int chunk_b = kScaleBytes + (kColBytes << log2g);
+    const uint8_t *row_base = packed + (size_t)t * NG * chunk_b;
     if (BATCH > 1) {   // rows BATCH..3 of the fp16 staging area are never written: they must read as zero
         reinterpret_cast<u32x4 *>(&stage_xh[wave][0][0][0][0])[lane] = u32x4{0u, 0u, 0u, 0u};
         __builtin_amdgcn_wave_barrier();
@@ -160,18 +163,18 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         auto fetch_head = [&](int kk, int p, int slot, const uint8_t *&chunk_out, uint32_t(&off)[8], int &n_out,
                               int &g_out, uint32_t(&xraw_out)[BATCH], u32x2 &sc_out, int &k_after) {
             const bool any = p < end;
-            const int g = any ? (__builtin_amdgcn_readfirstlane(kk) >> 7) : 0;
-            const bool in = any && ((kk >> 7) == g);
+            const int g = any ? (__builtin_amdgcn_readfirstlane(kk) >> log2g) : 0;
+            const bool in = any && ((kk >> log2g) == g);
             const int n = __builtin_amdgcn_readfirstlane((int)__popcll(__ballot(in)));
             k_after = fetch_k(p + n);
             // Lanes outside the pass point at the pass's first column and later carry x = 0:
             // they re-read a line that is being fetched anyway.
-            const uint32_t koff_in = (uint32_t)(kk & (kGroup - 1)) * kColBytes;
+            const uint32_t koff_in = (uint32_t)(kk & ((1 << log2g) - 1)) * kColBytes;
             const uint32_t koff_first = any ? (uint32_t)__builtin_amdgcn_readfirstlane((int)koff_in) : 0u;
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) xraw_out[b] = x[(size_t)b * K + (in ? kk : 0)];
             stage_off[wave][slot][lane] = in ? koff_in : koff_first;
-            const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;   // wave-uniform base
+            const uint8_t *chunk = row_base + (size_t)g * chunk_b;   // wave-uniform base
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int u = 0; u < 8; ++u) off[u] = stage_off[wave][slot][u * 8 + cg] + seg16;
@@ -397,7 +400,8 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             auto fetch_unit = [&](uint32_t xr, int u, int slot, u32x4(&w)[8], int &n_out, int &g_out,
                                   u32x2 &sc_out, uint32_t &xr_next, uint32_t &xs_bits) {
                 const bool any = u < end;
-                const int g = any ? (u >> 1) : 0;
+                const int upg = log2g - 6;                      // log2 of the 64-column units per group
+                const int g = any ? (u >> upg) : 0;
                 const float xf = half_bits_to_float(xr);
                 const bool keep = any && !(__builtin_fabsf(xf) < thr);
                 const uint64_t mask = __ballot(keep);
@@ -411,15 +415,16 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                 // kept columns go to entries 0..n-1 in ascending order; the other lanes fill entries
                 // n..63 with the pass's first kept column and x = 0
                 const int first_lane = n ? (int)__builtin_ctzll(mask) : 0;
-                const uint32_t koff_first = (uint32_t)(((u & 1) * kPassCols + first_lane) * kColBytes);
-                const uint32_t koff_own = (uint32_t)(((u & 1) * kPassCols + lane) * kColBytes);
+                const int uin = u & ((1 << upg) - 1);             // unit inside its group
+                const uint32_t koff_first = (uint32_t)((uin * kPassCols + first_lane) * kColBytes);
+                const uint32_t koff_own = (uint32_t)((uin * kPassCols + lane) * kColBytes);
                 const int entry = FUSED == 2 ? lane : (keep ? rank : n + lane - rank);
                 const float xs = keep ? xf * kTwo24 : 0.0f;
                 xs_bits = as_u32(xs);   // added to the group's bias sum when the unit is multiplied
                 stage_off[wave][slot][entry] = keep ? koff_own : koff_first;
                 stage_x[wave][slot][0][entry] = xs;
                 if (kMatrixCoreSingleRow) stage_x1[wave][slot][entry & 7][entry >> 3] = keep ? (uint16_t)xr : (uint16_t)0;
-                const uint8_t *chunk = row_base + (size_t)g * kChunkBytes;   // wave-uniform base
+                const uint8_t *chunk = row_base + (size_t)g * chunk_b;   // wave-uniform base
                 __builtin_amdgcn_wave_barrier();
                 uint32_t off[8];
 #pragma unroll
@@ -643,7 +648,7 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
 
-    const int T = (int)tiles(M), NG = (int)(K / kGroup);
+    const int T = (int)tiles(M), NG = (int)(K / group);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
     const bool dense = idx_dev == nullptr;
     hipStream_t st = (hipStream_t)stream;
@@ -687,7 +692,7 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
         epochs = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
-    const int T = (int)tiles(M), NG = (int)(K / kGroup);
+    const int T = (int)tiles(M), NG = (int)(K / group);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
     const bool compact = !(cfg && (cfg->flags & SPQT_CFG_NO_COMPACTION));
     hipStream_t st = (hipStream_t)stream;

@@ -25,8 +25,11 @@ inline size_t counter_bytes(int64_t M) {
     return (n + 255) & ~(size_t)255;
 }
 
+// Bytes of one chunk (block-row t, group g) of the group layout: 256 fp16 scales + `group` column runs.
+inline int chunk_bytes(int group) { return kScaleBytes + group * kColBytes; }
+
 inline int check_shape(int64_t M, int64_t K, int group) {
-    if (group != kGroup) return SPQT_ESHAPE;
+    if (group != kGroup && group != kGroup / 2) return SPQT_ESHAPE;
     if (M <= 0 || K <= 0 || K % kGroup != 0) return SPQT_ESHAPE;
     if (M > (int64_t)1 << 24 || K > (int64_t)1 << 24) return SPQT_ESHAPE;
     return SPQT_OK;

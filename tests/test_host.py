@@ -163,6 +163,17 @@ def test_pack_matches_oracle_packer_bit_exact(M, K):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("M,K", [(256, 128), (512, 1024), (300, 640)])
+def test_pack_group_64_matches_oracle_and_round_trips(M, K):
+    """Quantization groups of 64 columns: same layout with 64-column chunks."""
+    w = make_weights(M, K, 1100 + M + K, group=64)
+    got = spqt.spqt_pack(w["q_rowmajor"], w["scales"], group=64)
+    assert got.nbytes == spqt.spqt_packed_bytes(M, K, 64) == ((M + 255) // 256) * (K // 64) * (512 + 64 * 128)
+    assert np.array_equal(got, oracle.pack(w["q_rowmajor"], w["scales"], group=64))
+    q2, s2 = spqt.spqt_unpack(got, M, K, group=64)
+    assert np.array_equal(q2, w["q_rowmajor"]) and np.array_equal(s2.view(np.uint16), w["scales"].view(np.uint16))
+
+
 def test_pack_extreme_codes_and_scale_bits():
     M, K = 256, 256
     raw = np.zeros((M, K // 2), dtype=np.uint8)
@@ -234,7 +245,7 @@ def test_sizes():
     assert spqt.spqt_workspace_bytes(4096, 4096) >= 4096 * 4 * spqt.MAX_SPLITS
 
 
-@pytest.mark.parametrize("M,K,group", [(256, 127, 128), (256, 128, 64), (0, 128, 128), ((1 << 24) + 1, 128, 128),
+@pytest.mark.parametrize("M,K,group", [(256, 127, 128), (256, 128, 32), (256, 128, 256), (0, 128, 128), ((1 << 24) + 1, 128, 128),
                                        (256, 0, 128), (-256, 128, 128)])
 def test_bad_shapes_are_rejected(M, K, group):
     out = ctypes.c_size_t()

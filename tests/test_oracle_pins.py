@@ -331,6 +331,44 @@ def test_pack_position_encoding_matrix():
         assert int(p[off]) | (int(p[off + 1]) << 8) == int(sc[m, g])
 
 
+def test_gemv_group_64_against_independent_expression():
+    """Groups of 64 columns in the oracle's GEMV: threshold 0 equals (q * S repeated 64 times) @ x, and a
+    threshold drops exactly the columns np.flatnonzero would."""
+    w = make_weights(256, 512, 6464, group=64)
+    x = make_x(512, "laplace", 6465)
+    Wd = w["q"].astype(np.float64) * np.repeat(w["scales"].astype(np.float64), 64, axis=1)
+    got = oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0, group=64)[0]
+    assert np.allclose(got, Wd @ x[0].astype(np.float64), rtol=1e-12, atol=1e-12)
+    keep = ~(np.abs(x[0].astype(np.float32)) < np.float32(0.7))
+    got = oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.7, group=64)[0]
+    assert np.allclose(got, Wd[:, keep] @ x[0, keep].astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_pack_group_64_closed_form_positions():
+    """Groups of 64 columns: chunk (t, g) is 512 + 64 * 128 = 8704 bytes and holds columns 64 g .. 64 g + 63;
+    every code and scale sits at its closed-form place, and the oracle's own dequantizer with group = 64
+    reads the same source the packer was given."""
+    M, K, Gq = 512, 384, 64
+    NGq, CHq = K // Gq, 512 + Gq * 128
+    rng = np.random.default_rng(64)
+    code = rng.integers(-8, 8, size=(M, K))
+    raw = ((code[:, 0::2] & 0xF) | ((code[:, 1::2] & 0xF) << 4)).astype(np.uint8)
+    sc = rng.integers(1, 65536, size=(M, NGq), dtype=np.uint16)
+    p = oracle.pack(raw, sc, group=Gq)
+    assert p.size == (M // 256) * NGq * CHq == oracle.packed_bytes(M, K, Gq)
+    for m, k in itertools.product(range(0, M, 13), range(0, K, 5)):
+        off = ((m // 256) * NGq + k // Gq) * CHq + 512 + (k % Gq) * 128 + (m % 256) // 2
+        nib = (p[off] >> 4) if m % 2 else (p[off] & 0xF)
+        assert nib == code[m, k] + 8, (m, k)
+    for m, g in itertools.product(range(0, M, 29), range(NGq)):
+        off = ((m // 256) * NGq + g) * CHq + 2 * (m % 256)
+        assert int(p[off]) | (int(p[off + 1]) << 8) == int(sc[m, g])
+    q2, s2 = oracle.unpack(p, M, K, group=Gq)
+    assert np.array_equal(q2, raw) and np.array_equal(s2.view(np.uint16), sc)
+    with pytest.raises(ValueError):
+        oracle.pack(raw, sc, group=32)
+
+
 def test_pack_rejects_bad_shapes():
     raw = np.zeros((256, 50), dtype=np.uint8)          # K = 100 is not a multiple of the group
     with pytest.raises(ValueError):
