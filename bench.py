@@ -307,6 +307,73 @@ def rowmajor_baseline(torch, spqt, use_graph, cpu):
     return rows
 
 
+def merged_gate_up_70b(torch, spqt, use_graph, cpu):
+    """Config 5's gate and up projections as ONE matrix (57344 x 8192; both consume the same x, paper
+    Section 5: they share a threshold): what one launch reaches when it has twice the bytes to amortize
+    its fixed costs over.  Copy 0 is the two seeded tensors stacked and is checked against the oracle on
+    sampled rows; the other copies are random packed bytes."""
+    import numpy as np
+    from workloads import CONFIG_SCALE_RANGE, make_case, make_x, quantile_threshold, seed_for, KIND_X
+    dev = torch.device("cuda:0")
+    K, Mh = 8192, 28672
+    M = 2 * Mh
+    gate, up = make_case(5, "gate", want_q=False), make_case(5, "up", want_q=False)
+    q = np.concatenate([gate["q_rowmajor"], up["q_rowmajor"]], axis=0)
+    sc = np.concatenate([gate["scales"], up["scales"]], axis=0)
+    del gate, up
+    pbytes = spqt.spqt_packed_bytes(M, K)
+    copies = max(2, -(-ROTATE_BYTES // pbytes))
+    T, NG = M // 256, K // 128
+    lo, hi = CONFIG_SCALE_RANGE[5]
+    packed = [torch.from_numpy(spqt.spqt_pack(q, sc)).to(dev)]
+    g = torch.Generator(device=dev)
+    g.manual_seed(9301)
+    for _ in range(1, copies):
+        buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
+        s16 = (torch.rand((T * NG, 256), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
+        buf[:, :512] = s16.view(torch.uint8)
+        packed.append(buf.reshape(-1))
+    x_np = make_x(K, "laplace", seed_for(5, 0, "gate", KIND_X))
+    x = torch.from_numpy(x_np[0]).to(dev)
+    idx = torch.empty(K, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    y = torch.empty(M, dtype=torch.float32, device=dev)
+    ws = spqt.new_workspace(M, K)
+    rows = []
+    sample = np.unique(np.concatenate([np.arange(0, 512), np.arange(Mh - 256, Mh + 256), np.arange(M - 512, M)]))
+    for s in (0.5, 0.7):
+        thr = quantile_threshold(x_np, s)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        torch.cuda.synchronize()
+        n = int(cnt.item())
+        if cpu.enabled:
+            ref = cpu.gemv_rows({"q_rowmajor": q, "scales": sc}, x_np, thr, sample)
+            for name, call in (("list", lambda: spqt.spqt_gemv(packed[0], M, K, x, idx, cnt, y, ws)),
+                               ("fused", lambda: spqt.spqt_gemv_fused(packed[0], M, K, x, thr, y, ws))):
+                y.fill_(float("nan"))
+                call()
+                torch.cuda.synchronize()
+                if not cpu.close(y.cpu().numpy()[sample], ref)[0]:
+                    print(f"bench.py: merged gate|up parity check FAILED ({name}, s={s})", file=sys.stderr)
+                    sys.exit(1)
+        fns = {"us_gemv": lambda i: spqt.spqt_gemv(packed[i], M, K, x, idx, cnt, y, ws),
+               "us_dense": lambda i: spqt.spqt_gemv(packed[i], M, K, x, None, None, y, ws),
+               "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
+                                                 spqt.spqt_gemv(packed[i], M, K, x, idx, cnt, y, ws)),
+               "us_fused": lambda i: spqt.spqt_gemv_fused(packed[i], M, K, x, thr, y, ws)}
+        t = {k: time_sequence(torch, f, copies, 800, 200, use_graph) for k, f in fns.items()}
+        kept = kept_bytes(M, K, n)
+        rows.append({"M": M, "K": K, "sparsity": s, "kept_frac": round(n / K, 4), **{k: round(v, 3) for k, v in t.items()},
+                     "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
+                     "frac_of_8TBps": round(kept / (t["us_gemv"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "dense_GBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9, 1),
+                     "dense_frac_of_8TBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "speedup_vs_dense": round(t["us_dense"] / t["us_gemv"], 3)})
+    del packed
+    torch.cuda.empty_cache()
+    return rows
+
+
 def eight_bit_rows(torch, spqt, use_graph, cpu):
     """The 8-bit flavour of the column-block layout (128-row block-rows, one column still one
     128-byte run) on the headline and the 70B gate shape at 50 % and dense.  Copy 0 is quantized
@@ -745,6 +812,10 @@ class CpuBaseline:
         import oracle
         return oracle.gemv(case["q_rowmajor"], case["scales"], x_np, thr)[0]
 
+    def gemv_rows(self, case, x_np, thr, rows):
+        import oracle
+        return oracle.gemv_rows(case["q_rowmajor"], case["scales"], x_np, thr, rows)[0]
+
     def colblock(self, W_rows, x_np, thr):
         """Column-block reference on a subset of whole 256-row tiles of fp32 weights."""
         from oracle import colblock as cb
@@ -1012,6 +1083,7 @@ def main():
             out["ablations"] = ablations(torch, spqt, use_graph, cpu)
             out["rowmajor_baseline"] = rowmajor_baseline(torch, spqt, use_graph, cpu)
             out["eight_bit_layout"] = eight_bit_rows(torch, spqt, use_graph, cpu)
+            out["merged_gate_up_70b"] = merged_gate_up_70b(torch, spqt, use_graph, cpu)
             out["dense_shape_sweep"] = dense_shape_sweep(torch, spqt, use_graph)
             out["speedup_grid"] = speedup_grid(torch, spqt, use_graph)
             out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),
