@@ -72,6 +72,22 @@ constexpr bool kMatrixCoreSingleRow = SPQT_SINGLE_ROW_ON_MATRIX_CORES != 0;
 // FUSED == 2 is an ablation: same test, same static ranges, but NO compaction - a dropped column
 // keeps its slot in the pass with x = 0 (and re-reads a kept column's line), so skipping saves
 // memory traffic but not one multiply step.
+// Matrix-core B operands for 4 consecutive rows of W at 4 columns.  w0..w3 are the same dword of 4
+// steps (4 columns, 8 rows each); HALF picks rows 0..3 or 4..7 of the dword.  One v_perm_b32 puts the
+// same 16 bits of two columns side by side; masked in place, b[p] holds row p's code at the 4
+// columns as fp16 subnormals: code * 2^-24 for p = 0, 2 and 16 * code * 2^-24 for p = 1, 3.
+template <int HALF>
+__device__ __forceinline__ void code_rows(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, u32x2 (&b)[4]) {
+    constexpr uint32_t sel = HALF ? 0x07060302u : 0x05040100u;
+    const uint32_t t01 = __builtin_amdgcn_perm(w1, w0, sel);
+    const uint32_t t23 = __builtin_amdgcn_perm(w3, w2, sel);
+    const uint32_t s01 = t01 >> 8, s23 = t23 >> 8;
+    b[0] = u32x2{t01 & 0x000F000Fu, t23 & 0x000F000Fu};
+    b[1] = u32x2{t01 & 0x00F000F0u, t23 & 0x00F000F0u};
+    b[2] = u32x2{s01 & 0x000F000Fu, s23 & 0x000F000Fu};
+    b[3] = u32x2{s01 & 0x00F000F0u, s23 & 0x00F000F0u};
+}
+
 template <int WAVES, bool DENSE, int BATCH, int FUSED>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
@@ -224,21 +240,14 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                         const uint32_t w2 = w[4 * quad + 2][d], w3 = w[4 * quad + 3][d];
 #pragma unroll
                         for (int half = 0; half < 2; ++half) {
-                            // the same 16 bits (4 codes, rows 4 half .. 4 half + 3 of the dword) of two columns side by side
-                            const uint32_t sel = half ? 0x07060302u : 0x05040100u;
-                            const uint32_t t01 = __builtin_amdgcn_perm(w1, w0, sel);
-                            const uint32_t t23 = __builtin_amdgcn_perm(w3, w2, sel);
-                            const uint32_t s01 = t01 >> 8, s23 = t23 >> 8;
-                            const u32x2 b0 = {t01 & 0x000F000Fu, t23 & 0x000F000Fu};
-                            const u32x2 b1 = {t01 & 0x00F000F0u, t23 & 0x00F000F0u};
-                            const u32x2 b2 = {s01 & 0x000F000Fu, s23 & 0x000F000Fu};
-                            const u32x2 b3 = {s01 & 0x00F000F0u, s23 & 0x00F000F0u};
+                            u32x2 b[4];
+                            if (half) code_rows<1>(w0, w1, w2, w3, b);
+                            else code_rows<0>(w0, w1, w2, w3, b);
                             const int q = 8 * d + 4 * half;
                             const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-                            accq[q + 0] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b0), quad ? accq[q + 0] : zero, 0, 0, 0);
-                            accq[q + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b1), quad ? accq[q + 1] : zero, 0, 0, 0);
-                            accq[q + 2] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b2), quad ? accq[q + 2] : zero, 0, 0, 0);
-                            accq[q + 3] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b3), quad ? accq[q + 3] : zero, 0, 0, 0);
+#pragma unroll
+                            for (int p = 0; p < 4; ++p)
+                                accq[q + p] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, as_f16x4(b[p]), quad ? accq[q + p] : zero, 0, 0, 0);
                         }
                     }
                 }
@@ -293,20 +302,13 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                         const uint32_t w2 = w[4 * quad + 2][d], w3 = w[4 * quad + 3][d];
 #pragma unroll
                         for (int half = 0; half < 2; ++half) {
-                            const uint32_t sel = half ? 0x07060302u : 0x05040100u;
-                            const uint32_t t01 = __builtin_amdgcn_perm(w1, w0, sel);
-                            const uint32_t t23 = __builtin_amdgcn_perm(w3, w2, sel);
-                            const uint32_t s01 = t01 >> 8, s23 = t23 >> 8;
-                            const u32x2 b0 = {t01 & 0x000F000Fu, t23 & 0x000F000Fu};
-                            const u32x2 b1 = {t01 & 0x00F000F0u, t23 & 0x00F000F0u};
-                            const u32x2 b2 = {s01 & 0x000F000Fu, s23 & 0x000F000Fu};
-                            const u32x2 b3 = {s01 & 0x00F000F0u, s23 & 0x00F000F0u};
+                            u32x2 b[4];
+                            if (half) code_rows<1>(w0, w1, w2, w3, b);
+                            else code_rows<0>(w0, w1, w2, w3, b);
                             const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
                             f32x4 c = quad ? accq[2 * d + half] : zero;
-                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[0], as_f16x4(b0), c, 0, 0, 0);
-                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[1], as_f16x4(b1), c, 0, 0, 0);
-                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[2], as_f16x4(b2), c, 0, 0, 0);
-                            c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[3], as_f16x4(b3), c, 0, 0, 0);
+#pragma unroll
+                            for (int p = 0; p < 4; ++p) c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[p], as_f16x4(b[p]), c, 0, 0, 0);
                             accq[2 * d + half] = c;
                         }
                     }
