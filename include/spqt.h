@@ -64,8 +64,8 @@ typedef enum {
 } spqt_status;
 
 #define SPQT_TILE_ROWS 256
-#define SPQT_GROUP 128
-#define SPQT_CHUNK_BYTES 16896
+#define SPQT_GROUP 128            /* default group size; 64 is accepted too */
+#define SPQT_CHUNK_BYTES 16896    /* bytes of one chunk at group size 128 */
 #define SPQT_MAX_BATCH 4
 #define SPQT_MAX_SPLITS 64   /* most workgroups that may share one block-row */
 #define SPQT_GATHER_MAX_K 65536
@@ -84,9 +84,10 @@ int spqt_packed_bytes(int64_t M, int64_t K, int group, size_t *out_bytes);
  * (the tag of a call is its block-row's epoch + 1, so words of earlier calls never match).
  * Two calls that may overlap in time (different streams) need two workspaces; calls on one
  * stream, or replays of one graph, may share one PROVIDED THEY HAVE THE SAME M (any K, batch,
- * launch shape, dense / sparse / fused, group or column-block layout): the epochs of all
+ * launch shape, dense / sparse / fused, group or 4-bit column-block layout): the epochs of all
  * block-rows then advance in step, which is what keeps leftover words from matching.  Before
- * a workspace is reused for a different M, run spqt_workspace_init on it again. */
+ * a workspace is reused for a different M, or between the 8-bit column-block entry point (whose
+ * block-rows are 128 rows high) and the others, run spqt_workspace_init on it again. */
 int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out_bytes);
 
 /* DEVICE, async.  Clears the whole workspace (epochs and tagged words) with a small fill
@@ -150,7 +151,7 @@ typedef struct {
  * final store (2-byte aligned).  Accumulation and the exchange of partial sums stay fp32. */
 #define SPQT_CFG_Y_FP16 4
 
-/* DEVICE, async.  y[b][m] = sum over the listed columns k of scale[m][k/128] * q[m][k] *
+/* DEVICE, async.  y[b][m] = sum over the listed columns k of scale[m][k/group] * q[m][k] *
  * x[b][k], fp32 accumulation (Section 4.2.2 for the dense kernel, Section 4.2.3 for the
  * load-balanced sparse one: the index list is split evenly over all wavefronts that work
  * on a block-row).
