@@ -1099,6 +1099,18 @@ def main():
         us_cpu, reps, cores = cpu.time_gemv(wl.case0, wl.x_np[0:1], wl.thr[0])
         out["cpu_baseline"] = {"value": round(us_cpu, 1), "unit": "us/GEMV", "cores": cores, "kind": "oracle",
                                "sample": f"{reps} repeated oracle GEMVs (mask + dequantize + dot, fp64) on copy 0 of the same 4096x4096 50% workload"}
+        if args.full:
+            # the same oracle on one tensor of each larger configuration (about 3 s each)
+            from workloads import make_case, quantile_threshold
+            others = []
+            for config, tensor in ((3, "gate"), (4, "gate"), (5, "gate")):
+                case = make_case(config, tensor, want_q=False)
+                thr = quantile_threshold(case["x"], 0.5)
+                us, reps, cores = cpu.time_gemv(case, case["x"], thr, budget_s=3.0)
+                others.append({"config": config, "tensor": tensor, "M": case["M"], "K": case["K"], "sparsity": 0.5,
+                               "us_per_gemv": round(us, 1), "repetitions": reps, "cores": cores})
+                del case
+            out["cpu_baseline_other_shapes"] = others
     print(json.dumps(out))
 
 
