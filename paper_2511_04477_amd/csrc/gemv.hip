@@ -424,8 +424,8 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                 const float xs = keep ? xf * kTwo24 : 0.0f;
                 xs_bits = as_u32(xs);   // added to the group's bias sum when the unit is multiplied
                 stage_off[wave][slot][entry] = keep ? koff_own : koff_first;
-                stage_x[wave][slot][0][entry] = xs;
                 if (kMatrixCoreSingleRow) stage_x1[wave][slot][entry & 7][entry >> 3] = keep ? (uint16_t)xr : (uint16_t)0;
+                else stage_x[wave][slot][0][entry] = xs;
                 const uint8_t *chunk = row_base + (size_t)g * chunk_b;   // wave-uniform base
                 __builtin_amdgcn_wave_barrier();
                 uint32_t off[8];
