@@ -98,6 +98,11 @@ class Workload:
     def gemv_only(self, i):
         self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
 
+    def gemv_group_passes(self, i):
+        """The index-list kernel whose passes hold columns of one quantization group (an ablation)."""
+        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws,
+                            flags=self.spqt.CFG_GROUP_PASSES)
+
     def gather_only(self, i):
         self.spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
 
@@ -138,8 +143,9 @@ def make_graph(torch, fn, n):
 def time_sequence(torch, fn, copies, steps, warmup, use_graph=True, exact_warmup=False):
     """Average microseconds per call of fn over exactly `steps` calls (after `warmup` untimed
     ones), rotating the copy index; HIP events on the launch stream bracket the timed region.
-    Side measurements get at least 200 warm-up calls (a first measurement on an idle GPU
-    otherwise reads 5-10 % high); the headline passes exact_warmup and gets exactly `warmup`."""
+    Side measurements get at least 200 warm-up calls and at least 30 ms of them (a first
+    measurement on an idle GPU otherwise reads 5-10 % high); the headline passes exact_warmup and
+    gets exactly `warmup`."""
     if not exact_warmup:
         warmup = max(warmup, 200)
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -154,6 +160,11 @@ def time_sequence(torch, fn, copies, steps, warmup, use_graph=True, exact_warmup
             for _ in range(max(1, -(-warmup // copies))):
                 full.replay()
             torch.cuda.synchronize()
+            if not exact_warmup:    # and at least 30 ms of them: after seconds of host work the clocks are down
+                t0 = time.perf_counter()
+                while time.perf_counter() - t0 < 0.03:
+                    full.replay()
+                    torch.cuda.synchronize()
             start.record()
             for _ in range(steps // copies):
                 full.replay()
@@ -229,7 +240,8 @@ def ablations(torch, spqt, use_graph, cpu):
     list's even split (Section 4.2.3) and the compaction buy?  Two activation patterns: iid
     Laplace (kept columns spread evenly) and a clustered one (7 of 8 kept columns in the first
     half of K), three kernels: list-balanced (spqt_gather + spqt_gemv), static column ranges
-    with in-kernel test and compaction (spqt_gemv_fused), the same without compaction."""
+    with in-kernel test and compaction (spqt_gemv_fused), the same without compaction.  Also the
+    list-balanced kernel with one-group passes instead of row-aligned ones (SPQT_CFG_GROUP_PASSES)."""
     import numpy as np
     from workloads import CONFIG_SCALE_RANGE
     M, K, s = 28672, 8192, 0.5
@@ -239,7 +251,7 @@ def ablations(torch, spqt, use_graph, cpu):
         # copy 0 against the oracle in every mode (the clustered pattern is not covered elsewhere at this size)
         if cpu.enabled:
             ref = cpu.gemv(w.case0, w.x_np[0:1], w.thr[0])
-            for fn in (w.step, w.fused, w.fused_no_compaction):
+            for fn in (w.step, w.gemv_group_passes, w.fused, w.fused_no_compaction):
                 w.y[0].fill_(float("nan"))
                 fn(0)
                 torch.cuda.synchronize()
@@ -248,7 +260,8 @@ def ablations(torch, spqt, use_graph, cpu):
                     sys.exit(1)
         steps = w.copies * 40
         t = {name: time_sequence(torch, fn, w.copies, steps, w.copies, use_graph)
-             for name, fn in (("list_balanced_gemv", w.gemv_only), ("gather_plus_list_balanced_gemv", w.step),
+             for name, fn in (("list_balanced_gemv", w.gemv_only), ("list_balanced_gemv_group_passes", w.gemv_group_passes),
+                              ("gather_plus_list_balanced_gemv", w.step),
                               ("static_ranges_compacted", w.fused),
                               ("static_ranges_no_compaction", w.fused_no_compaction), ("dense", w.dense_only))}
         rows.append({"M": M, "K": K, "sparsity": s, "activations": dist,
@@ -872,7 +885,7 @@ def pmc_pass_large(torch, spqt, which):
         cal.copy(b, a, 64 << 20)
     if which == "gate70b":
         wl = Workload(torch, spqt, M, K, "laplace", CONFIG_SCALE_RANGE[5], 5, "gate", s)
-        for fn in (wl.gemv_only, wl.dense_only, wl.fused):
+        for fn in (wl.gemv_only, wl.gemv_group_passes, wl.dense_only, wl.fused):
             for i in range(wl.copies):
                 fn(i)
         kept, dense, copies = wl.mean_kept_bytes, wl.dense_bytes, wl.copies
@@ -1030,7 +1043,7 @@ def main():
         "us_fused_step": round(us_fused, 3),
         "fused_effective_GBps_kept_bytes": round(wl.mean_kept_bytes / (us_fused * 1e-6) / 1e9, 1),
         "oracle_max_abs_err": max_err,
-        "roofline": {"bound": "hbm", "kernel": "spqt_gemv_kernel<sparse>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "spqt_gemv_list_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "bytes_per_launch": wl.mean_kept_bytes, "us_per_launch": round(us_gemv, 3),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((M, K, 0.5))},

@@ -136,7 +136,7 @@ int spqt_gather_rows(const void *x_dev, int64_t K, int batch, float threshold, i
 /* Optional launch shape for spqt_gemv_ex (the two hyper-parameters of Section 4.2.2: how
  * many workgroups share a block-row, and how many wavefronts each holds).  0 = choose. */
 typedef struct {
-    int splits; /* workgroups per block-row, 1..SPQT_MAX_SPLITS */
+    int splits; /* workgroups per block-row, 1..SPQT_MAX_SPLITS (any integer) */
     int waves;  /* wavefronts per workgroup: 1, 2 or 4 */
     int flags;  /* 0, or SPQT_CFG_* bits */
 } spqt_launch_cfg;
@@ -150,6 +150,14 @@ typedef struct {
 /* y_dev is IEEE fp16 [batch][M] instead of fp32: the fp32 result rounded to nearest even at the
  * final store (2-byte aligned).  Accumulation and the exchange of partial sums stay fp32. */
 #define SPQT_CFG_Y_FP16 4
+
+/* spqt_gemv_ex with an index list and one activation row only - an ablation of how the list is
+ * consumed.  By default a pass of 64 column slots is 8 rows of 8 slots and only a ROW must hold
+ * columns of one quantization group, so a group boundary wastes the rest of a row.  With this flag
+ * the kernel that serves several activation rows is used: a whole pass holds columns of ONE group
+ * (its 8 column-lanes are folded before the scale is applied), so a group boundary wastes the rest
+ * of a pass - at 50 % sparsity nearly half of the slots.  Same results up to rounding order. */
+#define SPQT_CFG_GROUP_PASSES 8
 
 /* DEVICE, async.  y[b][m] = sum over the listed columns k of scale[m][k/group] * q[m][k] *
  * x[b][k], fp32 accumulation (Section 4.2.2 for the dense kernel, Section 4.2.3 for the
@@ -192,7 +200,8 @@ int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, con
                     float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                     void *stream, const spqt_launch_cfg *cfg);
 
-/* The launch shape spqt_gemv would pick for this shape (host only, no device access). */
+/* The launch shape spqt_gemv would pick for this shape (host only, no device access): sparse != 0
+ * for a call with an index list, 0 for the dense kernel. */
 int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spqt_launch_cfg *out);
 
 #ifdef __cplusplus

@@ -22,6 +22,7 @@ CHUNK_BYTES = 16896
 MAX_SPLITS = 64
 CFG_NO_COMPACTION = 1
 CFG_Y_FP16 = 4
+CFG_GROUP_PASSES = 8
 
 EXPORTS = [
     "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",
@@ -219,7 +220,7 @@ def spqt_gather_rows(x, threshold: float, idx_out, count_out, x_masked_out, stre
 
 
 def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, group: int = GROUP,
-              splits: int = 0, waves: int = 0) -> None:
+              splits: int = 0, waves: int = 0, flags: int = 0) -> None:
     """packed uint8 (device); x fp16[K] or [batch,K]; idx/count from spqt_gather or None/None
     for the dense kernel; y fp32 (or fp16) [M] or [batch,M]; workspace from new_workspace()."""
     import torch
@@ -236,8 +237,8 @@ def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, 
     wp, wbytes = None, 0
     if workspace is not None:
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
-    if splits or waves or yflags:
-        cfg = _cfg(splits, waves, yflags)
+    if splits or waves or yflags or flags:
+        cfg = _cfg(splits, waves, int(flags) | yflags)
         rc = lib().spqt_gemv_ex(pp, M, K, group, xp, batch, ip, cp, yp, wp, wbytes,
                                 _stream_ptr(stream), ctypes.byref(cfg))
     else:

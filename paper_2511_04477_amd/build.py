@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libspqt.so")
-SOURCES = ["pack.cpp", "quant_cb.cpp", "gather.hip", "gemv.hip", "gemv_cb.hip", "gemv_cb8.hip"]
+SOURCES = ["pack.cpp", "quant_cb.cpp", "gather.hip", "gemv.hip", "gemv_cb.hip", "gemv_cb8.hip", "gemv_list.hip"]
 CALIB_LIB = os.path.join(PKG, "libspqt_calib.so")       # benchmark-only helper kernels
 CALIB_SOURCES = ["calib.hip", "baseline_rowmajor.hip"]
 

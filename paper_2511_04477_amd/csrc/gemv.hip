@@ -72,22 +72,6 @@ constexpr bool kMatrixCoreSingleRow = SPQT_SINGLE_ROW_ON_MATRIX_CORES != 0;
 // FUSED == 2 is an ablation: same test, same static ranges, but NO compaction - a dropped column
 // keeps its slot in the pass with x = 0 (and re-reads a kept column's line), so skipping saves
 // memory traffic but not one multiply step.
-// Matrix-core B operands for 4 consecutive rows of W at 4 columns.  w0..w3 are the same dword of 4
-// steps (4 columns, 8 rows each); HALF picks rows 0..3 or 4..7 of the dword.  One v_perm_b32 puts the
-// same 16 bits of two columns side by side; masked in place, b[p] holds row p's code at the 4
-// columns as fp16 subnormals: code * 2^-24 for p = 0, 2 and 16 * code * 2^-24 for p = 1, 3.
-template <int HALF>
-__device__ __forceinline__ void code_rows(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, u32x2 (&b)[4]) {
-    constexpr uint32_t sel = HALF ? 0x07060302u : 0x05040100u;
-    const uint32_t t01 = __builtin_amdgcn_perm(w1, w0, sel);
-    const uint32_t t23 = __builtin_amdgcn_perm(w3, w2, sel);
-    const uint32_t s01 = t01 >> 8, s23 = t23 >> 8;
-    b[0] = u32x2{t01 & 0x000F000Fu, t23 & 0x000F000Fu};
-    b[1] = u32x2{t01 & 0x00F000F0u, t23 & 0x00F000F0u};
-    b[2] = u32x2{s01 & 0x000F000Fu, s23 & 0x000F000Fu};
-    b[3] = u32x2{s01 & 0x00F000F0u, s23 & 0x00F000F0u};
-}
-
 template <int WAVES, bool DENSE, int BATCH, int FUSED>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
@@ -595,25 +579,7 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
     if (!out) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
     if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
-    const int64_t T = tiles(M), NG = K / kGroup;
-    int waves = 4;
-    // Measured on MI355X over the benchmark shapes (sweep of S at 50 % sparsity and dense):
-    // the fastest launch has about 512 (sparse) / 1024 (dense) workgroups of 4 wavefronts in
-    // total, S a power of two and at most 16 - beyond that the fixed cost per wavefront
-    // (prologue loads, pipeline fill, exchange of partial sums) outweighs the extra
-    // parallelism.  Keep at least a quarter of a quantization group per wavefront.
-    // Four activation rows need enough accumulator registers that two wavefronts fit per SIMD
-    // instead of three: 512 workgroups of 4 wavefronts is then the whole chip, once.
-    // The dense batch-1 kernel on matrices large enough to be bandwidth-bound (>= 64 MB packed) is
-    // fastest with one wavefront per SIMD: about 256 workgroups.
-    const bool big = (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20);
-    const int64_t target = batch == 4 ? 512 : (sparse ? 512 : (big ? 256 : 1024));
-    int64_t S = 1;
-    while (S * 2 <= 16 && S * 2 * T <= target) S *= 2;
-    while (S > 1 && S * waves > 4 * NG) S /= 2;
-    out->splits = (int)S;
-    out->waves = waves;
-    out->flags = 0;
+    choose_cfg(M, K, batch, !sparse ? Kernel::dense : (batch == 1 ? Kernel::list_rows : Kernel::list_groups), out);
     return SPQT_OK;
 }
 
@@ -629,8 +595,11 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
         return SPQT_EALIGN;
 
+    const bool dense = idx_dev == nullptr;
+    // one activation row and an index list: row-aligned passes unless the caller asks for the other kernel
+    const bool row_passes = !dense && batch == 1 && !(cfg && (cfg->flags & SPQT_CFG_GROUP_PASSES));
     spqt_launch_cfg c;
-    if (int rc = spqt_default_cfg(M, K, batch, idx_dev != nullptr, &c)) return rc;
+    choose_cfg(M, K, batch, dense ? Kernel::dense : (row_passes ? Kernel::list_rows : Kernel::list_groups), &c);
     if (cfg) {
         if (cfg->splits) c.splits = cfg->splits;
         if (cfg->waves) c.waves = cfg->waves;
@@ -652,11 +621,15 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
 
     const int T = (int)tiles(M), NG = (int)(K / group);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
-    const bool dense = idx_dev == nullptr;
     hipStream_t st = (hipStream_t)stream;
     hipError_t err;
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
+    if (row_passes) {
+        err = launch_gemv_list(c.waves, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG,
+                               c.splits, T, (int)M | (y_half ? kHalfOutputBit : 0));
+        return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
+    }
     switch (c.waves) {
         case 1: err = launch_batch<1>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
         case 2: err = launch_batch<2>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
@@ -676,7 +649,7 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
         return SPQT_EALIGN;
     spqt_launch_cfg c;
-    if (int rc = spqt_default_cfg(M, K, 1, 1, &c)) return rc;
+    choose_cfg(M, K, 1, Kernel::fused, &c);
     if (cfg) {
         if (cfg->splits) c.splits = cfg->splits;
         if (cfg->waves) c.waves = cfg->waves;

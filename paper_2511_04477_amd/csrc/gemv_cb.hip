@@ -353,7 +353,7 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
         return SPQT_EALIGN;
     spqt_launch_cfg c;
-    if (int rc = spqt_default_cfg(M, K, batch, mode != 1 && mode != 4, &c)) return rc;
+    choose_cfg(M, K, batch, (mode != 1 && mode != 4) ? Kernel::list_groups : Kernel::dense, &c);
     {
         // Measured on MI355X (sweep of S per shape, 50 % and dense): this kernel has no per-group
         // work, so on matrices large enough to be bandwidth-bound (>= 64 MB packed) fewer, longer

@@ -150,6 +150,27 @@ __device__ __forceinline__ float sum_over_columns(float v) {
     return v;
 }
 
+// Matrix-core B operands for 4 consecutive rows of W at 4 columns.  w0..w3 are the same dword of 4
+// steps (4 columns, 8 rows each); HALF picks rows 0..3 or 4..7 of the dword.  One v_perm_b32 puts the
+// same 16 bits of two columns side by side; masked in place, b[p] holds row p's code at the 4
+// columns as fp16 subnormals: code * 2^-24 for p = 0, 2 and 16 * code * 2^-24 for p = 1, 3.
+template <int HALF>
+__device__ __forceinline__ void code_rows(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, u32x2 (&b)[4]) {
+    constexpr uint32_t sel = HALF ? 0x07060302u : 0x05040100u;
+    const uint32_t t01 = __builtin_amdgcn_perm(w1, w0, sel);
+    const uint32_t t23 = __builtin_amdgcn_perm(w3, w2, sel);
+    const uint32_t s01 = t01 >> 8, s23 = t23 >> 8;
+    b[0] = u32x2{t01 & 0x000F000Fu, t23 & 0x000F000Fu};
+    b[1] = u32x2{t01 & 0x00F000F0u, t23 & 0x00F000F0u};
+    b[2] = u32x2{s01 & 0x000F000Fu, s23 & 0x000F000Fu};
+    b[3] = u32x2{s01 & 0x00F000F0u, s23 & 0x00F000F0u};
+}
+
+// The index-list kernel for one activation row with row-aligned passes (gemv_list.hip).
+hipError_t launch_gemv_list(int waves, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
+                            const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                            int K, int NG, int S, int T, int m_and_flags);
+
 // Combine the S workgroups of block-row t (paper Section 4.2.2: the partial sums of the
 // threadgroups that share a superblock row are reduced once at the end, without atomics on y).
 // `red` holds this workgroup's [WAVES][BATCH][ROWS] partial sums in LDS (already synchronised);

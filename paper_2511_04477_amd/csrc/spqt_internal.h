@@ -35,5 +35,37 @@ inline int check_shape(int64_t M, int64_t K, int group) {
     return SPQT_OK;
 }
 
+enum class Kernel { dense, list_rows, list_groups, fused };
+
+// Launch shape per kernel, measured on MI355X over the benchmark shapes at 50 % sparsity and dense.
+inline void choose_cfg(int64_t M, int64_t K, int batch, Kernel kind, spqt_launch_cfg *out) {
+    const int64_t T = tiles(M), NG = K / kGroup;
+    const int waves = 4;
+    int64_t S = 1;
+    if (kind == Kernel::list_rows) {
+        // Row-aligned passes (one activation row): fastest with about one workgroup of 4 wavefronts per
+        // CU - at most 256 in total - and S any integer up to 16.  More workgroups only shorten every
+        // wavefront's slice, and the fixed cost per wavefront (dependent prologue loads, pipeline fill,
+        // fold, exchange of partial sums) outweighs the extra parallelism.
+        S = 256 / T;
+        S = S < 1 ? 1 : (S > 16 ? 16 : S);
+        while (S > 1 && S * waves > 4 * NG) --S;
+    } else {
+        // The others: about 512 (sparse) / 1024 (dense) workgroups in total, S a power of two and at
+        // most 16.  Four activation rows need enough accumulator registers that two wavefronts fit per
+        // SIMD instead of three: 512 workgroups of 4 wavefronts is then the whole chip, once.
+        // The dense batch-1 kernel on matrices large enough to be bandwidth-bound (>= 64 MB packed) is
+        // fastest with one wavefront per SIMD: about 256 workgroups.
+        const bool big = (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20);
+        const int64_t target = batch == 4 ? 512 : (kind != Kernel::dense ? 512 : (big ? 256 : 1024));
+        while (S * 2 <= 16 && S * 2 * T <= target) S *= 2;
+        // keep at least a quarter of a quantization group per wavefront
+        while (S > 1 && S * waves > 4 * NG) S /= 2;
+    }
+    out->splits = (int)S;
+    out->waves = waves;
+    out->flags = 0;
+}
+
 }  // namespace spqt
 #endif

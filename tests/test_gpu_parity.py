@@ -37,7 +37,7 @@ def gpu_gather(gpu, x_np, thr, poison=-7):
     return idx.cpu().numpy(), cnt.cpu().numpy()
 
 
-def gpu_gemv(gpu, w, x_np, thr, dense=False, splits=0, waves=0, packed=None):
+def gpu_gemv(gpu, w, x_np, thr, dense=False, splits=0, waves=0, packed=None, flags=0):
     torch, spqt, dev = gpu
     M, K = w["q_rowmajor"].shape[0], w["q_rowmajor"].shape[1] * 2
     if packed is None:
@@ -53,7 +53,7 @@ def gpu_gemv(gpu, w, x_np, thr, dense=False, splits=0, waves=0, packed=None):
         idx = torch.empty(K, dtype=torch.int32, device=dev)
         cnt = torch.zeros(1, dtype=torch.int32, device=dev)
         spqt.spqt_gather(xx, thr, idx, cnt)
-        spqt.spqt_gemv(packed, M, K, xx, idx, cnt, y if batch > 1 else y[0], ws, splits=splits, waves=waves)
+        spqt.spqt_gemv(packed, M, K, xx, idx, cnt, y if batch > 1 else y[0], ws, splits=splits, waves=waves, flags=flags)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
@@ -152,12 +152,17 @@ def test_launch_shapes_and_ragged_sizes(gpu, M, K, splits, waves):
 
 
 def test_threshold_zero_equals_dense_kernel_bitwise(gpu):
-    """thr = 0 lists every column, so the sparse kernel must do exactly what the index-free
-    dense kernel does (same partition, same order) - identical bits."""
+    """thr = 0 lists every column, so the list kernel with one-group passes must do exactly what the
+    index-free dense kernel does in the same launch shape (same partition, same order) - identical
+    bits.  The default list kernel (row-aligned passes) sums in another order: equal within tolerance."""
+    import paper_2511_04477_amd as spqt
     case = make_case(1, "w")
-    a = gpu_gemv(gpu, case, case["x"], 0.0)
-    b = gpu_gemv(gpu, case, case["x"], 0.0, dense=True)
-    assert np.array_equal(a, b)
+    for splits, waves in ((1, 4), (2, 4), (4, 2)):
+        a = gpu_gemv(gpu, case, case["x"], 0.0, splits=splits, waves=waves, flags=spqt.CFG_GROUP_PASSES)
+        b = gpu_gemv(gpu, case, case["x"], 0.0, dense=True, splits=splits, waves=waves)
+        assert np.array_equal(a, b), (splits, waves)
+        c = gpu_gemv(gpu, case, case["x"], 0.0, splits=splits, waves=waves)
+        assert_close(c, b.astype(np.float64), "row-aligned passes at threshold 0")
 
 
 def test_exact_arithmetic_case_is_bit_exact(gpu):
@@ -251,9 +256,12 @@ def test_batch4_union(gpu):
         assert_close(gpu_gemv(gpu, w, x, thr), ref, f"batch4 s={s}")
     x1 = np.ascontiguousarray(np.repeat(x[:1], 4, axis=0))
     thr = quantile_threshold(x1, 0.5)
-    y4 = gpu_gemv(gpu, w, x1, thr)
-    y1 = gpu_gemv(gpu, w, x1[:1], thr)
-    assert all(np.array_equal(y4[b], y1[0]) for b in range(4))
+    # four equal rows: the batch kernel must give each of them what the same kernel gives one row
+    import paper_2511_04477_amd as spqt
+    y4 = gpu_gemv(gpu, w, x1, thr, splits=2, waves=4)
+    y1 = gpu_gemv(gpu, w, x1[:1], thr, splits=2, waves=4, flags=spqt.CFG_GROUP_PASSES)
+    assert all(np.array_equal(y4[b], y4[0]) for b in range(4))
+    assert_close(y4[:1], y1.astype(np.float64), "batch 4 row vs the one-row kernel")
 
 
 @pytest.mark.parametrize("batch", [2, 3, 4])
