@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
 # HBM bytes per sparse-GEMV launch on the headline workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE scaled by a plain copy kernel of known size (profiles/spqt_gemv_sparse_4096x4096_s50.md).
-MEASURED_TRAFFIC_BYTES = {(4096, 4096, 0.5): 5854681}
+MEASURED_TRAFFIC_BYTES = {(4096, 4096, 0.5): 5759274}
 INFINITY_CACHE_BYTES = 256 << 20
 ROTATE_BYTES = 3 * INFINITY_CACHE_BYTES   # rotate over at least this many bytes of weights
 

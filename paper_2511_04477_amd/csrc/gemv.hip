@@ -8,6 +8,11 @@
 // segment is not a static column range but an even slice of the compacted index list
 // idx[0:n_ns], so every simdgroup gets about n_ns / (n1*n2) kept columns.
 //
+// This file holds the dense kernel, the kernel for several activation rows and the one-launch mode.
+// With an index list and ONE activation row the library launches gemv_list.hip instead, which forms its
+// passes differently (only a row of 8 slots must be of one group); this file's list mode for one row
+// stays reachable with SPQT_CFG_GROUP_PASSES.
+//
 // Mapping onto gfx950 (wave64):
 //   - grid = T*S workgroups of WAVES wavefronts; workgroup (t, s) works on block-row t, and
 //     wavefront j = s*WAVES + w of the S*WAVES that share the block-row takes
