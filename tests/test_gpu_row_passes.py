@@ -98,3 +98,39 @@ def test_list_passes_clustered_and_unordered_lists(gpu):
             for flags in (0, spqt.CFG_GROUP_PASSES):
                 say(f"list '{name}' splits={splits} waves={waves} flags={flags}")
                 assert_close(run(gpu, packed, M, K, 128, x, 0.0, splits, waves, idx_np=lst, flags=flags), ref, name)
+
+
+def test_one_workspace_across_kernels_and_launch_shapes(gpu):
+    """Calls of every group-layout kernel, in launch shapes that lay the exchanged words out differently
+    (any number of workgroups per block-row), alternate on ONE workspace with the same M: the tags
+    must keep words left by earlier calls from being taken for this call's."""
+    torch, spqt, dev = gpu
+    M, K = 2816, 2048          # 11 block-rows
+    w = make_weights(M, K, 9800)
+    q, sc = w["q_rowmajor"], w["scales"]
+    packed = torch.from_numpy(spqt.spqt_pack(q, sc)).to(dev)
+    ws = spqt.new_workspace(M, K, 1)
+    idx = torch.empty(K, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    y = torch.empty(M, dtype=torch.float32, device=dev)
+    rng = np.random.default_rng(9801)
+    shapes = [(0, 0), (16, 4), (5, 4), (3, 2), (64, 1), (7, 4), (2, 1), (13, 2)]
+    for it in range(24):
+        x_np = make_x(K, "laplace", 9802 + it)
+        thr = quantile_threshold(x_np, float(rng.uniform(0.1, 0.95)))
+        x = torch.from_numpy(x_np[0]).to(dev)
+        splits, waves = shapes[int(rng.integers(len(shapes)))]
+        kind = ("rows", "groups", "dense", "fused")[it % 4]
+        say(f"shared workspace it={it} kind={kind} splits={splits} waves={waves}")
+        y.fill_(float("nan"))
+        if kind == "fused":
+            spqt.spqt_gemv_fused(packed, M, K, x, thr, y, ws, splits=splits, waves=waves)
+        elif kind == "dense":
+            spqt.spqt_gemv(packed, M, K, x, None, None, y, ws, splits=splits, waves=waves)
+        else:
+            spqt.spqt_gather(x, thr, idx, cnt)
+            spqt.spqt_gemv(packed, M, K, x, idx, cnt, y, ws, splits=splits, waves=waves,
+                           flags=spqt.CFG_GROUP_PASSES if kind == "groups" else 0)
+        torch.cuda.synchronize()
+        ref = oracle.gemv(q, sc, x_np, 0.0 if kind == "dense" else thr)[0]
+        assert_close(y.cpu().numpy(), ref, f"it={it} {kind} {splits}x{waves}")
