@@ -109,6 +109,14 @@ class Workload:
     def fused(self, i):
         self.spqt.spqt_gemv_fused(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws)
 
+    def fused_rows(self, i):
+        """Several rows in one launch, union of the kept sets."""
+        self.spqt.spqt_gemv_fused_rows(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws)
+
+    def fused_rows_own_sets(self, i):
+        """Several rows in one launch, each summing over its own kept set."""
+        self.spqt.spqt_gemv_fused_rows(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws, own_sets=True)
+
     def fused_no_compaction(self, i):
         self.spqt.spqt_gemv_fused(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws,
                                   flags=self.spqt.CFG_NO_COMPACTION)
@@ -1070,7 +1078,8 @@ def main():
                        (5, "gate", 28672, 8192, "laplace", [0.3, 0.7], 1),
                        (5, "down", 8192, 28672, "laplace", [0.3, 0.5, 0.7], 1),
                        (5, "gate", 28672, 8192, "laplace", [0.3, 0.5, 0.7], 4),
-                       (5, "down", 8192, 28672, "laplace", [0.5], 4)]
+                       (5, "down", 8192, 28672, "laplace", [0.5], 4),
+                       (2, "q", 4096, 4096, "laplace", [0.5], 4)]
         for config, tensor, m, k, dist, sps, batch in shapes:
             for s in sps:
                 w = wl if (m, k, s, batch) == (M, K, 0.5, 1) else Workload(torch, spqt, m, k, dist, CONFIG_SCALE_RANGE[config], config, tensor, s, batch=batch)
@@ -1078,13 +1087,15 @@ def main():
                 t_g = time_sequence(torch, w.gemv_only, w.copies, steps, w.copies, use_graph)
                 t_d = time_sequence(torch, w.dense_only, w.copies, steps, w.copies, use_graph)
                 t_s = time_sequence(torch, w.step, w.copies, steps, w.copies, use_graph)
-                t_f = time_sequence(torch, w.fused, w.copies, steps, w.copies, use_graph) if batch == 1 else None
+                t_f = time_sequence(torch, w.fused if batch == 1 else w.fused_rows, w.copies, steps, w.copies, use_graph)
                 t_r = time_sequence(torch, w.step_own_sets, w.copies, steps, w.copies, use_graph) if batch > 1 else None
+                t_fo = time_sequence(torch, w.fused_rows_own_sets, w.copies, steps, w.copies, use_graph) if batch > 1 else None
                 gb = w.mean_kept_bytes / (t_g * 1e-6) / 1e9
                 sweep.append({"config": config, "tensor": tensor, "M": m, "K": k, "batch": batch, "sparsity_per_row": s,
                               "kept_frac": round(float(np.mean(w.n_ns)) / k, 4),
                               "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3), "us_fused": None if t_f is None else round(t_f, 3),
                               "us_gather_rows_plus_gemv": None if t_r is None else round(t_r, 3),
+                              "us_fused_own_sets": None if t_fo is None else round(t_fo, 3),
                               "GBps_kept": round(gb, 1), "frac_of_8TBps": round(gb / HBM_PEAK_GBPS, 4),
                               "dense_GBps": round(w.dense_bytes / (t_d * 1e-6) / 1e9, 1),
                               "speedup_vs_dense": round(t_d / t_g, 3)})

@@ -200,6 +200,21 @@ int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, con
                     float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                     void *stream, const spqt_launch_cfg *cfg);
 
+/* DEVICE, async.  spqt_gemv_fused for 2..4 activation rows that share one pass over the weights
+ * (Section 3.2 expects small beams to work; batch == 1 forwards to spqt_gemv_fused).  A column is
+ * visited if ANY row keeps it.
+ *   x_dev      fp16[batch][K].
+ *   own_sets   0: every row takes every visited column (the union, as spqt_gather + spqt_gemv do);
+ *              non-zero: row b takes only the columns it keeps itself, |x[b][k]| >= threshold - the
+ *              result spqt_gemv_fused gives for that row alone (as spqt_gather_rows + spqt_gemv do).
+ *   y_dev      fp32 (or fp16 with SPQT_CFG_Y_FP16) [batch][M].
+ *   cfg        NULL, or splits and SPQT_CFG_Y_FP16; this kernel always runs 4 wavefronts per
+ *              workgroup (cfg->waves must be 0 or 4, else SPQT_EINVAL).
+ * Workspace as for spqt_gemv with the same batch. */
+int spqt_gemv_fused_rows(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+                         int batch, float threshold, int own_sets, void *y_dev, void *workspace_dev,
+                         size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg);
+
 /* The launch shape spqt_gemv would pick for this shape (host only, no device access): sparse != 0
  * for a call with an index list, 0 for the dense kernel. */
 int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spqt_launch_cfg *out);

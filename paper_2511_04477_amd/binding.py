@@ -26,7 +26,7 @@ CFG_GROUP_PASSES = 8
 
 EXPORTS = [
     "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",
-    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gather_rows", "spqt_gemv", "spqt_gemv_ex", "spqt_gemv_fused",
+    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gather_rows", "spqt_gemv", "spqt_gemv_ex", "spqt_gemv_fused", "spqt_gemv_fused_rows",
     "spqt_default_cfg",
 ]
 
@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.spqt_gemv_ex.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp,
                                    c.POINTER(LaunchCfg)]
         L.spqt_gemv_fused.argtypes = [vp, i64, i64, i32, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_gemv_fused_rows.argtypes = [vp, i64, i64, i32, vp, i32, c.c_float, i32, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_default_cfg.argtypes = [i64, i64, i32, i32, c.POINTER(LaunchCfg)]
         L.spqt_cb_packed_bytes.argtypes = [i64, i64, c.POINTER(sz)]
         L.spqt_cb_quantize.argtypes = [vp, i64, i64, vp, sz]
@@ -261,6 +262,25 @@ def spqt_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, s
     cfg = _cfg(splits, waves, int(flags) | yflags)
     _check(lib().spqt_gemv_fused(pp, M, K, group, xp, float(threshold), yp, wp, wbytes,
                                  _stream_ptr(stream), ctypes.byref(cfg)))
+
+
+def spqt_gemv_fused_rows(packed, M: int, K: int, x, threshold: float, y, workspace, own_sets: bool = False, stream=None,
+                         group: int = GROUP, splits: int = 0) -> None:
+    """Threshold + compaction + GEMV in one launch for x fp16[batch, K], batch 1..4; y fp32 (or fp16) [batch, M].
+    own_sets: every row sums over its own kept columns instead of the union."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp, yflags = _y_out(y)
+    batch = 1 if x.dim() == 1 else x.shape[0]
+    if x.shape[-1] != K or y.numel() != batch * M or packed.numel() < spqt_packed_bytes(M, K, group):
+        raise SpqtError("spqt_gemv_fused_rows: x / y / packed sizes do not match M, K, batch")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    cfg = _cfg(splits, 0, yflags)
+    _check(lib().spqt_gemv_fused_rows(pp, M, K, group, xp, batch, float(threshold), int(bool(own_sets)), yp, wp, wbytes,
+                                      _stream_ptr(stream), ctypes.byref(cfg)))
 
 
 # ------------------------------------------------------------- column-block variant (spqt_colblock.h)

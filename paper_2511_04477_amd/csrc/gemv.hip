@@ -212,9 +212,13 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
                                  const uint8_t *chunk_next, const uint32_t *off_next) {
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
-                const uint32_t hb = lane < n ? xraw[b] : 0u;
-                xsum[b] += half_bits_to_float(hb) * kTwo24;
-                stage_xh[wave][slot][lane & 7][b][lane >> 3] = (uint16_t)hb;
+                if (FUSED) {    // the fused fetch head has already staged x; xraw carries this lane's share of the bias sum
+                    xsum[b] += as_float(xraw[b]);
+                } else {
+                    const uint32_t hb = lane < n ? xraw[b] : 0u;
+                    xsum[b] += half_bits_to_float(hb) * kTwo24;
+                    stage_xh[wave][slot][lane & 7][b][lane >> 3] = (uint16_t)hb;
+                }
             }
             __builtin_amdgcn_wave_barrier();
             const u32x4 xa = *reinterpret_cast<const u32x4 *>(&stage_xh[wave][slot][cg][lane & 3][0]);
@@ -385,7 +389,93 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         u32x2 scA, scB;
         uint32_t xrA[BATCH], xrB[BATCH];
         int nA, nB, gA, gB, kA, kB;
-        if (FUSED) {
+        if (FUSED && BATCH > 1) {
+            // One launch for several activation rows: a column of the unit is kept if ANY row keeps it;
+            // with the own-sets flag every row then contributes only where it keeps the column itself
+            // (its x is staged as 0 elsewhere), which is that row's batch-1 result.
+            const bool own = (M & kOwnSetsBit) != 0;
+            const int upg = log2g - 6;                      // log2 of the 64-column units per group
+            // FETCH head of unit u (xr[b] = this lane's x[b][64u + lane], requested one stage earlier):
+            // everything of the fetch stage but the weight loads.
+            auto fetch_head_unit = [&](const uint32_t(&xr)[BATCH], int u, int slot, const uint8_t *&chunk_out,
+                                       uint32_t(&off)[8], int &n_out, int &g_out, uint32_t(&xs_out)[BATCH],
+                                       u32x2 &sc_out, uint32_t(&xr_next)[BATCH]) {
+                const bool any = u < end;
+                const int g = any ? (u >> upg) : 0;
+                bool kb[BATCH];
+                bool keep = false;
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) {
+                    kb[b] = any && !(__builtin_fabsf(half_bits_to_float(xr[b])) < thr);
+                    keep = keep || kb[b];
+                }
+                const uint64_t mask = __ballot(keep);
+                const int n = __builtin_amdgcn_readfirstlane((int)__popcll(mask));
+                const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                {   // next unit's x (index clamped: the value is unused past the slice)
+                    const int c = (u + 1) * kPassCols + lane;
+#pragma unroll
+                    for (int b = 0; b < BATCH; ++b) xr_next[b] = x[(size_t)b * K + (c < K ? c : K - 1)];
+                }
+                const int first_lane = n ? (int)__builtin_ctzll(mask) : 0;
+                const int uin = u & ((1 << upg) - 1);             // unit inside its group
+                const uint32_t koff_first = (uint32_t)((uin * kPassCols + first_lane) * kColBytes);
+                const uint32_t koff_own = (uint32_t)((uin * kPassCols + lane) * kColBytes);
+                const int entry = keep ? rank : n + lane - rank;
+                stage_off[wave][slot][entry] = keep ? koff_own : koff_first;
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) {
+                    const bool use = keep && (!own || kb[b]);
+                    xs_out[b] = as_u32(use ? half_bits_to_float(xr[b]) * kTwo24 : 0.0f);
+                    stage_xh[wave][slot][entry & 7][b][entry >> 3] = use ? (uint16_t)xr[b] : (uint16_t)0;
+                }
+                const uint8_t *chunk = row_base + (size_t)g * chunk_b;   // wave-uniform base
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int v = 0; v < 8; ++v) off[v] = stage_off[wave][slot][v * 8 + cg] + seg16;
+                sc_out = *reinterpret_cast<const u32x2 *>(chunk + (size_t)sc_off);
+                chunk_out = chunk;
+                n_out = n;
+                g_out = g;
+            };
+            uint32_t xc[BATCH], xn[BATCH];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) xc[b] = x[(size_t)b * K + pos * kPassCols + lane];
+            {
+                const uint8_t *chunk0;
+                uint32_t off0[8];
+                fetch_head_unit(xc, pos, 0, chunk0, off0, nA, gA, xrA, scA, xn);
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    wA[v] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(chunk0 + kScaleBytes + (size_t)off0[v]));
+            }
+            int slot = 0, u = pos;
+            for (;;) {
+                const int uN = u + 1;
+                const uint8_t *chunkN;
+                uint32_t offN[8], xsN[BATCH], xnn[BATCH];
+                u32x2 scN;
+                int nN, gN;
+                fetch_head_unit(xn, uN, slot ^ 1, chunkN, offN, nN, gN, xsN, scN, xnn);
+                multiply(nA, xrA, slot, wA, chunkN, offN);
+                if (uN >= end) {
+                    flush(scA);
+                    break;
+                }
+                if (gN != gA) flush(scA);
+                u = uN;
+                nA = nN;
+                gA = gN;
+                scA = scN;
+                slot ^= 1;
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) {
+                    xrA[b] = xsN[b];
+                    xn[b] = xnn[b];
+                }
+            }
+        } else if (FUSED) {
             // FETCH stage of unit u (xr = this lane's x[64u + lane], requested one stage earlier):
             // threshold, rank, stage, request the next unit's x, the weights and the scales.
             auto fetch_unit = [&](uint32_t xr, int u, int slot, u32x4(&w)[8], int &n_out, int &g_out,
@@ -547,6 +637,18 @@ hipError_t launch_fused(bool compact, int grid, hipStream_t stream, const uint8_
     return hipGetLastError();
 }
 
+// One launch for 2..4 activation rows (4 wavefronts per workgroup).
+hipError_t launch_fused_rows(int batch, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x, float thr,
+                             float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int m_and_flags) {
+    const int32_t *none = nullptr;
+    switch (batch) {
+        case 2: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 2, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, epochs, K, NG, S, T, m_and_flags, thr); break;
+        case 3: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 3, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, epochs, K, NG, S, T, m_and_flags, thr); break;
+        default: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 4, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, epochs, K, NG, S, T, m_and_flags, thr); break;
+    }
+    return hipGetLastError();
+}
+
 template <int WAVES>
 hipError_t launch_batch(int batch, bool dense, int grid, hipStream_t stream, const uint8_t *packed,
                         const uint16_t *x, const int32_t *idx, const int32_t *count, float *y,
@@ -684,6 +786,44 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
         case 2: err = launch_fused<2>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
         default: err = launch_fused<4>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
     }
+    return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
+}
+
+extern "C" int spqt_gemv_fused_rows(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev, int batch,
+                                    float threshold, int own_sets, void *y_dev, void *workspace_dev,
+                                    size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg) {
+    if (batch == 1) return spqt_gemv_fused(packed_dev, M, K, group, x_dev, threshold, y_dev, workspace_dev, workspace_bytes, stream, cfg);
+    if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
+    if (threshold != threshold) return SPQT_EINVAL;
+    if (int rc = check_shape(M, K, group)) return rc;
+    if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
+    if (cfg && (cfg->flags & ~SPQT_CFG_Y_FP16)) return SPQT_EINVAL;
+    const int y_half = cfg && (cfg->flags & SPQT_CFG_Y_FP16) ? 1 : 0;
+    if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
+        return SPQT_EALIGN;
+    spqt_launch_cfg c;
+    choose_cfg(M, K, batch, Kernel::fused, &c);
+    if (cfg) {
+        if (cfg->splits) c.splits = cfg->splits;
+        if (cfg->waves && cfg->waves != 4) return SPQT_EINVAL;   // this kernel is built for 4 wavefronts per workgroup
+    }
+    if (c.splits < 1 || c.splits > SPQT_MAX_SPLITS) return SPQT_EINVAL;
+    size_t need = 0;
+    spqt_workspace_bytes(M, K, batch, &need);
+    void *partials = nullptr;
+    int32_t *epochs = nullptr;
+    if (c.splits > 1) {
+        if (!workspace_dev) return SPQT_EINVAL;
+        if (workspace_bytes < need) return SPQT_ESIZE;
+        if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
+        epochs = (int32_t *)workspace_dev;
+        partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
+    }
+    const int T = (int)tiles(M), NG = (int)(K / group);
+    const int grid = 8 * ((T + 7) / 8) * c.splits;
+    const int mf = (int)M | (y_half ? kHalfOutputBit : 0) | (own_sets ? kOwnSetsBit : 0);
+    hipError_t err = launch_fused_rows(batch, grid, (hipStream_t)stream, (const uint8_t *)packed_dev, (const uint16_t *)x_dev,
+                                       threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, mf);
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }
 

@@ -20,6 +20,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kPassCols = 64;                  // most columns one pass covers (8 steps)
 constexpr float kTwo24 = 16777216.0f;          // 2^24: undoes the fp16 subnormal exponent
 constexpr int kHalfOutputBit = 1 << 30;        // in the kernels' M argument: y is fp16, not fp32
+constexpr int kOwnSetsBit = 1 << 29;           // in the kernels' M argument: every activation row keeps its own set
+constexpr int kRowsMask = (1 << 25) - 1;       // the bits of that argument that hold M (M <= 2^24)
 constexpr int kMaxPolls = 1 << 18;             // bound on the reducer's wait for one batch of partials
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
@@ -190,7 +192,7 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
                                                   int m_and_flags) {
     // One kernel argument carries both (M <= 2^24): every extra scalar argument costs the
     // four-row kernels, which sit at the register limit, a spill.
-    const int M = m_and_flags & (kHalfOutputBit - 1);
+    const int M = m_and_flags & kRowsMask;
     const bool y_half = (m_and_flags & kHalfOutputBit) != 0;
     constexpr int kOut = BATCH * ROWS;           // values one workgroup contributes: [BATCH][ROWS]
     unsigned long long *slots = reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kOut;

@@ -52,12 +52,12 @@ inline void choose_cfg(int64_t M, int64_t K, int batch, Kernel kind, spqt_launch
         while (S > 1 && S * waves > 4 * NG) --S;
     } else {
         // The others: about 512 (sparse) / 1024 (dense) workgroups in total, S a power of two and at
-        // most 16.  Four activation rows need enough accumulator registers that two wavefronts fit per
+        // most 16.  Several activation rows need enough accumulator registers that two wavefronts fit per
         // SIMD instead of three: 512 workgroups of 4 wavefronts is then the whole chip, once.
         // The dense batch-1 kernel on matrices large enough to be bandwidth-bound (>= 64 MB packed) is
         // fastest with one wavefront per SIMD: about 256 workgroups.
         const bool big = (size_t)M * (size_t)K / 2 >= ((size_t)64 << 20);
-        const int64_t target = batch == 4 ? 512 : (kind != Kernel::dense ? 512 : (big ? 256 : 1024));
+        const int64_t target = batch >= 2 ? 512 : (kind != Kernel::dense ? 512 : (big ? 256 : 1024));
         while (S * 2 <= 16 && S * 2 * T <= target) S *= 2;
         // keep at least a quarter of a quantization group per wavefront
         while (S > 1 && S * waves > 4 * NG) S /= 2;

@@ -279,6 +279,17 @@ def test_null_and_small_buffers_are_rejected_on_the_host():
     assert L.spqt_gemv(64, 256, 128, 128, 16, 1, None, None, 16, None, 0, None) == -3
     assert L.spqt_gemv(128, 256, 128, 128, 16, 1, 16, None, 16, None, 0, None) == -1  # idx without count
     assert L.spqt_gemv(128, 256, 128, 128, 16, 7, None, None, 16, None, 0, None) == -2
+    # one launch for several rows: same checks, and 4 wavefronts per workgroup only
+    fr = L.spqt_gemv_fused_rows
+    assert fr(None, 256, 128, 128, 16, 2, ctypes.c_float(0.0), 0, 16, None, 0, None, None) == -1
+    assert fr(128, 256, 100, 128, 16, 2, ctypes.c_float(0.0), 0, 16, None, 0, None, None) == -2
+    assert fr(128, 256, 128, 128, 16, 5, ctypes.c_float(0.0), 0, 16, None, 0, None, None) == -2
+    assert fr(128, 256, 128, 128, 16, 2, ctypes.c_float(float("nan")), 0, 16, None, 0, None, None) == -1
+    assert fr(64, 256, 128, 128, 16, 2, ctypes.c_float(0.0), 0, 16, None, 0, None, None) == -3
+    two_waves = spqt.binding.LaunchCfg(1, 2, 0)
+    assert fr(128, 256, 128, 128, 16, 2, ctypes.c_float(0.0), 0, 16, None, 0, None, ctypes.byref(two_waves)) == -1
+    no_ws = spqt.binding.LaunchCfg(4, 0, 0)
+    assert fr(128, 1024, 1024, 128, 16, 2, ctypes.c_float(0.0), 0, 16, None, 0, None, ctypes.byref(no_ws)) == -1
 
 
 @pytest.mark.parametrize("M,K", [(512, 1024), (4096, 4096), (1024, 4096), (11008, 4096), (4096, 11008),
