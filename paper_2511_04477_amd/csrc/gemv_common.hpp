@@ -195,52 +195,77 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
     const int M = m_and_flags & kRowsMask;
     const bool y_half = (m_and_flags & kHalfOutputBit) != 0;
     constexpr int kOut = BATCH * ROWS;           // values one workgroup contributes: [BATCH][ROWS]
+    constexpr int kThreads = WAVES * 64;
+    constexpr int kPerThread = (kOut + kThreads - 1) / kThreads;
+    // A thread that owns several values handles 2 of them together, so that the reducer's loads for
+    // all of them are in flight at once (one round trip instead of one per value).
+    constexpr int kTogether = kPerThread < 2 ? kPerThread : 2;
     unsigned long long *slots = reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kOut;
-    for (int r = tid; r < kOut; r += WAVES * 64) {
-        float sum = 0.0f;
+    for (int r0 = tid; r0 < kOut; r0 += kTogether * kThreads) {
+        int r[kTogether];
+        bool real[kTogether];
+        float sum[kTogether];
 #pragma unroll
-        for (int w2 = 0; w2 < WAVES; ++w2) sum += red[w2 * kOut + r];
-        const int row = t * ROWS + (r % ROWS);
-        const bool real = row < M;                   // rows past M are the last block-row's zero padding
-        const size_t y_at = (size_t)(r / ROWS) * M + row;
+        for (int i = 0; i < kTogether; ++i) {
+            const bool have = r0 + i * kThreads < kOut;
+            r[i] = have ? r0 + i * kThreads : r0;
+            real[i] = have && t * ROWS + (r[i] % ROWS) < M;   // rows past M are the last block-row's zero padding
+            sum[i] = 0.0f;
+#pragma unroll
+            for (int w2 = 0; w2 < WAVES; ++w2) sum[i] += red[w2 * kOut + r[i]];
+        }
         // fp32 output, or the same value rounded to fp16 (nearest even) when the caller asked for it
-        auto store_y = [&](float v) {
+        auto store_y = [&](int i, float v) {
+            const size_t y_at = (size_t)(r[i] / ROWS) * M + t * ROWS + (r[i] % ROWS);
             if (y_half) reinterpret_cast<_Float16 *>(y)[y_at] = (_Float16)v;
             else y[y_at] = v;
         };
         if (S == 1) {
-            if (real) store_y(sum);
+#pragma unroll
+            for (int i = 0; i < kTogether; ++i)
+                if (real[i]) store_y(i, sum[i]);
         } else if (s != S - 1) {
-            const unsigned long long word = ((unsigned long long)tag << 32) | as_u32(sum);
-            __hip_atomic_store(slots + (size_t)s * kOut + r, word, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < kTogether; ++i) {
+                const unsigned long long word = ((unsigned long long)tag << 32) | as_u32(sum[i]);
+                __hip_atomic_store(slots + (size_t)s * kOut + r[i], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         } else {
-            float total = 0.0f;
+            float total[kTogether];
+#pragma unroll
+            for (int i = 0; i < kTogether; ++i) total[i] = 0.0f;
             bool gave_up = false;
             for (int p0 = 0; p0 < S - 1; p0 += 16) {
-                unsigned long long v[16];
+                unsigned long long v[kTogether][16];
                 int polls = 0;
                 bool all_here;
                 do {
-                    // 16 unconditional loads back to back (clamped index), then one check
+                    // unconditional loads back to back (clamped index), then one check
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int p = p0 + j < S - 1 ? p0 + j : S - 2;
-                        v[j] = __hip_atomic_load(slots + (size_t)p * kOut + r, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-                    }
+                    for (int i = 0; i < kTogether; ++i)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const int p = p0 + j < S - 1 ? p0 + j : S - 2;
+                            v[i][j] = __hip_atomic_load(slots + (size_t)p * kOut + r[i], __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+                        }
                     uint32_t missing = 0u;
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[j] >> 32) ^ tag;
+                    for (int i = 0; i < kTogether; ++i)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[i][j] >> 32) ^ tag;
                     all_here = missing == 0u;
                 } while (!all_here && ++polls < kMaxPolls);
                 gave_up = gave_up || !all_here;
 #pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    if (p0 + j < S - 1) total += as_float((uint32_t)v[j]);
+                for (int i = 0; i < kTogether; ++i)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+                        if (p0 + j < S - 1) total[i] += as_float((uint32_t)v[i][j]);
             }
-            total += sum;
-            if (real) store_y(gave_up ? __builtin_nanf("") : total);
+#pragma unroll
+            for (int i = 0; i < kTogether; ++i)
+                if (real[i]) store_y(i, gave_up ? __builtin_nanf("") : total[i] + sum[i]);
         }
     }
     if (S > 1 && s == S - 1 && tid == 0)
