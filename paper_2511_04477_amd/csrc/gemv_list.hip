@@ -219,12 +219,12 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         }
     }
 
-    // back to true units, then the 8 column-lanes are folded: lane (cg, seg) ends with rows 32 seg + 4 rev(cg) + j
-#pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] *= (i & 1) ? kTwo24 * 0.0625f : kTwo24;
+    // the 8 column-lanes are folded: lane (cg, seg) ends with rows 32 seg + 4 rev(cg) + j (the fold only adds
+    // rows whose index is equal mod 4, so odd and even rows stay apart), then back to true units
     float r4[4];
     fold_columns(acc, r4);
-    reinterpret_cast<f32x4 *>(red[wave][0])[8 * seg + cgr] = f32x4{r4[0], r4[1], r4[2], r4[3]};
+    reinterpret_cast<f32x4 *>(red[wave][0])[8 * seg + cgr] =
+        f32x4{r4[0] * kTwo24, r4[1] * (kTwo24 * 0.0625f), r4[2] * kTwo24, r4[3] * (kTwo24 * 0.0625f)};
     __syncthreads();
     combine_block_row<WAVES, 1>(&red[0][0][0], tid, t, s, S, tag, partials, epochs, y, M);
 }
