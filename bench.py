@@ -7,7 +7,7 @@ workload is the Llama-7B attention-projection shape (4096 x 4096, group 128) at 
 activation sparsity.  Weight buffers rotate over independently seeded copies whose total
 size is several times the 256 MB Infinity Cache, so no launch re-reads cached weights.
 
-Prints ONE JSON line (see README for the fields).  `--gpus` above 1 is refused:
+Prints ONE JSON line (the fields are built in main() below).  `--gpus` above 1 is refused:
 this build is a one-GPU kernel path.
 """
 from __future__ import annotations
@@ -974,7 +974,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
-              "(sharding is described in DESIGN.md, not implemented)", file=sys.stderr)
+              "(sharding across GPUs is not implemented)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
