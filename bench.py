@@ -858,6 +858,49 @@ class CpuBaseline:
         from oracle import colblock_k as ck
         return ck.gemv(ck.quantize(W_rows), x_np, thr)[0]
 
+    def quantization_error(self):
+        """Bytes against accuracy of the weight formats on the same synthetic fp32 matrices (2048 x 4096;
+        x ~ Laplace(0,1), dense product): relative RMS error of the dequantized weights and of y = W x
+        against the unquantized fp64 product.  Two matrices: plain N(0, 0.02^2), and the workload
+        module's matrix in which every 64th COLUMN is 8 times larger (an input channel with outlier
+        weights: blocks along a column keep it to itself, groups along a row all contain one).  The
+        group layout carries whatever the model's quantizer produced (it is a repack); here its source
+        is made with the plain symmetric rule s = max|w| / 7 over G consecutive weights of a ROW, the
+        counterpart of the column-block rule.  Host only (NumPy and the oracles); says nothing about
+        trained weights."""
+        import numpy as np
+        from oracle import colblock as cb, colblock_k as ck, colblock_w8 as c8
+        from workloads import make_fp_weights, make_x
+        M, K = 2048, 4096
+        x = make_x(K, "laplace", 424243)[0].astype(np.float64)
+
+        def rel(a, b):
+            return float(np.sqrt(np.mean((a - b) ** 2) / np.mean(b ** 2)))
+
+        def row_groups(Wf, G):      # symmetric int4 along K, fp16 scale per (row, G columns)
+            w = Wf.reshape(M, K // G, G)
+            s = (np.max(np.abs(w), axis=2) / np.float32(7.0)).astype(np.float16).astype(np.float32)
+            with np.errstate(divide="ignore", invalid="ignore"):
+                q = np.where(s[:, :, None] > 0, np.clip(np.rint(w / s[:, :, None]), -8, 7), 0)
+            return (q * s[:, :, None]).reshape(M, K).astype(np.float64)
+
+        rows = []
+        plain = (np.random.default_rng(424244).standard_normal((M, K)) * 0.02).astype(np.float32)
+        for label, Wf in (("gaussian", plain), ("gaussian, every 64th column x8", make_fp_weights(M, K, 424242))):
+            W = Wf.astype(np.float64)
+            y = W @ x
+            q4, s4 = cb.quantize(Wf)
+            q8, s8 = c8.quantize(Wf)
+            forms = [("group layout, 128 along K", 4 + 16 / 128, row_groups(Wf, 128)),
+                     ("group layout, 64 along K", 4 + 16 / 64, row_groups(Wf, 64)),
+                     ("column blocks of 32 rows", 4 + 16 / 32, cb.dequant(q4, s4)),
+                     ("column blocks, 6-bit scales and minima", 4.5, ck.dequant(ck.quantize(Wf))),
+                     ("column blocks of 32 rows, 8-bit", 8 + 16 / 32, c8.dequant(q8, s8))]
+            rows += [{"weights": label, "format": name, "bits_per_weight": round(bits, 3),
+                      "rel_rms_weight_error": round(rel(Wd, W), 5), "rel_rms_gemv_error": round(rel(Wd @ x, y), 5)}
+                     for name, bits, Wd in forms]
+        return rows
+
     @staticmethod
     def close(got, ref):
         import numpy as np
@@ -1109,6 +1152,8 @@ def main():
             # over 32 layers (config 4); spqt_gather time included
             out["colblock_layout"] = colblock_rows(torch, spqt, use_graph, cpu)
             out["ablations"] = ablations(torch, spqt, use_graph, cpu)
+            if cpu.enabled:
+                out["quantization_error"] = cpu.quantization_error()
             out["rowmajor_baseline"] = rowmajor_baseline(torch, spqt, use_graph, cpu)
             out["eight_bit_layout"] = eight_bit_rows(torch, spqt, use_graph, cpu)
             out["merged_gate_up_70b"] = merged_gate_up_70b(torch, spqt, use_graph, cpu)
