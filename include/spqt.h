@@ -76,21 +76,21 @@ const char *spqt_status_str(int status);
 /* Size in bytes of the packed form of an M x K matrix (layout above). */
 int spqt_packed_bytes(int64_t M, int64_t K, int group, size_t *out_bytes);
 
-/* Size in bytes of the device workspace spqt_gemv needs for this shape: one epoch counter
- * per block-row plus, for each of up to SPQT_MAX_SPLITS workgroups that may share a
- * block-row, 256 x batch 64-bit words {partial sum, tag} through which they hand their
- * partial sums to the workgroup that writes y.  The workspace must be prepared ONCE with
- * spqt_workspace_init before its first use; every call leaves it ready for the next one
- * (the tag of a call is its block-row's epoch + 1, so words of earlier calls never match).
- * Two calls that may overlap in time (different streams) need two workspaces; calls on one
- * stream, or replays of one graph, may share one PROVIDED THEY HAVE THE SAME M (any K, batch,
- * launch shape, dense / sparse / fused, group or 4-bit column-block layout): the epochs of all
- * block-rows then advance in step, which is what keeps leftover words from matching.  Before
- * a workspace is reused for a different M, or between the 8-bit column-block entry point (whose
- * block-rows are 128 rows high) and the others, run spqt_workspace_init on it again. */
+/* Size in bytes of the device workspace spqt_gemv needs for this shape: a 256-byte head plus, for
+ * each of up to SPQT_MAX_SPLITS workgroups that may share a block-row, 256 x batch 64-bit words
+ * {partial sum, tag} through which they hand their partial sums to the workgroup that writes y.
+ * The workspace must be prepared ONCE with spqt_workspace_init before its first use.  The workgroup
+ * that consumes a word puts it back to zero, so every call leaves the workspace all zeros: calls on
+ * one stream, or replays of one graph, may share one workspace whatever their M, K, batch, launch
+ * shape, kernel (dense / sparse / one launch) or layout (group, column-block, 8-bit), provided it is
+ * large enough for each.  Two calls that may overlap in time (different streams) need two workspaces.
+ * Word 0 of the head is a poison flag: should a reducer ever abandon its bounded wait (it cannot
+ * while the device makes progress), it writes NaN, raises the flag, and every later call on that
+ * workspace yields NaN until spqt_workspace_init is run on it again - a late word of the abandoned
+ * call could otherwise be mistaken for a later call's. */
 int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out_bytes);
 
-/* DEVICE, async.  Clears the whole workspace (epochs and tagged words) with a small fill
+/* DEVICE, async.  Clears the whole workspace (head and exchange words) with a small fill
  * kernel, so it is safe under graph capture. */
 int spqt_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream);
 

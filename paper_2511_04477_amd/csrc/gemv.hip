@@ -81,7 +81,7 @@ template <int WAVES, bool DENSE, int BATCH, int FUSED>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    void *partials, int32_t *epochs, int K, int NG, int S, int T, int M, float thr) {
+    void *partials, int32_t *ws_flags, int K, int NG, int S, int T, int M, float thr) {
     // Two staging slots per wave (the pass being multiplied and the pass being fetched).
     __shared__ uint32_t stage_off[WAVES][2][kPassCols];      // byte offset of each column of the pass
     __shared__ float stage_x[WAVES][2][BATCH][kPassCols];    // its x per batch row, pre-scaled by 2^24
@@ -101,19 +101,13 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     const uint32_t seg16 = (uint32_t)seg * 16u;              // this lane's bytes inside a column run
     const uint32_t sc_off = (uint32_t)(seg * 64 + cgr * 8);  // this lane's 4 scales inside a chunk
     // Workgroups are handed to the 8 XCDs round-robin by index.  Keep all S workgroups of a
-    // block-row on ONE XCD (same index mod 8): their epoch word and partial sums then stay in that XCD's
+    // block-row on ONE XCD (same index mod 8): their partial sums then stay in that XCD's
     // L2 instead of bouncing between dies.  Only a matter of speed, never of correctness.
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;          // position among this XCD's workgroups
     const int t = xcd + 8 * (slot / S);        // block-row
     const int s = slot % S;
     if (t >= T) return;
-    // This call's tag for the cross-workgroup exchange (requested now, used at the very end).
-    uint32_t tag = 0;   // unsigned: the epoch wraps after 2^32 calls on one workspace, skipping 0
-    if (S > 1) {        // (0 is what a cleared, never written word carries)
-        tag = __hip_atomic_load(reinterpret_cast<uint32_t *>(epochs) + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        tag += tag == 0u;
-    }
 
     // Even split of the index list over the S*WAVES wavefronts of this block-row.
     // (a count outside 0..K cannot come from spqt_gather; clamping keeps a corrupt one inside idx)
@@ -601,7 +595,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         reinterpret_cast<f32x4 *>(red[wave][b])[8 * seg + cgr] = f32x4{yacc[b][0], yacc[b][1], yacc[b][2], yacc[b][3]};
     __syncthreads();
 
-    combine_block_row<WAVES, BATCH>(&red[0][0][0], tid, t, s, S, tag, partials, epochs, y, M);
+    combine_block_row<WAVES, BATCH>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
 }
 
 __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
@@ -612,39 +606,39 @@ __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
 template <int WAVES, int BATCH>
 hipError_t launch(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                   const int32_t *idx, const int32_t *count, float *y, void *partials,
-                  int32_t *epochs, int K, int NG, int S, int T, int M, int y_half) {
+                  int32_t *ws_flags, int K, int NG, int S, int T, int M, int y_half) {
     if (dense)
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, true, BATCH, 0>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+                           packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     else
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, BATCH, 0>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, idx, count, y, partials, epochs, K, NG, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+                           packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     return hipGetLastError();
 }
 
 template <int WAVES>
 hipError_t launch_fused(bool compact, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                        float thr, float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int M,
+                        float thr, float *y, void *partials, int32_t *ws_flags, int K, int NG, int S, int T, int M,
                         int y_half) {
     if (compact)
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, 1>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K,
+                           packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, ws_flags, K,
                            NG, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
     else
         hipLaunchKernelGGL((spqt_gemv_kernel<WAVES, false, 1, 2>), dim3(grid), dim3(WAVES * 64), 0, stream,
-                           packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, epochs, K,
+                           packed, x, (const int32_t *)nullptr, (const int32_t *)nullptr, y, partials, ws_flags, K,
                            NG, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
     return hipGetLastError();
 }
 
 // One launch for 2..4 activation rows (4 wavefronts per workgroup).
 hipError_t launch_fused_rows(int batch, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x, float thr,
-                             float *y, void *partials, int32_t *epochs, int K, int NG, int S, int T, int m_and_flags) {
+                             float *y, void *partials, int32_t *ws_flags, int K, int NG, int S, int T, int m_and_flags) {
     const int32_t *none = nullptr;
     switch (batch) {
-        case 2: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 2, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, epochs, K, NG, S, T, m_and_flags, thr); break;
-        case 3: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 3, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, epochs, K, NG, S, T, m_and_flags, thr); break;
-        default: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 4, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, epochs, K, NG, S, T, m_and_flags, thr); break;
+        case 2: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 2, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, ws_flags, K, NG, S, T, m_and_flags, thr); break;
+        case 3: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 3, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, ws_flags, K, NG, S, T, m_and_flags, thr); break;
+        default: hipLaunchKernelGGL((spqt_gemv_kernel<4, false, 4, 1>), dim3(grid), dim3(256), 0, stream, packed, x, none, none, y, partials, ws_flags, K, NG, S, T, m_and_flags, thr); break;
     }
     return hipGetLastError();
 }
@@ -652,12 +646,12 @@ hipError_t launch_fused_rows(int batch, int grid, hipStream_t stream, const uint
 template <int WAVES>
 hipError_t launch_batch(int batch, bool dense, int grid, hipStream_t stream, const uint8_t *packed,
                         const uint16_t *x, const int32_t *idx, const int32_t *count, float *y,
-                        void *partials, int32_t *epochs, int K, int NG, int S, int T, int M, int y_half) {
+                        void *partials, int32_t *ws_flags, int K, int NG, int S, int T, int M, int y_half) {
     switch (batch) {
-        case 1: return launch<WAVES, 1>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
-        case 2: return launch<WAVES, 2>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
-        case 3: return launch<WAVES, 3>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
-        default: return launch<WAVES, 4>(dense, grid, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, M, y_half);
+        case 1: return launch<WAVES, 1>(dense, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, M, y_half);
+        case 2: return launch<WAVES, 2>(dense, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, M, y_half);
+        case 3: return launch<WAVES, 3>(dense, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, M, y_half);
+        default: return launch<WAVES, 4>(dense, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, M, y_half);
     }
 }
 
@@ -674,8 +668,7 @@ extern "C" int spqt_workspace_bytes(int64_t M, int64_t K, int batch, size_t *out
 extern "C" int spqt_workspace_init(void *workspace_dev, size_t workspace_bytes, void *stream) {
     if (!workspace_dev || workspace_bytes < 256) return SPQT_EINVAL;
     if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-    // Epochs start at zero and no stale {value, tag} word may survive from an earlier use of
-    // this memory: clear all of it.
+    // The poison flag and every exchange word start at zero: clear all of it.
     size_t words = workspace_bytes / 4;
     hipLaunchKernelGGL(spqt_fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, (uint32_t *)workspace_dev, words);
@@ -690,10 +683,13 @@ extern "C" int spqt_default_cfg(int64_t M, int64_t K, int batch, int sparse, spq
     return SPQT_OK;
 }
 
-extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
-                            int batch, const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
-                            void *workspace_dev, size_t workspace_bytes, void *stream,
-                            const spqt_launch_cfg *cfg) {
+namespace {
+
+// spqt_gemv_ex, and the allocation-free variant: `tight` accepts a workspace that holds just the
+// exchange words this launch shape touches instead of the size spqt_workspace_bytes reports.
+int gemv_run(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev, int batch,
+             const int32_t *idx_dev, const int32_t *count_dev, void *y_dev, void *workspace_dev,
+             size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg, bool tight) {
     if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
     if (idx_dev && !count_dev) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, group)) return rc;
@@ -716,13 +712,14 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
 
     size_t need = 0;
     spqt_workspace_bytes(M, K, batch, &need);
+    if (tight) need = exchange_bytes(tiles(M), kTileRows, c.splits, batch);
     void *partials = nullptr;
-    int32_t *epochs = nullptr;
+    int32_t *ws_flags = nullptr;
     if (c.splits > 1) {
         if (!workspace_dev) return SPQT_EINVAL;
         if (workspace_bytes < need) return SPQT_ESIZE;
         if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-        epochs = (int32_t *)workspace_dev;
+        ws_flags = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
 
@@ -733,17 +730,27 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
     if (row_passes) {
-        err = launch_gemv_list(c.waves, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG,
+        err = launch_gemv_list(c.waves, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NG,
                                c.splits, T, (int)M | (y_half ? kHalfOutputBit : 0));
         return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
     }
     switch (c.waves) {
-        case 1: err = launch_batch<1>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
-        case 2: err = launch_batch<2>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
-        default: err = launch_batch<4>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        case 1: err = launch_batch<1>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        case 2: err = launch_batch<2>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        default: err = launch_batch<4>(batch, dense, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;
     }
     if (err != hipSuccess) return SPQT_EHIP;
     return SPQT_OK;
+}
+
+}  // namespace
+
+extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+                            int batch, const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
+                            void *workspace_dev, size_t workspace_bytes, void *stream,
+                            const spqt_launch_cfg *cfg) {
+    return gemv_run(packed_dev, M, K, group, x_dev, batch, idx_dev, count_dev, y_dev, workspace_dev,
+                    workspace_bytes, stream, cfg, false);
 }
 
 extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
@@ -766,12 +773,12 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
     size_t need = 0;
     spqt_workspace_bytes(M, K, 1, &need);
     void *partials = nullptr;
-    int32_t *epochs = nullptr;
+    int32_t *ws_flags = nullptr;
     if (c.splits > 1) {
         if (!workspace_dev) return SPQT_EINVAL;
         if (workspace_bytes < need) return SPQT_ESIZE;
         if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-        epochs = (int32_t *)workspace_dev;
+        ws_flags = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
     const int T = (int)tiles(M), NG = (int)(K / group);
@@ -782,9 +789,9 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
     switch (c.waves) {
-        case 1: err = launch_fused<1>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
-        case 2: err = launch_fused<2>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
-        default: err = launch_fused<4>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        case 1: err = launch_fused<1>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        case 2: err = launch_fused<2>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;
+        default: err = launch_fused<4>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }
@@ -811,19 +818,19 @@ extern "C" int spqt_gemv_fused_rows(const void *packed_dev, int64_t M, int64_t K
     size_t need = 0;
     spqt_workspace_bytes(M, K, batch, &need);
     void *partials = nullptr;
-    int32_t *epochs = nullptr;
+    int32_t *ws_flags = nullptr;
     if (c.splits > 1) {
         if (!workspace_dev) return SPQT_EINVAL;
         if (workspace_bytes < need) return SPQT_ESIZE;
         if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-        epochs = (int32_t *)workspace_dev;
+        ws_flags = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
     const int T = (int)tiles(M), NG = (int)(K / group);
     const int grid = 8 * ((T + 7) / 8) * c.splits;
     const int mf = (int)M | (y_half ? kHalfOutputBit : 0) | (own_sets ? kOwnSetsBit : 0);
     hipError_t err = launch_fused_rows(batch, grid, (hipStream_t)stream, (const uint8_t *)packed_dev, (const uint16_t *)x_dev,
-                                       threshold, (float *)y_dev, partials, epochs, (int)K, NG, c.splits, T, mf);
+                                       threshold, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, mf);
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }
 

@@ -51,7 +51,7 @@ template <int WAVES, bool DENSE, bool FUSED, int BATCH, bool KQ = false>
 __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    void *partials, int32_t *epochs, int K, int NC, int S, int T, int M, float thr) {
+    void *partials, int32_t *ws_flags, int K, int NC, int S, int T, int M, float thr) {
     // One staging area per wavefront is enough: offsets are written and read back inside a FETCH
     // stage, products inside a MULTIPLY stage, and a wavefront runs its stages one after the other.
     __shared__ uint32_t stage_off[WAVES][kPassCols];                               // byte offset of each column
@@ -72,11 +72,6 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
     const int t = xcd + 8 * (slot_id / S);
     const int s = slot_id % S;
     if (t >= T) return;
-    uint32_t tag = 0;   // unsigned: the epoch wraps after 2^32 calls on one workspace, skipping 0
-    if (S > 1) {        // (0 is what a cleared, never written word carries)
-        tag = __hip_atomic_load(reinterpret_cast<uint32_t *>(epochs) + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        tag += tag == 0u;
-    }
 
     // (a count outside 0..K cannot come from spqt_gather; clamping keeps a corrupt one inside idx)
     const int n_raw = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));
@@ -297,48 +292,48 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb_gemv_kernel(
             f32x4{r4[0] - bias, r4[1] - bias, r4[2] - bias, r4[3] - bias};
     }
     __syncthreads();
-    combine_block_row<WAVES, BATCH>(&red[0][0][0], tid, t, s, S, tag, partials, epochs, y, M);
+    combine_block_row<WAVES, BATCH>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
 }
 
 template <int WAVES, int BATCH>
 hipError_t launch_cb_batch(int mode, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                           const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                           const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *ws_flags,
                            int K, int NC, int S, int T, int M, int y_half) {
     const dim3 g(grid), b(WAVES * 64);
     if (mode == 3)        // K-quant flavour, index list
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, BATCH, true>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+                           partials, ws_flags, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     else if (mode == 4)   // K-quant flavour, dense
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, BATCH, true>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+                           partials, ws_flags, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     else if (mode == 0)   // index list
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, false, BATCH>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+                           partials, ws_flags, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     else                  // dense
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, true, false, BATCH>), g, b, 0, stream, packed, x, idx, count, y,
-                           partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
+                           partials, ws_flags, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), 0.0f);
     return hipGetLastError();
 }
 
 template <int WAVES>
 hipError_t launch_cb(int mode, int batch, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                     const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                     const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *ws_flags,
                      int K, int NC, int S, int T, int M, float thr, int y_half) {
     if (mode == 5) {      // K-quant flavour, threshold inside the kernel (batch 1)
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true, 1, true>), dim3(grid), dim3(WAVES * 64), 0, stream, packed,
-                           x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
+                           x, idx, count, y, partials, ws_flags, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
         return hipGetLastError();
     }
     if (mode == 2) {      // threshold inside the kernel (batch 1)
         hipLaunchKernelGGL((spqt_cb_gemv_kernel<WAVES, false, true, 1>), dim3(grid), dim3(WAVES * 64), 0, stream, packed,
-                           x, idx, count, y, partials, epochs, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
+                           x, idx, count, y, partials, ws_flags, K, NC, S, T, M | (y_half ? kHalfOutputBit : 0), thr);
         return hipGetLastError();
     }
     switch (batch) {
-        case 1: return launch_cb_batch<WAVES, 1>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
-        case 2: return launch_cb_batch<WAVES, 2>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
-        case 3: return launch_cb_batch<WAVES, 3>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
-        default: return launch_cb_batch<WAVES, 4>(mode, grid, stream, packed, x, idx, count, y, partials, epochs, K, NC, S, T, M, y_half);
+        case 1: return launch_cb_batch<WAVES, 1>(mode, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, y_half);
+        case 2: return launch_cb_batch<WAVES, 2>(mode, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, y_half);
+        case 3: return launch_cb_batch<WAVES, 3>(mode, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, y_half);
+        default: return launch_cb_batch<WAVES, 4>(mode, grid, stream, packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, y_half);
     }
 }
 
@@ -371,12 +366,12 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
     size_t need = 0;
     spqt_workspace_bytes(M, K, batch, &need);
     void *partials = nullptr;
-    int32_t *epochs = nullptr;
+    int32_t *ws_flags = nullptr;
     if (c.splits > 1) {
         if (!workspace_dev) return SPQT_EINVAL;
         if (workspace_bytes < need) return SPQT_ESIZE;
         if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-        epochs = (int32_t *)workspace_dev;
+        ws_flags = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
     const int T = (int)tiles(M), NC = (int)(K / kGroup);
@@ -386,9 +381,9 @@ int run_cb(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, co
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
     switch (c.waves) {
-        case 1: err = launch_cb<1>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
-        case 2: err = launch_cb<2>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
-        default: err = launch_cb<4>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
+        case 1: err = launch_cb<1>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
+        case 2: err = launch_cb<2>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
+        default: err = launch_cb<4>(mode, batch, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NC, c.splits, T, (int)M, threshold, y_half); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }

@@ -71,7 +71,7 @@ template <int WAVES, bool DENSE>
 __global__ __launch_bounds__(WAVES * 64) void spqt_cb8_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ count, float *__restrict__ y,
-    void *partials, int32_t *epochs, int K, int NC, int S, int T, int M) {
+    void *partials, int32_t *ws_flags, int K, int NC, int S, int T, int M) {
     __shared__ uint32_t stage_off[WAVES][kPassCols];                          // byte offset of each column
     __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][kPassCols][4];   // x * scale per block
     __shared__ __attribute__((aligned(16))) float red[WAVES][1][kRows8];
@@ -89,11 +89,6 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb8_gemv_kernel(
     const int t = xcd + 8 * (slot_id / S);
     const int s = slot_id % S;
     if (t >= T) return;
-    uint32_t tag = 0;
-    if (S > 1) {
-        tag = __hip_atomic_load(reinterpret_cast<uint32_t *>(epochs) + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        tag += tag == 0u;
-    }
 
     const int n_raw = DENSE ? K : __builtin_amdgcn_readfirstlane(*count);
     const int n_ns = n_raw < 0 ? 0 : (n_raw > K ? K : n_raw);
@@ -188,19 +183,19 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_cb8_gemv_kernel(
     red[wave][0][16 * seg + 2 * cgr + 0] = r2[0] - bias;
     red[wave][0][16 * seg + 2 * cgr + 1] = r2[1] - bias;
     __syncthreads();
-    combine_block_row<WAVES, 1, kRows8>(&red[0][0][0], tid, t, s, S, tag, partials, epochs, y, M);
+    combine_block_row<WAVES, 1, kRows8>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
 }
 
 template <int WAVES>
 hipError_t launch8(bool dense, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                   const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs, int K,
+                   const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *ws_flags, int K,
                    int NC, int S, int T, int m_and_flags) {
     if (dense)
         hipLaunchKernelGGL((spqt_cb8_gemv_kernel<WAVES, true>), dim3(grid), dim3(WAVES * 64), 0, stream, packed, x, idx,
-                           count, y, partials, epochs, K, NC, S, T, m_and_flags);
+                           count, y, partials, ws_flags, K, NC, S, T, m_and_flags);
     else
         hipLaunchKernelGGL((spqt_cb8_gemv_kernel<WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, stream, packed, x, idx,
-                           count, y, partials, epochs, K, NC, S, T, m_and_flags);
+                           count, y, partials, ws_flags, K, NC, S, T, m_and_flags);
     return hipGetLastError();
 }
 
@@ -234,12 +229,12 @@ extern "C" int spqt_cb8_gemv(const void *packed_dev, int64_t M, int64_t K, const
     size_t need = 0;
     spqt_workspace_bytes(M, K, 1, &need);
     void *partials = nullptr;
-    int32_t *epochs = nullptr;
+    int32_t *ws_flags = nullptr;
     if (S > 1) {
         if (!workspace_dev) return SPQT_EINVAL;
         if (workspace_bytes < need) return SPQT_ESIZE;
         if ((uintptr_t)workspace_dev % 256 != 0) return SPQT_EALIGN;
-        epochs = (int32_t *)workspace_dev;
+        ws_flags = (int32_t *)workspace_dev;
         partials = (void *)((uint8_t *)workspace_dev + counter_bytes(M));
     }
     const int T = (int)T64, NC = (int)(K / kGroup);
@@ -250,9 +245,9 @@ extern "C" int spqt_cb8_gemv(const void *packed_dev, int64_t M, int64_t K, const
     const int m_and_flags = (int)M | (y_half ? kHalfOutputBit : 0);
     hipError_t err;
     switch (waves) {
-        case 1: err = launch8<1>(idx_dev == nullptr, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, S, T, m_and_flags); break;
-        case 2: err = launch8<2>(idx_dev == nullptr, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, S, T, m_and_flags); break;
-        default: err = launch8<4>(idx_dev == nullptr, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, epochs, (int)K, NC, S, T, m_and_flags); break;
+        case 1: err = launch8<1>(idx_dev == nullptr, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NC, S, T, m_and_flags); break;
+        case 2: err = launch8<2>(idx_dev == nullptr, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NC, S, T, m_and_flags); break;
+        default: err = launch8<4>(idx_dev == nullptr, grid, st, pk, xp, idx_dev, count_dev, (float *)y_dev, partials, ws_flags, (int)K, NC, S, T, m_and_flags); break;
     }
     return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
 }

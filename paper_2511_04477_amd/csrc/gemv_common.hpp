@@ -170,7 +170,7 @@ __device__ __forceinline__ void code_rows(uint32_t w0, uint32_t w1, uint32_t w2,
 
 // The index-list kernel for one activation row with row-aligned passes (gemv_list.hip).
 hipError_t launch_gemv_list(int waves, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                            const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                            const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *ws_flags,
                             int K, int NG, int S, int T, int m_and_flags);
 
 // Combine the S workgroups of block-row t (paper Section 4.2.2: the partial sums of the
@@ -178,18 +178,20 @@ hipError_t launch_gemv_list(int waves, int grid, hipStream_t stream, const uint8
 // `red` holds this workgroup's [WAVES][BATCH][ROWS] partial sums in LDS (already synchronised);
 // ROWS is the height of a block-row (256 for the 4-bit layouts).
 // Every workgroup but the last (s == S-1) publishes its ROWS partial sums as 64-bit words
-// {value, tag} with device-scope stores and is done: no wait, no counter.  The last one adds
-// the others' words in index order, polling a word until its tag equals this call's tag,
-// then its own sums, and writes y.  The tag is the block-row's epoch + 1; the epoch lives in
-// the workspace, is read by everybody at kernel start and advanced by the reducer at the
-// end, so words left over from earlier calls never match.  A 64-bit store is a single
-// access: value and tag arrive together.  The reducer has the highest index of its block-row
-// and workgroups are dispatched in index order, so everything it waits for is running or
-// finished; the wait is bounded anyway and a give-up poisons y with NaN instead of hanging.
+// {value, kWordTag} with device-scope stores and is done: no wait, no counter.  The last one adds
+// the others' words in index order, polling a word until it carries the tag, then its own sums,
+// writes y, and stores zero back into every word it consumed - so between calls the exchange area
+// is all zeros whatever M, launch shape or kernel the calls had, and a word with the tag is always
+// one of THIS call.  A 64-bit store is a single access: value and tag arrive together.  The
+// reducer has the highest index of its block-row and workgroups are dispatched in index order, so
+// everything it waits for is running or finished; the wait is bounded anyway, and a give-up
+// poisons y with NaN instead of hanging and raises the workspace's poison flag (word 0 of its
+// head): a late word of the abandoned call could otherwise be taken for a later call's, so from
+// then on every call on that workspace yields NaN until spqt_workspace_init clears it.
+constexpr uint32_t kWordTag = 0x5B07C0DEu;
 template <int WAVES, int BATCH, int ROWS = kTileRows>
-__device__ __forceinline__ void combine_block_row(const float *red, int tid, int t, int s, int S, uint32_t tag,
-                                                  void *partials, int32_t *epochs, float *__restrict__ y,
-                                                  int m_and_flags) {
+__device__ __forceinline__ void combine_block_row(const float *red, int tid, int t, int s, int S, void *partials,
+                                                  int32_t *ws_flags, float *__restrict__ y, int m_and_flags) {
     // One kernel argument carries both (M <= 2^24): every extra scalar argument costs the
     // four-row kernels, which sit at the register limit, a spill.
     const int M = m_and_flags & kRowsMask;
@@ -201,6 +203,9 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
     // all of them are in flight at once (one round trip instead of one per value).
     constexpr int kTogether = kPerThread < 2 ? kPerThread : 2;
     unsigned long long *slots = reinterpret_cast<unsigned long long *>(partials) + (size_t)t * S * kOut;
+    const bool reducer = S > 1 && s == S - 1;
+    uint32_t poisoned = 0u;
+    if (reducer) poisoned = __hip_atomic_load(reinterpret_cast<uint32_t *>(ws_flags), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int r0 = tid; r0 < kOut; r0 += kTogether * kThreads) {
         int r[kTogether];
         bool real[kTogether];
@@ -224,10 +229,11 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
 #pragma unroll
             for (int i = 0; i < kTogether; ++i)
                 if (real[i]) store_y(i, sum[i]);
-        } else if (s != S - 1) {
+        } else if (!reducer) {
 #pragma unroll
             for (int i = 0; i < kTogether; ++i) {
-                const unsigned long long word = ((unsigned long long)tag << 32) | as_u32(sum[i]);
+                if (i > 0 && r[i] == r[0]) continue;   // a clamped duplicate: already published
+                const unsigned long long word = ((unsigned long long)kWordTag << 32) | as_u32(sum[i]);
                 __hip_atomic_store(slots + (size_t)s * kOut + r[i], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         } else {
@@ -253,7 +259,7 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
 #pragma unroll
                     for (int i = 0; i < kTogether; ++i)
 #pragma unroll
-                        for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[i][j] >> 32) ^ tag;
+                        for (int j = 0; j < 16; ++j) missing |= (uint32_t)(v[i][j] >> 32) ^ kWordTag;
                     all_here = missing == 0u;
                 } while (!all_here && ++polls < kMaxPolls);
                 gave_up = gave_up || !all_here;
@@ -261,15 +267,19 @@ __device__ __forceinline__ void combine_block_row(const float *red, int tid, int
                 for (int i = 0; i < kTogether; ++i)
 #pragma unroll
                     for (int j = 0; j < 16; ++j)
-                        if (p0 + j < S - 1) total[i] += as_float((uint32_t)v[i][j]);
+                        if (p0 + j < S - 1) {
+                            total[i] += as_float((uint32_t)v[i][j]);
+                            // consumed: the word goes back to zero for whatever call comes next
+                            __hip_atomic_store(slots + (size_t)(p0 + j) * kOut + r[i], 0ull, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                        }
             }
+            if (gave_up) __hip_atomic_store(reinterpret_cast<uint32_t *>(ws_flags), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int i = 0; i < kTogether; ++i)
-                if (real[i]) store_y(i, gave_up ? __builtin_nanf("") : total[i] + sum[i]);
+                if (real[i]) store_y(i, (gave_up || poisoned) ? __builtin_nanf("") : total[i] + sum[i]);
         }
     }
-    if (S > 1 && s == S - 1 && tid == 0)
-        __hip_atomic_store(reinterpret_cast<uint32_t *>(epochs) + t, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace spqt

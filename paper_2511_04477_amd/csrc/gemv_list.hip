@@ -37,7 +37,7 @@ __device__ __forceinline__ h2 as_h2(uint32_t bits) { return __builtin_bit_cast(h
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x, const int32_t *__restrict__ idx,
-    const int32_t *__restrict__ count, float *__restrict__ y, void *partials, int32_t *epochs, int K, int NG,
+    const int32_t *__restrict__ count, float *__restrict__ y, void *partials, int32_t *ws_flags, int K, int NG,
     int S, int T, int M) {
     // Two staging slots per wave (the pass being multiplied and the pass being fetched).
     __shared__ __attribute__((aligned(16))) uint32_t stage_off[WAVES][2][kPassCols];   // byte offset of each slot's column in the block-row
@@ -59,11 +59,6 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
     const int t = xcd + 8 * (slot_x / S);
     const int s = slot_x % S;
     if (t >= T) return;
-    uint32_t tag = 0;
-    if (S > 1) {
-        tag = __hip_atomic_load(reinterpret_cast<uint32_t *>(epochs) + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-        tag += tag == 0u;
-    }
 
     const int n_raw = __builtin_amdgcn_readfirstlane(*count);
     const int n_ns = n_raw < 0 ? 0 : (n_raw > K ? K : n_raw);
@@ -226,7 +221,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
     reinterpret_cast<f32x4 *>(red[wave][0])[8 * seg + cgr] =
         f32x4{r4[0] * kTwo24, r4[1] * (kTwo24 * 0.0625f), r4[2] * kTwo24, r4[3] * (kTwo24 * 0.0625f)};
     __syncthreads();
-    combine_block_row<WAVES, 1>(&red[0][0][0], tid, t, s, S, tag, partials, epochs, y, M);
+    combine_block_row<WAVES, 1>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
 }
 
 }  // namespace
@@ -234,12 +229,12 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
 namespace spqt {
 
 hipError_t launch_gemv_list(int waves, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
-                            const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *epochs,
+                            const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *ws_flags,
                             int K, int NG, int S, int T, int m_and_flags) {
     switch (waves) {
-        case 1: hipLaunchKernelGGL((spqt_gemv_list_kernel<1>), dim3(grid), dim3(64), 0, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, m_and_flags); break;
-        case 2: hipLaunchKernelGGL((spqt_gemv_list_kernel<2>), dim3(grid), dim3(128), 0, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, m_and_flags); break;
-        default: hipLaunchKernelGGL((spqt_gemv_list_kernel<4>), dim3(grid), dim3(256), 0, stream, packed, x, idx, count, y, partials, epochs, K, NG, S, T, m_and_flags); break;
+        case 1: hipLaunchKernelGGL((spqt_gemv_list_kernel<1>), dim3(grid), dim3(64), 0, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, m_and_flags); break;
+        case 2: hipLaunchKernelGGL((spqt_gemv_list_kernel<2>), dim3(grid), dim3(128), 0, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, m_and_flags); break;
+        default: hipLaunchKernelGGL((spqt_gemv_list_kernel<4>), dim3(grid), dim3(256), 0, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, m_and_flags); break;
     }
     return hipGetLastError();
 }

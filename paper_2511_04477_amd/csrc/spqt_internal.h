@@ -18,11 +18,14 @@ static_assert(kChunkBytes == kScaleBytes + kGroup * kColBytes, "chunk size");
 // Block-rows of a matrix with M rows; the last one is zero-padded when M is not a multiple of 256.
 inline int64_t tiles(int64_t M) { return (M + kTileRows - 1) / kTileRows; }
 
-// Bytes reserved at the head of the workspace for the per-block-row epoch counters (two per
-// 256 rows: the 8-bit layout's block-rows are 128 rows high).
-inline size_t counter_bytes(int64_t M) {
-    size_t n = (size_t)tiles(M) * 2 * sizeof(int32_t);
-    return (n + 255) & ~(size_t)255;
+// Bytes reserved at the head of the workspace: word 0 is the poison flag the reducers raise when a
+// wait for partial sums is abandoned; the rest keeps the exchange words 256-byte aligned.
+inline size_t counter_bytes(int64_t) { return 256; }
+
+// Bytes of exchange words a launch with S workgroups per block-row really touches (64-bit words,
+// `rows` outputs per block-row and activation row), head included.
+inline size_t exchange_bytes(int64_t n_tiles, int rows, int S, int batch) {
+    return 256 + (size_t)n_tiles * (size_t)rows * (size_t)S * (size_t)batch * 8;
 }
 
 // Bytes of one chunk (block-row t, group g) of the group layout: 256 fp16 scales + `group` column runs.

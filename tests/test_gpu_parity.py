@@ -370,28 +370,51 @@ def test_longest_supported_k(gpu):
     assert_close(gpu_gemv(gpu, w, x, 0.0, dense=True), oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0), "K=65536 dense")
 
 
-def test_exchange_tag_wraps_around(gpu):
-    """The tag of the partial-sum exchange is the block-row's epoch + 1 as an unsigned 32-bit
-    number; start the epochs just under 2^32 and run across the wrap."""
+def test_one_workspace_serves_any_sequence_of_shapes_and_kernels(gpu):
+    """The reducer of a block-row puts every exchange word it consumed back to zero, so one workspace may
+    serve calls of different M, K, launch shape and kernel in any order: after every call the whole
+    workspace reads as zeros again and the result is that of a fresh workspace."""
     torch, spqt, dev = gpu
-    M, K = 1024, 2048
-    w = make_weights(M, K, 91)
-    x_np = make_x(K, "laplace", 92)
-    thr = quantile_threshold(x_np, 0.5)
-    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x_np, thr)
-    packed = torch.from_numpy(spqt.spqt_pack(w["q_rowmajor"], w["scales"])).to(dev)
-    x = torch.from_numpy(x_np[0]).to(dev)
-    idx = torch.empty(K, dtype=torch.int32, device=dev)
-    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-    spqt.spqt_gather(x, thr, idx, cnt)
-    ws = spqt.new_workspace(M, K)
-    ws.view(torch.int32)[: M // 256] = -3          # 0xFFFFFFFD: the third call from now wraps
-    for call in range(6):
+    shapes = [(1024, 2048), (2048, 1024), (300, 1024), (1024, 2048), (512, 4096)]
+    ws = spqt.new_workspace(2048, 4096, 2)
+    cases = {}
+    for (M, K) in set(shapes):
+        w = make_weights(M, K, 91 + M + K)
+        x_np = make_x(K, "laplace", 92 + M, batch=2)
+        thr = quantile_threshold(x_np[:1], 0.5)
+        cases[(M, K)] = (w, x_np, thr, torch.from_numpy(spqt.spqt_pack(w["q_rowmajor"], w["scales"])).to(dev),
+                         oracle.gemv(w["q_rowmajor"], w["scales"], x_np[:1], thr),
+                         oracle.gemv(w["q_rowmajor"], w["scales"], x_np, thr),
+                         oracle.gemv(w["q_rowmajor"], w["scales"], x_np[:1], 0.0))
+    launch = [(8, 2), (16, 4), (3, 1), (5, 4), (64, 1)]
+    for call, (M, K) in enumerate(shapes):
+        w, x_np, thr, packed, ref1, ref2, ref_dense = cases[(M, K)]
+        splits, waves = launch[call]
+        say(f"shared workspace call {call}: {M}x{K} splits={splits} waves={waves}")
+        x1 = torch.from_numpy(x_np[0]).to(dev)
+        x2 = torch.from_numpy(x_np).to(dev)
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
         y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
-        spqt.spqt_gemv(packed, M, K, x, idx, cnt, y, ws, splits=8, waves=2)
+        spqt.spqt_gather(x1, thr, idx, cnt)
+        spqt.spqt_gemv(packed, M, K, x1, idx, cnt, y, ws, splits=splits, waves=waves)
         torch.cuda.synchronize()
-        assert_close(y.cpu().numpy()[None, :], ref, f"call {call} across the epoch wrap")
-    assert int(ws.view(torch.int32)[0].item()) == 4    # ... FFFFFFFE, FFFFFFFF, 1 (0 skipped), 2, 3, 4
+        assert_close(y.cpu().numpy()[None, :], ref1, f"list, call {call}")
+        assert int(torch.count_nonzero(ws).item()) == 0, "exchange words must be back to zero"
+        y.fill_(float("nan"))
+        spqt.spqt_gemv(packed, M, K, x1, None, None, y, ws, splits=splits, waves=waves)
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy()[None, :], ref_dense, f"dense, call {call}")
+        y.fill_(float("nan"))
+        spqt.spqt_gemv_fused(packed, M, K, x1, thr, y, ws, splits=min(splits, K // 64), waves=waves)
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy()[None, :], ref1, f"one launch, call {call}")
+        y2 = torch.full((2, M), float("nan"), dtype=torch.float32, device=dev)
+        spqt.spqt_gather(x2, thr, idx, cnt)
+        spqt.spqt_gemv(packed, M, K, x2, idx, cnt, y2, ws, splits=splits, waves=waves)
+        torch.cuda.synchronize()
+        assert_close(y2.cpu().numpy(), ref2, f"two rows, call {call}")
+        assert int(torch.count_nonzero(ws).item()) == 0, "exchange words must be back to zero"
 
 
 def test_hip_graph_replay_matches_eager(gpu):
@@ -438,7 +461,7 @@ def test_hip_graph_replay_matches_eager(gpu):
 FULL = [(2, "q", [0.0, 0.25, 0.4, 0.5, 0.65]),
         (3, "gate", [0.4, 0.5]), (3, "down", [0.4, 0.5]),
         (4, "k", [0.5]), (4, "gate", [0.5]), (4, "down", [0.5]),
-        (5, "gate", [0.3, 0.5, 0.7]), (5, "down", [0.5])]
+        (5, "gate", [0.3, 0.5, 0.7]), (5, "down", [0.3, 0.5, 0.7])]
 
 
 @pytest.mark.parametrize("config,tensor,sparsities", FULL)
@@ -457,3 +480,36 @@ def test_full_size_default_launch(gpu, config, tensor, sparsities):
         say(f"   s={s}: max|err|={e:.3e}")
     ref = oracle.gemv(case["q_rowmajor"], case["scales"], case["x"], 0.0)
     assert_close(gpu_gemv(gpu, case, case["x"], 0.0, dense=True, packed=packed), ref, "dense")
+
+
+@pytest.mark.parametrize("tensor", ["gate", "down"])
+def test_full_size_four_rows_union_list(gpu, tensor):
+    """The 70B MLP shapes with 4 activation rows: spqt_gather(batch 4) gives the union list, spqt_gemv(batch 4)
+    consumes it in the library's default launch shape - the calls and shape the benchmark times.  The index
+    list is compared whole; the outputs on 640 sampled rows (the last block-row included) that the oracle
+    computes one by one."""
+    torch, spqt, dev = gpu
+    case = make_case(5, tensor, batch=4, want_q=False)
+    M, K = case["M"], case["K"]
+    q, sc, x_np = case["q_rowmajor"], case["scales"], case["x"]
+    packed = torch.from_numpy(spqt.spqt_pack(q, sc)).to(dev)
+    rng = np.random.default_rng(9970 + M)
+    rows = np.unique(np.concatenate([rng.choice(M - 256, size=512, replace=False), np.arange(M - 128, M)]))
+    x = torch.from_numpy(x_np).to(dev)
+    idx = torch.full((K,), -7, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws = spqt.new_workspace(M, K, 4)
+    for s in (0.3, 0.5, 0.7):
+        thr = quantile_threshold(x_np, s)
+        say(f"four rows, full size: {tensor} {M}x{K} s={s}")
+        y = torch.full((4, M), float("nan"), dtype=torch.float32, device=dev)
+        idx.fill_(-7)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        spqt.spqt_gemv(packed, M, K, x, idx, cnt, y, ws)
+        torch.cuda.synchronize()
+        ref_idx, n = oracle.gather(x_np, thr)
+        assert int(cnt.item()) == n and np.array_equal(idx[:n].cpu().numpy(), ref_idx)
+        got = y.cpu().numpy()
+        assert not np.isnan(got).any()
+        e = assert_close(got[:, rows], oracle.gemv_rows(q, sc, x_np, thr, rows), f"{tensor} 4 rows s={s}")
+        say(f"   kept {n}/{K}, max|err|={e:.3e}")
