@@ -186,6 +186,26 @@ int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const 
                  void *workspace_dev, size_t workspace_bytes, void *stream,
                  const spqt_launch_cfg *cfg);
 
+/* DEVICE, async.  spqt_gemv for callers that cannot allocate device memory and therefore cannot bring
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, kernels, launch shape and results as spqt_gemv; the exchange words live in a fixed
+ * array of SPQT_STATIC_SCRATCH_BYTES inside the library's device image (every GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees nothing.
+ *   - SPQT_ESIZE when the default launch shape for (M, K, batch) needs more exchange words than the
+ *     array holds: 256 + ceil(M/256) * 256 * splits * batch * 8 bytes, splits as spqt_default_cfg
+ *     reports (a shape that runs with one workgroup per block-row needs none).  The default launch
+ *     shapes keep block-rows x splits <= 512, so every shape fits with 1 or 2 activation rows; with
+ *     3 or 4 rows the large ones (e.g. 8192 x 28672: 32 block-rows x 16 splits) do not.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ *     different host threads) race on it and must use spqt_gemv with workspaces of their own.  Every
+ *     call leaves the array all zeros, so successive calls may differ in shape.
+ *   - The first call on a GPU looks the array's device address up (no allocation either); make that
+ *     call outside graph capture. */
+#define SPQT_STATIC_SCRATCH_BYTES ((2u << 20) + 256u)
+int spqt_gemv_static(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+                     int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                     void *stream);
+
 /* DEVICE, async.  Gather and GEMV in ONE launch, batch 1: the kernel applies the sparsity test of
  * Section 2 (sparse iff |x_i| < threshold, compared in fp32) to x itself, compacts the kept
  * columns of each 64-column stretch with a wavefront ballot, and multiplies - no index list

@@ -26,7 +26,7 @@ CFG_GROUP_PASSES = 8
 
 EXPORTS = [
     "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",
-    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gather_rows", "spqt_gemv", "spqt_gemv_ex", "spqt_gemv_fused", "spqt_gemv_fused_rows",
+    "spqt_pack", "spqt_unpack", "spqt_gather", "spqt_gather_rows", "spqt_gemv", "spqt_gemv_ex", "spqt_gemv_static", "spqt_gemv_fused", "spqt_gemv_fused_rows",
     "spqt_default_cfg",
 ]
 
@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
         L.spqt_gemv.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         L.spqt_gemv_ex.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp,
                                    c.POINTER(LaunchCfg)]
+        L.spqt_gemv_static.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp, vp, vp]
         L.spqt_gemv_fused.argtypes = [vp, i64, i64, i32, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_gemv_fused_rows.argtypes = [vp, i64, i64, i32, vp, i32, c.c_float, i32, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_default_cfg.argtypes = [i64, i64, i32, i32, c.POINTER(LaunchCfg)]
@@ -245,6 +246,22 @@ def spqt_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, 
     else:
         rc = lib().spqt_gemv(pp, M, K, group, xp, batch, ip, cp, yp, wp, wbytes, _stream_ptr(stream))
     _check(rc)
+
+
+def spqt_gemv_static(packed, M: int, K: int, x, idx, count, y, stream=None, group: int = GROUP) -> None:
+    """spqt_gemv without a workspace argument: the exchange words live in the library's own device array."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp = _dev(y, torch.float32, "y")
+    batch = 1 if x.dim() == 1 else x.shape[0]
+    if x.shape[-1] != K or y.numel() != batch * M or packed.numel() < spqt_packed_bytes(M, K, group):
+        raise SpqtError("spqt_gemv_static: x / y / packed sizes do not match M, K, batch")
+    ip = cp = None
+    if idx is not None:
+        ip = _dev(idx, torch.int32, "idx")
+        cp = _dev(count, torch.int32, "count")
+    _check(lib().spqt_gemv_static(pp, M, K, group, xp, batch, ip, cp, yp, _stream_ptr(stream)))
 
 
 def spqt_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspace, stream=None,

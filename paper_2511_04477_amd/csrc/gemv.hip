@@ -54,6 +54,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "gemv_common.hpp"
 
 namespace {
@@ -743,6 +745,28 @@ int gemv_run(const void *packed_dev, int64_t M, int64_t K, int group, const void
     return SPQT_OK;
 }
 
+// Exchange words for callers that cannot bring a workspace: one array per GPU, in the library's own
+// image, zero when the image is loaded and put back to zero by every call that used it.
+constexpr size_t kStaticScratchBytes = SPQT_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_of_device[kMaxDevices];   // this process's address of `scratch` on each GPU, once known
+
+// The array's name is only a host-side handle: its device address comes from the runtime, per GPU.
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPQT_EHIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_of_device[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SPQT_EHIP;
+        scratch_of_device[dev] = p;
+    }
+    *out = scratch_of_device[dev];
+    return SPQT_OK;
+}
+
 }  // namespace
 
 extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
@@ -751,6 +775,22 @@ extern "C" int spqt_gemv_ex(const void *packed_dev, int64_t M, int64_t K, int gr
                             const spqt_launch_cfg *cfg) {
     return gemv_run(packed_dev, M, K, group, x_dev, batch, idx_dev, count_dev, y_dev, workspace_dev,
                     workspace_bytes, stream, cfg, false);
+}
+
+extern "C" int spqt_gemv_static(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
+                                int batch, const int32_t *idx_dev, const int32_t *count_dev, float *y_dev,
+                                void *stream) {
+    // Shape errors first, so that a bad call never touches the runtime.
+    if (int rc = check_shape(M, K, group)) return rc;
+    if (batch < 1 || batch > SPQT_MAX_BATCH) return SPQT_ESHAPE;
+    spqt_launch_cfg c;
+    const bool dense = idx_dev == nullptr;
+    choose_cfg(M, K, batch, dense ? Kernel::dense : (batch == 1 ? Kernel::list_rows : Kernel::list_groups), &c);
+    if (c.splits > 1 && exchange_bytes(tiles(M), kTileRows, c.splits, batch) > kStaticScratchBytes) return SPQT_ESIZE;
+    void *ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return gemv_run(packed_dev, M, K, group, x_dev, batch, idx_dev, count_dev, y_dev, ws, kStaticScratchBytes,
+                    stream, nullptr, true);
 }
 
 extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
