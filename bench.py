@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the SpQt hot path on one MI355X.
 
-A step is one pass of the whole hot path over one activation vector: spqt_gather (threshold
-+ index compaction) followed by the load-balanced sparse int4 GEMV, batch 1.  The headline
-workload is the Llama-7B attention-projection shape (4096 x 4096, group 128) at 50 %
-activation sparsity.  Weight buffers rotate over independently seeded copies whose total
-size is several times the 256 MB Infinity Cache, so no launch re-reads cached weights.
+A step is one pass of the whole hot path over one activation vector: spqt_gather (threshold + index
+compaction) followed by the load-balanced sparse int4 GEMV, batch 1.  The headline workload is the
+largest single-GPU configuration: the 70B-shaped MLP gate projection (28672 x 8192, group 128) at 50 %
+activation sparsity.  Weight buffers rotate over independently seeded copies whose total size is
+several times the 256 MB Infinity Cache, so no launch re-reads cached weights.
 
-Prints ONE JSON line (the fields are built in main() below).  `--gpus` above 1 is refused:
-this build is a one-GPU kernel path.
+Prints ONE JSON line (the fields are built in main() below): the headline step, the GEMV-only kernel
+time with its roofline fraction, the dense kernel, the one-launch kernels, a sweep over the other
+configurations' shapes and sparsities, the decoder-layer sequences of configurations 3 and 4, what
+trivial kernels reach on this machine, and the CPU oracle timed on the same workload.  `--full` adds the
+side studies of bench_studies.py.  `--gpus` above 1 is refused: this build is a one-GPU kernel path.
 """
 from __future__ import annotations
 
@@ -18,805 +21,25 @@ import os
 import sys
 import time
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
-if ROOT not in sys.path:
-    sys.path.insert(0, ROOT)
+from bench_support import (HBM_PEAK_GBPS, ROOT, Workload, calibrate, kept_bytes, layer_sequence, time_sequence)
 
-HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E peak
-# HBM bytes per sparse-GEMV launch on the headline workload, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE scaled by a plain copy kernel of known size (profiles/spqt_gemv_sparse_4096x4096_s50.md).
-MEASURED_TRAFFIC_BYTES = {(4096, 4096, 0.5): 5759274}
-INFINITY_CACHE_BYTES = 256 << 20
-ROTATE_BYTES = 3 * INFINITY_CACHE_BYTES   # rotate over at least this many bytes of weights
+HEADLINE = dict(config=5, tensor="gate", M=28672, K=8192, dist="laplace", sparsity=0.5)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 
-def kept_bytes(M, K, n_ns, groups_touched=None):
-    """Algorithmic HBM bytes of one sparse GEMV: the 128-byte runs of the kept columns plus the
-    fp16 scales of every (row, group) that has a kept column."""
-    ng = K // 128 if groups_touched is None else groups_touched
-    return n_ns * M // 2 + ng * M * 2
-
-
-class Workload:
-    """Rotating set of packed weight copies + per-copy activations, thresholds and index lists
-    for one (M, K) shape at one sparsity."""
-
-    def __init__(self, torch, spqt, M, K, dist, scale_range, config, tensor, sparsity, copies=None, batch=1):
-        import numpy as np
-        from workloads import make_case, make_x, quantile_threshold, seed_for, KIND_X
-        self.torch, self.spqt, self.M, self.K = torch, spqt, M, K
-        self.sparsity = sparsity
-        self.batch = batch
-        dev = torch.device("cuda:0")
-        pbytes = spqt.spqt_packed_bytes(M, K)
-        self.copies = copies or max(2, -(-ROTATE_BYTES // pbytes))
-        lo, hi = scale_range
-        T, NG = M // 256, K // 128
-        # copy 0: the seeded row-major tensors of the workload module, repacked by the library
-        self.case0 = make_case(config, tensor, layer=0, want_q=False)
-        self.packed = [torch.from_numpy(spqt.spqt_pack(self.case0["q_rowmajor"], self.case0["scales"])).to(dev)]
-        # other copies: independently seeded random codes and scales drawn directly in packed
-        # form on the GPU (any byte is a valid pair of codes; scale area gets fp16 U(lo, hi))
-        for layer in range(1, self.copies):
-            g = torch.Generator(device=dev)
-            g.manual_seed(seed_for(config, layer, tensor))
-            buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NG, 256), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
-            buf[:, :512] = sc.view(torch.uint8)
-            self.packed.append(buf.reshape(-1))
-        xs, thr = [], []
-        self.dist = dist
-        for layer in range(self.copies):
-            x = make_x(K, dist, seed_for(config, layer, tensor, KIND_X), batch)
-            xs.append(x[0] if batch == 1 else x)
-            thr.append(quantile_threshold(x, sparsity))
-        self.x_np = np.stack(xs)
-        self.thr = thr
-        self.x = torch.from_numpy(self.x_np).to(dev)
-        self.idx = torch.zeros((self.copies, K), dtype=torch.int32, device=dev)
-        self.cnt = torch.zeros((self.copies, 1), dtype=torch.int32, device=dev)
-        self.y = torch.zeros((self.copies, M) if batch == 1 else (self.copies, batch, M), dtype=torch.float32, device=dev)
-        self.ws = spqt.new_workspace(M, K, batch)
-        self.x_masked = torch.zeros_like(self.x) if batch > 1 else None
-        for i in range(self.copies):
-            spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
-        torch.cuda.synchronize()
-        self.n_ns = self.cnt.cpu().numpy().ravel()
-        self.mean_kept_bytes = float(np.mean([kept_bytes(M, K, int(n)) for n in self.n_ns]))
-        self.dense_bytes = kept_bytes(M, K, K)
-
-    # one step of the hot path on copy i
-    def step(self, i):
-        self.spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
-        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
-
-    def step_own_sets(self, i):
-        """Several rows, each keeping its own set: union list + per-row zeroed copy of x."""
-        self.spqt.spqt_gather_rows(self.x[i], self.thr[i], self.idx[i], self.cnt[i], self.x_masked[i])
-        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x_masked[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
-
-    def gemv_only(self, i):
-        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws)
-
-    def gemv_group_passes(self, i):
-        """The index-list kernel whose passes hold columns of one quantization group (an ablation)."""
-        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], self.idx[i], self.cnt[i], self.y[i], self.ws,
-                            flags=self.spqt.CFG_GROUP_PASSES)
-
-    def gather_only(self, i):
-        self.spqt.spqt_gather(self.x[i], self.thr[i], self.idx[i], self.cnt[i])
-
-    def fused(self, i):
-        self.spqt.spqt_gemv_fused(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws)
-
-    def fused_rows(self, i):
-        """Several rows in one launch, union of the kept sets."""
-        self.spqt.spqt_gemv_fused_rows(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws)
-
-    def fused_rows_own_sets(self, i):
-        """Several rows in one launch, each summing over its own kept set."""
-        self.spqt.spqt_gemv_fused_rows(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws, own_sets=True)
-
-    def fused_no_compaction(self, i):
-        self.spqt.spqt_gemv_fused(self.packed[i], self.M, self.K, self.x[i], self.thr[i], self.y[i], self.ws,
-                                  flags=self.spqt.CFG_NO_COMPACTION)
-
-    def dense_only(self, i):
-        self.spqt.spqt_gemv(self.packed[i], self.M, self.K, self.x[i], None, None, self.y[i], self.ws)
-
-    def check_copy0(self, cpu):
-        """Parity of copy 0 against the oracle (through the cpu_baseline leg) in exactly this launch
-        configuration; (True, None) when the leg is off."""
-        import numpy as np
-        if not cpu.enabled:
-            return True, None
-        self.step(0)
-        self.torch.cuda.synchronize()
-        ref_idx, n = cpu.gather(self.x_np[0:1], self.thr[0])
-        ref = cpu.gemv(self.case0, self.x_np[0:1], self.thr[0])
-        ok_idx = int(self.cnt[0].item()) == n and np.array_equal(self.idx[0, :n].cpu().numpy(), ref_idx)
-        ok_y, max_err = cpu.close(self.y[0].cpu().numpy(), ref)
-        return ok_idx and ok_y, max_err
-
-
-def make_graph(torch, fn, n):
-    """Capture fn(0..n-1) back to back into one HIP graph."""
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
-        for i in range(n):
-            fn(i)
-    return g
-
-
-def time_sequence(torch, fn, copies, steps, warmup, use_graph=True, exact_warmup=False):
-    """Average microseconds per call of fn over exactly `steps` calls (after `warmup` untimed
-    ones), rotating the copy index; HIP events on the launch stream bracket the timed region.
-    Side measurements get at least 200 warm-up calls and at least 30 ms of them (a first
-    measurement on an idle GPU otherwise reads 5-10 % high); the headline passes exact_warmup and
-    gets exactly `warmup`."""
-    if not exact_warmup:
-        warmup = max(warmup, 200)
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    fn(0)                       # first launch of a kernel loads its code object: not under capture
-    torch.cuda.synchronize()
-    if use_graph:
-        s = torch.cuda.Stream()
-        with torch.cuda.stream(s):
-            full = make_graph(torch, fn, copies)
-            rem_n = steps % copies
-            rem = make_graph(torch, fn, rem_n) if rem_n else None
-            for _ in range(max(1, -(-warmup // copies))):
-                full.replay()
-            torch.cuda.synchronize()
-            if not exact_warmup:    # and at least 30 ms of them: after seconds of host work the clocks are down
-                t0 = time.perf_counter()
-                while time.perf_counter() - t0 < 0.03:
-                    full.replay()
-                    torch.cuda.synchronize()
-            start.record()
-            for _ in range(steps // copies):
-                full.replay()
-            if rem is not None:
-                rem.replay()
-            stop.record()
-            torch.cuda.synchronize()
-    else:
-        for k in range(warmup):
-            fn(k % copies)
-        torch.cuda.synchronize()
-        start.record()
-        for k in range(steps):
-            fn(k % copies)
-        stop.record()
-        torch.cuda.synchronize()
-    return start.elapsed_time(stop) * 1e3 / steps
-
-
-class Calib:
-    """ctypes face of libspqt_calib.so: plain streaming read / copy / empty launch, used to put the
-    GEMV numbers next to what a trivial kernel reaches on the same box."""
-
-    def __init__(self, torch):
-        import ctypes
-        self.torch = torch
-        path = os.path.join(ROOT, "paper_2511_04477_amd", "libspqt_calib.so")
-        L = ctypes.CDLL(path)
-        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
-        L.spqt_calib_read.argtypes = [vp, sz, vp, i32, i32, vp]
-        L.spqt_calib_copy.argtypes = [vp, vp, sz, i32, vp]
-        L.spqt_calib_empty.argtypes = [vp]
-        L.spqt_calib_rowmajor_gemv.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_float, i32, vp, vp]
-        self.L = L
-        self.sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
-
-    def stream(self):
-        return self.torch.cuda.current_stream().cuda_stream
-
-    def empty(self, _i=0):
-        self.L.spqt_calib_empty(self.stream())
-
-    def read(self, buf, offset, nbytes, blocks=0, unroll=4):
-        self.L.spqt_calib_read(buf.data_ptr() + offset, nbytes, self.sink.data_ptr(), blocks, unroll, self.stream())
-
-    def rowmajor_gemv(self, q, scales, M, K, x, thr, skip, y):
-        rc = self.L.spqt_calib_rowmajor_gemv(q.data_ptr(), scales.data_ptr(), M, K, x.data_ptr(), float(thr), int(skip),
-                                             y.data_ptr(), self.stream())
-        if rc != 0:
-            raise RuntimeError(f"spqt_calib_rowmajor_gemv failed ({rc})")
-
-    def copy(self, dst, src, nbytes):
-        self.L.spqt_calib_copy(dst.data_ptr(), src.data_ptr(), nbytes, 0, self.stream())
-
-
-def calibrate(torch, nbytes_like):
-    """(empty-launch us, us of a plain cold streaming read of ~nbytes_like bytes, GB/s of a 1 GiB read)."""
-    cal = Calib(torch)
-    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 256)
-    t_empty = time_sequence(torch, cal.empty, 100, 2000, 200, True)
-    size = max(1 << 20, (int(nbytes_like) + 65535) // 65536 * 65536)
-    k = (1 << 30) // size
-    blocks = max(64, min(4096, size // 16 // 256 // 2))
-    t_small = time_sequence(torch, lambda i: cal.read(big, (i % k) * size, size, blocks, 2), k, 2 * k, k, True)
-    t_big = time_sequence(torch, lambda i: cal.read(big, 0, 1 << 30, 8192, 4), 2, 6, 2, True)
-    del big
-    torch.cuda.empty_cache()
-    return t_empty, t_small, size, (1 << 30) / (t_big * 1e-6) / 1e9
-
-
-def ablations(torch, spqt, use_graph, cpu):
-    """Section 6.3's question on this hardware, on the 70B gate shape at 50 %: what do the index
-    list's even split (Section 4.2.3) and the compaction buy?  Two activation patterns: iid
-    Laplace (kept columns spread evenly) and a clustered one (7 of 8 kept columns in the first
-    half of K), three kernels: list-balanced (spqt_gather + spqt_gemv), static column ranges
-    with in-kernel test and compaction (spqt_gemv_fused), the same without compaction.  Also the
-    list-balanced kernel with one-group passes instead of row-aligned ones (SPQT_CFG_GROUP_PASSES)."""
-    import numpy as np
-    from workloads import CONFIG_SCALE_RANGE
-    M, K, s = 28672, 8192, 0.5
-    rows = []
-    for dist in ("laplace", "laplace_clustered"):
-        w = Workload(torch, spqt, M, K, dist, CONFIG_SCALE_RANGE[5], 5, "gate", s)
-        # copy 0 against the oracle in every mode (the clustered pattern is not covered elsewhere at this size)
-        if cpu.enabled:
-            ref = cpu.gemv(w.case0, w.x_np[0:1], w.thr[0])
-            for fn in (w.step, w.gemv_group_passes, w.fused, w.fused_no_compaction):
-                w.y[0].fill_(float("nan"))
-                fn(0)
-                torch.cuda.synchronize()
-                if not cpu.close(w.y[0].cpu().numpy(), ref)[0]:
-                    print(f"bench.py: ablation parity check FAILED ({dist}, {fn.__name__})", file=sys.stderr)
-                    sys.exit(1)
-        steps = w.copies * 40
-        t = {name: time_sequence(torch, fn, w.copies, steps, w.copies, use_graph)
-             for name, fn in (("list_balanced_gemv", w.gemv_only), ("list_balanced_gemv_group_passes", w.gemv_group_passes),
-                              ("gather_plus_list_balanced_gemv", w.step),
-                              ("static_ranges_compacted", w.fused),
-                              ("static_ranges_no_compaction", w.fused_no_compaction), ("dense", w.dense_only))}
-        rows.append({"M": M, "K": K, "sparsity": s, "activations": dist,
-                     "kept_frac": round(float(np.mean(w.n_ns)) / K, 4),
-                     "us": {k: round(v, 3) for k, v in t.items()},
-                     "speedup_vs_dense": {k: round(t["dense"] / v, 3) for k, v in t.items() if k != "dense"}})
-        del w
-        torch.cuda.empty_cache()
-    return rows
-
-
-def rowmajor_baseline(torch, spqt, use_graph, cpu):
-    """Sections 6.1 and 6.3 on this hardware: the same int4 GEMV read from the ROW-MAJOR source
-    layout - dense (the row-wise baseline the zigzag dense kernel should be on par with) and with
-    the naive per-weight sparsity test (no byte of a row-major line can be skipped) - next to the
-    zigzag kernels, at 50 % on the headline and the 70B gate shape.  Copy 0 of every mode is
-    checked against the oracle."""
-    import numpy as np
-    from workloads import CONFIG_SCALE_RANGE
-    calib = Calib(torch)
-    dev = torch.device("cuda:0")
-    rows = []
-    for config, tensor, M, K in ((2, "q", 4096, 4096), (5, "gate", 28672, 8192)):
-        w = Workload(torch, spqt, M, K, "laplace", CONFIG_SCALE_RANGE[config], config, tensor, 0.5)
-        lo, hi = CONFIG_SCALE_RANGE[config]
-        # row-major copies: copy 0 is the seeded source of the packed copy 0, the others random codes
-        q = [torch.from_numpy(w.case0["q_rowmajor"]).to(dev)]
-        sc = [torch.from_numpy(np.ascontiguousarray(w.case0["scales"])).to(dev)]
-        g = torch.Generator(device=dev)
-        g.manual_seed(4242 + M)
-        for _ in range(1, w.copies):
-            q.append(torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device=dev, generator=g))
-            sc.append((torch.rand((M, K // 128), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16))
-        y = torch.zeros((w.copies, M), dtype=torch.float32, device=dev)
-
-        def rm_dense(i):
-            calib.rowmajor_gemv(q[i], sc[i], M, K, w.x[i], 0.0, 0, y[i])
-
-        def rm_skip(i):
-            calib.rowmajor_gemv(q[i], sc[i], M, K, w.x[i], w.thr[i], 1, y[i])
-
-        if cpu.enabled:
-            for fn, thr in ((rm_dense, 0.0), (rm_skip, w.thr[0])):
-                y[0].fill_(float("nan"))
-                fn(0)
-                torch.cuda.synchronize()
-                if not cpu.close(y[0].cpu().numpy(), cpu.gemv(w.case0, w.x_np[0:1], thr))[0]:
-                    print(f"bench.py: row-major baseline parity check FAILED ({fn.__name__})", file=sys.stderr)
-                    sys.exit(1)
-        steps = max(w.copies * 8, 400)
-        t = {name: time_sequence(torch, fn, w.copies, steps, w.copies, use_graph)
-             for name, fn in (("rowmajor_dense", rm_dense), ("rowmajor_naive_skip", rm_skip),
-                              ("zigzag_dense", w.dense_only), ("zigzag_static_ranges_no_compaction", w.fused_no_compaction),
-                              ("zigzag_list_balanced_gemv", w.gemv_only), ("zigzag_gather_plus_gemv", w.step))}
-        rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(float(np.mean(w.n_ns)) / K, 4),
-                     "us": {k: round(v, 3) for k, v in t.items()},
-                     "speedup_vs_rowmajor_dense": {k: round(t["rowmajor_dense"] / v, 3) for k, v in t.items() if k != "rowmajor_dense"}})
-        del w, q, sc, y
-        torch.cuda.empty_cache()
-    return rows
-
-
-def merged_gate_up_70b(torch, spqt, use_graph, cpu):
-    """Config 5's gate and up projections as ONE matrix (57344 x 8192; both consume the same x, paper
-    Section 5: they share a threshold): what one launch reaches when it has twice the bytes to amortize
-    its fixed costs over.  Copy 0 is the two seeded tensors stacked and is checked against the oracle on
-    sampled rows; the other copies are random packed bytes."""
-    import numpy as np
-    from workloads import CONFIG_SCALE_RANGE, make_case, make_x, quantile_threshold, seed_for, KIND_X
-    dev = torch.device("cuda:0")
-    K, Mh = 8192, 28672
-    M = 2 * Mh
-    gate, up = make_case(5, "gate", want_q=False), make_case(5, "up", want_q=False)
-    q = np.concatenate([gate["q_rowmajor"], up["q_rowmajor"]], axis=0)
-    sc = np.concatenate([gate["scales"], up["scales"]], axis=0)
-    del gate, up
-    pbytes = spqt.spqt_packed_bytes(M, K)
-    copies = max(2, -(-ROTATE_BYTES // pbytes))
-    T, NG = M // 256, K // 128
-    lo, hi = CONFIG_SCALE_RANGE[5]
-    packed = [torch.from_numpy(spqt.spqt_pack(q, sc)).to(dev)]
-    g = torch.Generator(device=dev)
-    g.manual_seed(9301)
-    for _ in range(1, copies):
-        buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-        s16 = (torch.rand((T * NG, 256), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
-        buf[:, :512] = s16.view(torch.uint8)
-        packed.append(buf.reshape(-1))
-    x_np = make_x(K, "laplace", seed_for(5, 0, "gate", KIND_X))
-    x = torch.from_numpy(x_np[0]).to(dev)
-    idx = torch.empty(K, dtype=torch.int32, device=dev)
-    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-    y = torch.empty(M, dtype=torch.float32, device=dev)
-    ws = spqt.new_workspace(M, K)
-    rows = []
-    sample = np.unique(np.concatenate([np.arange(0, 512), np.arange(Mh - 256, Mh + 256), np.arange(M - 512, M)]))
-    for s in (0.5, 0.7):
-        thr = quantile_threshold(x_np, s)
-        spqt.spqt_gather(x, thr, idx, cnt)
-        torch.cuda.synchronize()
-        n = int(cnt.item())
-        if cpu.enabled:
-            ref = cpu.gemv_rows({"q_rowmajor": q, "scales": sc}, x_np, thr, sample)
-            for name, call in (("list", lambda: spqt.spqt_gemv(packed[0], M, K, x, idx, cnt, y, ws)),
-                               ("fused", lambda: spqt.spqt_gemv_fused(packed[0], M, K, x, thr, y, ws))):
-                y.fill_(float("nan"))
-                call()
-                torch.cuda.synchronize()
-                if not cpu.close(y.cpu().numpy()[sample], ref)[0]:
-                    print(f"bench.py: merged gate|up parity check FAILED ({name}, s={s})", file=sys.stderr)
-                    sys.exit(1)
-        fns = {"us_gemv": lambda i: spqt.spqt_gemv(packed[i], M, K, x, idx, cnt, y, ws),
-               "us_dense": lambda i: spqt.spqt_gemv(packed[i], M, K, x, None, None, y, ws),
-               "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
-                                                 spqt.spqt_gemv(packed[i], M, K, x, idx, cnt, y, ws)),
-               "us_fused": lambda i: spqt.spqt_gemv_fused(packed[i], M, K, x, thr, y, ws)}
-        t = {k: time_sequence(torch, f, copies, 800, 200, use_graph) for k, f in fns.items()}
-        kept = kept_bytes(M, K, n)
-        rows.append({"M": M, "K": K, "sparsity": s, "kept_frac": round(n / K, 4), **{k: round(v, 3) for k, v in t.items()},
-                     "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
-                     "frac_of_8TBps": round(kept / (t["us_gemv"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "dense_GBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9, 1),
-                     "dense_frac_of_8TBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "speedup_vs_dense": round(t["us_dense"] / t["us_gemv"], 3)})
-    del packed
-    torch.cuda.empty_cache()
-    return rows
-
-
-def eight_bit_rows(torch, spqt, use_graph, cpu):
-    """The 8-bit flavour of the column-block layout (128-row block-rows, one column still one
-    128-byte run) on the headline and the 70B gate shape at 50 % and dense.  Copy 0 is quantized
-    from seeded fp32 weights by the library and checked against the NumPy oracle on sampled
-    block-rows; the other copies are random codes under valid fp16 scales."""
-    import numpy as np
-    from workloads import make_fp_weights, make_x, quantile_threshold
-    dev = torch.device("cuda:0")
-    rows = []
-    for M, K in ((4096, 4096), (28672, 8192)):
-        pbytes = spqt.spqt_cb8_packed_bytes(M, K)
-        copies = max(2, -(-ROTATE_BYTES // pbytes))
-        T, NC = M // 128, K // 128
-        W0 = make_fp_weights(M, K, 9100 + M)
-        packed = [torch.from_numpy(spqt.spqt_cb8_quantize(W0)).to(dev)]
-        g = torch.Generator(device=dev)
-        g.manual_seed(9101 + M)
-        for _ in range(1, copies):
-            buf = torch.randint(0, 256, (T * NC, spqt.CB8_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NC, 512), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
-            buf[:, :1024] = sc.view(torch.uint8)
-            packed.append(buf.reshape(-1))
-        tiles = np.unique(np.array([0, T // 2, T - 1]))
-        sample = (tiles[:, None] * 128 + np.arange(128)[None, :]).ravel()
-        W0_sample = W0[sample].copy()
-        del W0
-        x_np = make_x(K, "laplace", 9102 + M)
-        thr = quantile_threshold(x_np, 0.5)
-        x = torch.from_numpy(x_np[0]).to(dev)
-        idx = torch.empty(K, dtype=torch.int32, device=dev)
-        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-        y = torch.empty(M, dtype=torch.float32, device=dev)
-        ws = spqt.new_workspace(M, K)
-        spqt.spqt_gather(x, thr, idx, cnt)
-        torch.cuda.synchronize()
-        n = int(cnt.item())
-        if cpu.enabled:
-            y.fill_(float("nan"))
-            spqt.spqt_cb8_gemv(packed[0], M, K, x, idx, cnt, y, ws)
-            torch.cuda.synchronize()
-            if not cpu.close(y.cpu().numpy()[sample], cpu.colblock_w8(W0_sample, x_np, thr))[0]:
-                print(f"bench.py: 8-bit column-block parity check FAILED ({M}x{K})", file=sys.stderr)
-                sys.exit(1)
-        fns = {"us_gemv": lambda i: spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws),
-               "us_dense": lambda i: spqt.spqt_cb8_gemv(packed[i], M, K, x, None, None, y, ws),
-               "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
-                                                 spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws))}
-        t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
-        kept = n * (M + M // 16)
-        rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(n / K, 4), "bits_per_weight": 8.5,
-                     "kept_bytes": kept, **{k: round(v, 3) for k, v in t.items()},
-                     "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
-                     "frac_of_8TBps": round(kept / (t["us_gemv"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "dense_GBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9, 1),
-                     "speedup_vs_dense": round(t["us_dense"] / t["us_gemv"], 3)})
-        del packed
-        torch.cuda.empty_cache()
-    return rows
-
-
-def colblock_rows(torch, spqt, use_graph, cpu, full=True):
-    """The column-block variant of the layout (the paper's own grouping, Section 4.1.2: 32-row
-    blocks along a column, scales skipped with their column) on the headline and 70B shapes.
-    Copy 0 is quantized from seeded fp32 weights by the library and checked against the
-    NumPy oracle on sampled 256-row tiles; the other copies are random packed bytes."""
-    import numpy as np
-    from workloads import make_fp_weights, make_x, quantile_threshold
-    dev = torch.device("cuda:0")
-    rows = []
-    L, C = "laplace", "laplace_clustered"     # C: 7 of 8 kept columns in the first half of K
-    shapes = ((4096, 4096, ((0.5, L),)), (28672, 8192, ((0.3, L), (0.5, L), (0.7, L), (0.5, C))),
-              (8192, 28672, ((0.5, L),)))
-    for M, K, sps in (shapes if full else shapes[:1]):
-        pbytes = spqt.spqt_cb_packed_bytes(M, K)
-        copies = max(2, -(-ROTATE_BYTES // pbytes))
-        T, NC = M // 256, K // 128
-        W0 = make_fp_weights(M, K, 9000 + M)
-        packed = [torch.from_numpy(spqt.spqt_cb_quantize(W0)).to(dev)]
-        g = torch.Generator(device=dev)
-        g.manual_seed(9001 + M)
-        for _ in range(1, copies):
-            buf = torch.randint(0, 256, (T * NC, spqt.CB_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NC, 1024), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
-            buf[:, :2048] = sc.view(torch.uint8)
-            packed.append(buf.reshape(-1))
-        tiles = np.unique(np.array([0, T // 2, T - 1]))
-        sample = (tiles[:, None] * 256 + np.arange(256)[None, :]).ravel()
-        W0_sample = W0[sample].copy()
-        packed_k0 = torch.from_numpy(spqt.spqt_cbk_quantize(W0)).to(dev) if cpu.enabled else None
-        del W0
-        idx = torch.empty(K, dtype=torch.int32, device=dev)
-        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-        y = torch.empty(M, dtype=torch.float32, device=dev)
-        ws = spqt.new_workspace(M, K)
-        for s, dist in sps:
-            x_np = make_x(K, dist, 9002 + M)
-            thr = quantile_threshold(x_np, s)
-            x = torch.from_numpy(x_np[0]).to(dev)
-            spqt.spqt_gather(x, thr, idx, cnt)
-            torch.cuda.synchronize()
-            n = int(cnt.item())
-            if cpu.enabled:
-                ref = cpu.colblock(W0_sample, x_np, thr)
-                for name, call in (("list", lambda: spqt.spqt_cb_gemv(packed[0], M, K, x, idx, cnt, y, ws)),
-                                   ("fused", lambda: spqt.spqt_cb_gemv_fused(packed[0], M, K, x, thr, y, ws))):
-                    y.fill_(float("nan"))
-                    call()
-                    torch.cuda.synchronize()
-                    if not cpu.close(y.cpu().numpy()[sample], ref)[0]:
-                        print(f"bench.py: column-block parity check FAILED ({M}x{K}, {name})", file=sys.stderr)
-                        sys.exit(1)
-            fns = {"us_gemv": lambda i: spqt.spqt_cb_gemv(packed[i], M, K, x, idx, cnt, y, ws),
-                   "us_dense": lambda i: spqt.spqt_cb_gemv(packed[i], M, K, x, None, None, y, ws),
-                   "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
-                                                     spqt.spqt_cb_gemv(packed[i], M, K, x, idx, cnt, y, ws)),
-                   "us_fused": lambda i: spqt.spqt_cb_gemv_fused(packed[i], M, K, x, thr, y, ws)}
-            t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
-            kept = n * (M // 2 + M // 16)
-            rows.append({"M": M, "K": K, "sparsity": s, "activations": dist, "kept_frac": round(n / K, 4),
-                         "bits_per_weight": 4.5, "kept_bytes": kept,
-                         **{k: round(v, 3) for k, v in t.items()},
-                         "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
-                         "frac_of_8TBps": round(kept / (t["us_gemv"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                         "dense_GBps": round(pbytes / (t["us_dense"] * 1e-6) / 1e9, 1),
-                         "speedup_vs_dense": round(t["us_dense"] / t["us_gemv"], 3),
-                         "fused_speedup_vs_dense": round(t["us_dense"] / t["us_fused"], 3)})
-        if M == 28672:      # four activation rows sharing the union list (config 5's batch-4 case)
-            xb_np = make_x(K, "laplace", 9003 + M, 4)
-            thr = quantile_threshold(xb_np, 0.5)
-            xb = torch.from_numpy(xb_np).to(dev)
-            yb = torch.empty((4, M), dtype=torch.float32, device=dev)
-            wsb = spqt.new_workspace(M, K, 4)
-            spqt.spqt_gather(xb, thr, idx, cnt)
-            torch.cuda.synchronize()
-            n = int(cnt.item())
-            if cpu.enabled:
-                from_ref = []
-                spqt.spqt_cb_gemv(packed[0], M, K, xb, idx, cnt, yb, wsb)
-                torch.cuda.synchronize()
-                for b in range(4):      # the union set with each row's own values == that row with the others' dropped columns kept
-                    from_ref.append(cpu.colblock(W0_sample, np.where(np.any(~(np.abs(xb_np.astype(np.float32)) < np.float32(thr)), axis=0), xb_np[b], 0).astype(np.float16)[None, :], 0.0))
-                    if not cpu.close(yb[b].cpu().numpy()[sample], from_ref[b])[0]:
-                        print(f"bench.py: column-block batch-4 parity check FAILED (row {b})", file=sys.stderr)
-                        sys.exit(1)
-            t_s = time_sequence(torch, lambda i: spqt.spqt_cb_gemv(packed[i], M, K, xb, idx, cnt, yb, wsb), copies, max(copies * 4, 400), copies, use_graph)
-            t_d = time_sequence(torch, lambda i: spqt.spqt_cb_gemv(packed[i], M, K, xb, None, None, yb, wsb), copies, max(copies * 4, 400), copies, use_graph)
-            rows.append({"M": M, "K": K, "batch": 4, "sparsity_per_row": 0.5, "activations": L, "kept_frac": round(n / K, 4),
-                         "us_gemv": round(t_s, 3), "us_dense": round(t_d, 3), "speedup_vs_dense": round(t_d / t_s, 3)})
-        # K-quant flavour (6-bit block scales and minima under fp16 superblock scales): copy 0 quantized
-        # by the library and checked, then timed on the rotating buffers with their headers rewritten
-        # (finite superblock scales; any 6-bit fields and codes are valid)
-        x_np = make_x(K, L, 9002 + M)
-        thr = quantile_threshold(x_np, 0.5)
-        x = torch.from_numpy(x_np[0]).to(dev)
-        spqt.spqt_gather(x, thr, idx, cnt)
-        torch.cuda.synchronize()
-        n = int(cnt.item())
-        if cpu.enabled:
-            ref = cpu.colblock_k(W0_sample, x_np, thr)
-            y.fill_(float("nan"))
-            spqt.spqt_cbk_gemv(packed_k0, M, K, x, idx, cnt, y, ws)
-            torch.cuda.synchronize()
-            if not cpu.close(y.cpu().numpy()[sample], ref)[0]:
-                print(f"bench.py: K-quant column-block parity check FAILED ({M}x{K})", file=sys.stderr)
-                sys.exit(1)
-            del packed_k0
-        for buf in packed:
-            hdr = buf.view(T * NC, spqt.CB_CHUNK_BYTES)[:, :2048].view(torch.float16).view(T * NC, 128, 8)
-            hdr[:, :, 0] = 0.0005
-            hdr[:, :, 1] = 0.0004
-        t_ks = time_sequence(torch, lambda i: spqt.spqt_cbk_gemv(packed[i], M, K, x, idx, cnt, y, ws), copies, max(copies * 4, 800), copies, use_graph)
-        t_kd = time_sequence(torch, lambda i: spqt.spqt_cbk_gemv(packed[i], M, K, x, None, None, y, ws), copies, max(copies * 4, 800), copies, use_graph)
-        rows.append({"M": M, "K": K, "format": "k-quant", "sparsity": 0.5, "activations": L, "kept_frac": round(n / K, 4),
-                     "us_gemv": round(t_ks, 3), "us_dense": round(t_kd, 3), "speedup_vs_dense": round(t_kd / t_ks, 3)})
-        del packed
-        torch.cuda.empty_cache()
-    return rows
-
-
-def speedup_grid(torch, spqt, use_graph):
-    """Sparse-over-dense speed-up against sparsity on the GEMV shapes of the paper's kernel
-    micro-benchmark (Section 6.3: Llama-3-8B, Llama-2-13B and Llama-2-70B projections at 25 / 40 /
-    50 %), for both layouts; random packed bytes, iid Laplace activations, gather time not included."""
-    import numpy as np
-    from workloads import make_x, quantile_threshold
-    dev = torch.device("cuda:0")
-    shapes = [("llama-3-8b", 4096, 4096), ("llama-3-8b", 14336, 4096), ("llama-3-8b", 4096, 14336),
-              ("llama-2-13b", 5120, 5120), ("llama-2-13b", 13824, 5120), ("llama-2-13b", 5120, 13824),
-              ("llama-2-70b", 8192, 8192), ("llama-2-70b", 28672, 8192), ("llama-2-70b", 8192, 28672)]
-    rows = []
-    for model, M, K in shapes:
-        T, NC = M // 256, K // 128
-        x_np = make_x(K, "laplace", 9200 + M + K)
-        x = torch.from_numpy(x_np[0]).to(dev)
-        idx = torch.empty(K, dtype=torch.int32, device=dev)
-        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-        y = torch.empty(M, dtype=torch.float32, device=dev)
-        ws = spqt.new_workspace(M, K)
-        for layout, chunk, nscale, gemv in (("group", spqt.CHUNK_BYTES, 256, spqt.spqt_gemv),
-                                            ("colblock", spqt.CB_CHUNK_BYTES, 1024, spqt.spqt_cb_gemv)):
-            pbytes = T * NC * chunk
-            copies = max(2, -(-ROTATE_BYTES // pbytes))
-            g = torch.Generator(device=dev)
-            g.manual_seed(9201 + M + K)
-            packed = []
-            for _ in range(copies):
-                buf = torch.randint(0, 256, (T * NC, chunk), dtype=torch.uint8, device=dev, generator=g)
-                sc = (torch.rand((T * NC, nscale), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
-                buf[:, :2 * nscale] = sc.view(torch.uint8)
-                packed.append(buf.reshape(-1))
-            steps = max(copies * 4, 400)
-            t_dense = time_sequence(torch, lambda i: gemv(packed[i], M, K, x, None, None, y, ws), copies, steps, copies, use_graph)
-            row = {"model": model, "M": M, "K": K, "layout": layout, "us_dense": round(t_dense, 3), "sparse": []}
-            for sp in (0.25, 0.4, 0.5):
-                thr = quantile_threshold(x_np, sp)
-                spqt.spqt_gather(x, thr, idx, cnt)
-                torch.cuda.synchronize()
-                t_sparse = time_sequence(torch, lambda i: gemv(packed[i], M, K, x, idx, cnt, y, ws), copies, steps, copies, use_graph)
-                row["sparse"].append({"sparsity": sp, "us": round(t_sparse, 3), "speedup_vs_dense": round(t_dense / t_sparse, 3)})
-            rows.append(row)
-            del packed
-            torch.cuda.empty_cache()
-    return rows
-
-
-def dense_shape_sweep(torch, spqt, use_graph):
-    """The dense zigzag kernel on the 15 shapes of the paper's dense micro-benchmark
-    (Section 6.4: m in {2048, 4096, 8192} x k in {1024 ... 16384}); random packed bytes."""
-    dev = torch.device("cuda:0")
-    rows = []
-    for M in (2048, 4096, 8192):
-        for K in (1024, 2048, 4096, 8192, 16384):
-            pbytes = spqt.spqt_packed_bytes(M, K)
-            copies = max(2, -(-ROTATE_BYTES // pbytes))
-            g = torch.Generator(device=dev)
-            g.manual_seed(1000 * M + K)
-            T, NG = M // 256, K // 128
-            packed = []
-            for _ in range(copies):
-                buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-                sc = (torch.rand((T * NG, 256), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
-                buf[:, :512] = sc.view(torch.uint8)
-                packed.append(buf.reshape(-1))
-            x = torch.randn(K, device=dev, generator=g).to(torch.float16)
-            y = torch.empty(M, dtype=torch.float32, device=dev)
-            ws = spqt.new_workspace(M, K)
-            fn = lambda i: spqt.spqt_gemv(packed[i], M, K, x, None, None, y, ws)
-            us = time_sequence(torch, fn, copies, copies * 4, copies, use_graph)
-            rows.append({"M": M, "K": K, "us_dense": round(us, 3), "GBps": round(pbytes / (us * 1e-6) / 1e9, 1),
-                         "GFLOPS": round(2.0 * M * K / (us * 1e-6) / 1e9, 1)})
-            del packed
-            torch.cuda.empty_cache()
-    return rows
-
-
-def layer_sequence(torch, spqt, config, layers, sparsity, use_graph=True, reps=5):
-    """Decoder-layer GEMV sequence (configs 3 and 4): every projection of every layer has its own
-    independently seeded weights and a threshold calibrated offline (separate 64*K draw) for the
-    requested sparsity; activations are per input site (attention input, o input, MLP input,
-    down input).  One HIP graph holds the whole multi-layer pass.  Returns per-mode timings."""
-    import numpy as np
-    from workloads import (CONFIG_SHAPES, CONFIG_SCALE_RANGE, KIND_CALIB, KIND_X, calibrated_threshold,
-                           make_x, seed_for)
-    dev = torch.device("cuda:0")
-    shapes = CONFIG_SHAPES[config]
-    lo, hi = CONFIG_SCALE_RANGE[config]
-    site_of = {"q": "attn", "k": "attn", "v": "attn", "o": "o", "gate": "mlp", "up": "mlp", "down": "down"}
-    thr = {name: calibrated_threshold(K, dist, sparsity, seed_for(config, 0, name, KIND_CALIB))
-           for name, M, K, dist in shapes}
-    L = []          # per layer: list of (name, M, K, packed, x, thr, idx, cnt, y, site)
-    kept_bytes_total, dense_bytes_total, n_gemv = 0.0, 0.0, 0
-    ws = {}
-    for layer in range(layers):
-        xs = {}
-        items = []
-        for name, M, K, dist in shapes:
-            site = site_of[name]
-            if site not in xs:
-                xv = make_x(K, dist, seed_for(config, layer, name, KIND_X))
-                xs[site] = torch.from_numpy(xv[0]).to(dev)
-            g = torch.Generator(device=dev)
-            g.manual_seed(seed_for(config, layer, name))
-            T, NG = M // 256, K // 128
-            buf = torch.randint(0, 256, (T * NG, spqt.CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NG, 256), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
-            buf[:, :512] = sc.view(torch.uint8)
-            if (M, K) not in ws:
-                ws[(M, K)] = spqt.new_workspace(M, K)
-            idx = torch.zeros(K, dtype=torch.int32, device=dev)
-            cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-            y = torch.zeros(M, dtype=torch.float32, device=dev)
-            items.append((name, M, K, buf.reshape(-1), xs[site], thr[name], idx, cnt, y, site))
-        L.append(items)
-    # Projections that read the same activations, packed as ONE matrix: block-rows are the
-    # storage unit of the layout, so concatenating packed buffers along M is concatenating bytes.
-    # {q,k,v} and {gate,up} then share one threshold, as in the paper's customized mode (Section 5).
-    merged = []
-    for items in L:
-        groups, order = {}, []
-        for it in items:
-            if it[9] not in groups:
-                groups[it[9]] = []
-                order.append(it[9])
-            groups[it[9]].append(it)
-        mitems = []
-        for site in order:
-            g_items = groups[site]
-            Mtot = sum(it[1] for it in g_items)
-            K = g_items[0][2]
-            pk = torch.cat([it[3] for it in g_items]) if len(g_items) > 1 else g_items[0][3]
-            if (Mtot, K) not in ws:
-                ws[(Mtot, K)] = spqt.new_workspace(Mtot, K)
-            y = torch.zeros(Mtot, dtype=torch.float32, device=dev)
-            mitems.append((Mtot, K, pk, g_items[0][4], g_items[0][5], g_items[0][6], g_items[0][7], y))
-        merged.append(mitems)
-
-    # The same merged matrices in the column-block layout (random packed bytes of that format).
-    cb_merged = []
-    for li, mitems in enumerate(merged):
-        row = []
-        for mi, (Mtot, K, pk, x, t, idx, cnt, y) in enumerate(mitems):
-            g = torch.Generator(device=dev)
-            g.manual_seed(seed_for(config, li, "w") + 7000 + mi)
-            T, NC = Mtot // 256, K // 128
-            buf = torch.randint(0, 256, (T * NC, spqt.CB_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NC, 1024), device=dev, generator=g) * (hi - lo) + lo).to(torch.float16)
-            buf[:, :2048] = sc.view(torch.uint8)
-            row.append(buf.reshape(-1))
-        cb_merged.append(row)
-
-    # achieved kept counts (one eager pass)
-    for items in L:
-        for name, M, K, pk, x, t, idx, cnt, y, site in items:
-            spqt.spqt_gather(x, t, idx, cnt)
-    torch.cuda.synchronize()
-    for items in L:
-        for name, M, K, pk, x, t, idx, cnt, y, site in items:
-            kept_bytes_total += kept_bytes(M, K, int(cnt.item()))
-            dense_bytes_total += kept_bytes(M, K, K)
-            n_gemv += 1
-
-    def run(mode):
-        if mode.startswith("cb_"):
-            for mitems, cbrow in zip(merged, cb_merged):
-                for (Mtot, K, pk, x, t, idx, cnt, y), cpk in zip(mitems, cbrow):
-                    if mode == "cb_merged_fused":
-                        spqt.spqt_cb_gemv_fused(cpk, Mtot, K, x, t, y, ws[(Mtot, K)])
-                    elif mode == "cb_merged_dense":
-                        spqt.spqt_cb_gemv(cpk, Mtot, K, x, None, None, y, ws[(Mtot, K)])
-                    else:
-                        spqt.spqt_gather(x, t, idx, cnt)
-                        spqt.spqt_cb_gemv(cpk, Mtot, K, x, idx, cnt, y, ws[(Mtot, K)])
-            return
-        if mode.startswith("merged"):
-            for mitems in merged:
-                for Mtot, K, pk, x, t, idx, cnt, y in mitems:
-                    if mode == "merged_fused":
-                        spqt.spqt_gemv_fused(pk, Mtot, K, x, t, y, ws[(Mtot, K)])
-                    elif mode == "merged_dense":
-                        spqt.spqt_gemv(pk, Mtot, K, x, None, None, y, ws[(Mtot, K)])
-                    else:
-                        spqt.spqt_gather(x, t, idx, cnt)
-                        spqt.spqt_gemv(pk, Mtot, K, x, idx, cnt, y, ws[(Mtot, K)])
-            return
-        for items in L:
-            done_sites = {}
-            for name, M, K, pk, x, t, idx, cnt, y, site in items:
-                w = ws[(M, K)]
-                if mode == "dense":
-                    spqt.spqt_gemv(pk, M, K, x, None, None, y, w)
-                elif mode == "fused":
-                    spqt.spqt_gemv_fused(pk, M, K, x, t, y, w)
-                elif mode == "strict":          # one gather per projection
-                    spqt.spqt_gather(x, t, idx, cnt)
-                    spqt.spqt_gemv(pk, M, K, x, idx, cnt, y, w)
-                else:                           # "shared": one gather per input site (threshold sharing)
-                    if site not in done_sites:
-                        spqt.spqt_gather(x, t, idx, cnt)
-                        done_sites[site] = (idx, cnt)
-                    si, sc_ = done_sites[site]
-                    spqt.spqt_gemv(pk, M, K, x, si, sc_, y, w)
-
-    out = {"config": config, "layers": layers, "gemvs_per_layer": len(shapes), "sparsity_target": sparsity,
-           "packed_MB": round(dense_bytes_total / 1e6, 1), "kept_MB": round(kept_bytes_total / 1e6, 1)}
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for mode in ("strict", "shared", "fused", "merged_gather_gemv", "merged_fused", "dense", "merged_dense",
-                 "cb_merged_gather_gemv", "cb_merged_fused", "cb_merged_dense"):
-        run(mode)
-        torch.cuda.synchronize()
-        st = torch.cuda.Stream()
-        with torch.cuda.stream(st):
-            if use_graph:
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g):
-                    run(mode)
-                fn = g.replay
-            else:
-                fn = lambda: run(mode)
-            fn()
-            torch.cuda.synchronize()
-            start.record()
-            for _ in range(reps):
-                fn()
-            stop.record()
-            torch.cuda.synchronize()
-        us_pass = start.elapsed_time(stop) * 1e3 / reps
-        nbytes = dense_bytes_total if mode.endswith("dense") else kept_bytes_total
-        if mode.startswith("cb_"):
-            nbytes *= 0.5625 / 0.515625          # 4.5 instead of 4.125 bits per weight
-        out[mode] = {"us_per_layer": round(us_pass / layers, 2), "us_per_gemv": round(us_pass / n_gemv, 3),
-                     "GBps": round(nbytes / (us_pass * 1e-6) / 1e9, 1)}
-    out["speedup_strict_vs_dense"] = round(out["dense"]["us_per_layer"] / out["strict"]["us_per_layer"], 3)
-    out["speedup_fused_vs_dense"] = round(out["dense"]["us_per_layer"] / out["fused"]["us_per_layer"], 3)
-    out["speedup_merged_fused_vs_merged_dense"] = round(out["merged_dense"]["us_per_layer"] / out["merged_fused"]["us_per_layer"], 3)
-    out["speedup_cb_merged_fused_vs_cb_merged_dense"] = round(out["cb_merged_dense"]["us_per_layer"] / out["cb_merged_fused"]["us_per_layer"], 3)
-    out["launches_per_layer"] = {"strict": 2 * len(shapes), "shared": len(shapes) + len(merged[0]), "fused": len(shapes),
-                                 "merged_gather_gemv": 2 * len(merged[0]), "merged_fused": len(merged[0]), "dense": len(shapes), "merged_dense": len(merged[0])}
-    return out
+def measured_traffic(kernel, M, K, sparsity):
+    """HBM bytes per launch of `kernel` on this workload as the hardware counters saw them, from the table
+    the profile summarizer keeps under profiles/ (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled
+    by what the same counter reads for a plain copy of known size); None when the table has no such row."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) >= 5 and not line.startswith("#") and f[0] == kernel and (int(f[1]), int(f[2])) == (M, K) \
+                    and abs(float(f[3]) - sparsity) < 1e-9:
+                return int(float(f[4]))
+    except OSError:
+        pass
+    return None
 
 
 class CpuBaseline:
@@ -907,113 +130,67 @@ class CpuBaseline:
         err = np.abs(np.asarray(got, dtype=np.float64) - ref)
         return bool(np.all(err <= 1e-2 + 2e-3 * np.abs(ref))), float(err.max())
 
-    def time_gemv(self, case, x_np, thr, budget_s=12.0):
-        """Repeated oracle GEMVs for about budget_s: (us per GEMV, repetitions, threads used)."""
+    def time_gemv(self, case, x_np, thr, threads, runs=5):
+        """Median over `runs` oracle GEMVs (after one warm-up) on `threads` threads (0 = all the host's):
+        (median us per GEMV, threads used)."""
         import oracle
+        all_threads = oracle.threads()
+        oracle.set_threads(threads or all_threads)
+        used = oracle.threads()
         oracle.gemv(case["q_rowmajor"], case["scales"], x_np, thr)       # warm
-        t0 = time.perf_counter()
-        reps = 0
-        while True:
+        times = []
+        for _ in range(runs):
+            t0 = time.perf_counter()
             oracle.gemv(case["q_rowmajor"], case["scales"], x_np, thr)
-            reps += 1
-            dt = time.perf_counter() - t0
-            if dt >= budget_s or reps >= 2000:
-                break
-        return dt / reps * 1e6, reps, oracle.threads()
+            times.append(time.perf_counter() - t0)
+        oracle.set_threads(all_threads)
+        times.sort()
+        return times[len(times) // 2] * 1e6, used
 
 
-def pmc_pass_large(torch, spqt, which):
-    """Hardware-counter pass on the 70B gate shape (28672 x 8192, 50 %): 8 plain copies of 64 MiB
-    for counter scaling, then the sparse, dense and one-launch kernels once per weight copy."""
-    import numpy as np
-    from workloads import CONFIG_SCALE_RANGE, make_x, quantile_threshold
-    M, K, s = 28672, 8192, 0.5
-    cal = Calib(torch)
-    dev = torch.device("cuda:0")
-    a = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 256)
-    b = torch.empty_like(a)
-    for _ in range(8):
-        cal.copy(b, a, 64 << 20)
-    if which == "gate70b":
-        wl = Workload(torch, spqt, M, K, "laplace", CONFIG_SCALE_RANGE[5], 5, "gate", s)
-        for fn in (wl.gemv_only, wl.gemv_group_passes, wl.dense_only, wl.fused):
-            for i in range(wl.copies):
-                fn(i)
-        kept, dense, copies = wl.mean_kept_bytes, wl.dense_bytes, wl.copies
-    elif which == "gate70b_w8":
-        pbytes = spqt.spqt_cb8_packed_bytes(M, K)
-        copies = max(2, -(-ROTATE_BYTES // pbytes))
-        T, NC = M // 128, K // 128
-        g = torch.Generator(device=dev)
-        g.manual_seed(9201)
-        packed = []
-        for _ in range(copies):
-            buf = torch.randint(0, 256, (T * NC, spqt.CB8_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NC, 512), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
-            buf[:, :1024] = sc.view(torch.uint8)
-            packed.append(buf.reshape(-1))
-        x_np = make_x(K, "laplace", 9202)
-        thr = quantile_threshold(x_np, s)
-        x = torch.from_numpy(x_np[0]).to(dev)
-        idx = torch.empty(K, dtype=torch.int32, device=dev)
-        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-        y = torch.empty(M, dtype=torch.float32, device=dev)
-        ws = spqt.new_workspace(M, K)
-        spqt.spqt_gather(x, thr, idx, cnt)
-        torch.cuda.synchronize()
-        for i in range(copies):
-            spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws)
-        for i in range(copies):
-            spqt.spqt_cb8_gemv(packed[i], M, K, x, None, None, y, ws)
-        kept, dense = int(cnt.item()) * (M + M // 16), pbytes
-    else:
-        pbytes = spqt.spqt_cb_packed_bytes(M, K)
-        copies = max(2, -(-ROTATE_BYTES // pbytes))
-        T, NC = M // 256, K // 128
-        g = torch.Generator(device=dev)
-        g.manual_seed(9101)
-        packed = []
-        for _ in range(copies):
-            buf = torch.randint(0, 256, (T * NC, spqt.CB_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NC, 1024), device=dev, generator=g) * 0.015 + 0.005).to(torch.float16)
-            buf[:, :2048] = sc.view(torch.uint8)
-            packed.append(buf.reshape(-1))
-        x_np = make_x(K, "laplace", 9102)
-        thr = quantile_threshold(x_np, s)
-        x = torch.from_numpy(x_np[0]).to(dev)
-        idx = torch.empty(K, dtype=torch.int32, device=dev)
-        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
-        y = torch.empty(M, dtype=torch.float32, device=dev)
-        ws = spqt.new_workspace(M, K)
-        spqt.spqt_gather(x, thr, idx, cnt)
-        torch.cuda.synchronize()
-        for i in range(copies):
-            spqt.spqt_cb_gemv(packed[i], M, K, x, idx, cnt, y, ws)
-        for i in range(copies):
-            spqt.spqt_cb_gemv(packed[i], M, K, x, None, None, y, ws)
-        for i in range(copies):
-            spqt.spqt_cb_gemv_fused(packed[i], M, K, x, thr, y, ws)
-        kept, dense = int(cnt.item()) * (M // 2 + M // 16), pbytes
-    torch.cuda.synchronize()
-    print(json.dumps({"pmc_pass": True, "workload": which, "copy_bytes": 64 << 20, "launches_per_kernel": copies,
-                      "kept_bytes_per_launch": kept, "dense_bytes_per_launch": dense, "y_bytes_per_launch": 4 * M}))
+def sweep_row(torch, spqt, np, config, tensor, m, k, dist, s, batch, K_steps, use_graph, reuse=None):
+    """One row of the sweep: GEMV only, dense, gather + GEMV and the one-launch kernel on one shape and sparsity."""
+    from workloads import CONFIG_SCALE_RANGE
+    w = reuse or Workload(torch, spqt, m, k, dist, CONFIG_SCALE_RANGE[config], config, tensor, s, batch=batch,
+                          min_copies=8 if config == 5 else 2)
+    steps = max(w.copies * 4, min(K_steps, 1600))
+    t_g = time_sequence(torch, w.gemv_only, w.copies, steps, w.copies, use_graph)
+    t_d = time_sequence(torch, w.dense_only, w.copies, steps, w.copies, use_graph)
+    t_s = time_sequence(torch, w.step, w.copies, steps, w.copies, use_graph)
+    t_f = time_sequence(torch, w.fused if batch == 1 else w.fused_rows, w.copies, steps, w.copies, use_graph)
+    t_r = time_sequence(torch, w.step_own_sets, w.copies, steps, w.copies, use_graph) if batch > 1 else None
+    t_fo = time_sequence(torch, w.fused_rows_own_sets, w.copies, steps, w.copies, use_graph) if batch > 1 else None
+    gb = w.mean_kept_bytes / (t_g * 1e-6) / 1e9
+    return {"config": config, "tensor": tensor, "M": m, "K": k, "batch": batch, "sparsity_per_row": s,
+            "kept_frac": round(float(np.mean(w.n_ns)) / k, 4),
+            "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3),
+            "us_fused": None if t_f is None else round(t_f, 3),
+            "us_gather_rows_plus_gemv": None if t_r is None else round(t_r, 3),
+            "us_fused_own_sets": None if t_fo is None else round(t_fo, 3),
+            "GBps_kept": round(gb, 1), "frac_of_8TBps": round(gb / HBM_PEAK_GBPS, 4),
+            "dense_GBps": round(w.dense_bytes / (t_d * 1e-6) / 1e9, 1),
+            "speedup_vs_dense": round(t_d / t_g, 3), "fused_speedup_vs_dense": None if t_f is None else round(t_d / t_f, 3)}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=6400)
-    ap.add_argument("--warmup", type=int, default=640)
+    ap.add_argument("--steps", type=int, default=1600)
+    ap.add_argument("--warmup", type=int, default=160)
     ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
     ap.add_argument("--no-sweep", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
-    ap.add_argument("--full", action="store_true", help="also sweep the MLP / 70B shapes")
+    ap.add_argument("--full", action="store_true", help="also the side studies (bench_studies.py)")
+    ap.add_argument("--trace-pass", action="store_true",
+                    help="for rocprofv3 --kernel-trace: only the headline workload's four graphs (GEMV only, dense, "
+                         "gather + GEMV, one launch), replayed exactly as the benchmark times them; prints their "
+                         "HIP-event times")
     ap.add_argument("--pmc-pass", action="store_true",
-                    help="for hardware-counter runs: launch only a 64 MiB calibration copy (x8) and the "
-                         "headline sparse GEMV once per weight copy, eagerly, and exit")
-    ap.add_argument("--pmc-workload", choices=["headline", "gate70b", "gate70b_colblock", "gate70b_w8"], default="headline",
-                    help="with --pmc-pass: which sparse GEMV to launch (4096x4096 group layout, 28672x8192 group "
-                         "layout, 28672x8192 column-block layout), all at 50 %%")
+                    help="for hardware-counter runs: launch only a 64 MiB calibration copy (x8) and the kernels "
+                         "of --pmc-workload once per weight copy, eagerly, and exit")
+    ap.add_argument("--pmc-workload", choices=["gate70b", "q4096", "gate70b_colblock", "gate70b_w8"], default="gate70b",
+                    help="with --pmc-pass: 28672x8192 group layout (the headline), 4096x4096 group layout, "
+                         "28672x8192 column-block layout, 28672x8192 8-bit column-block layout, all at 50 %%")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU kernel path; run with --gpus 1 "
@@ -1030,45 +207,48 @@ def main():
     use_graph = not args.eager
     K_steps, W = args.steps, args.warmup
 
-    if args.pmc_pass and args.pmc_workload != "headline":
-        pmc_pass_large(torch, spqt, args.pmc_workload)
+    if args.pmc_pass:
+        import bench_studies
+        if args.pmc_workload == "q4096":
+            bench_studies.pmc_pass_small(torch, spqt)
+        else:
+            bench_studies.pmc_pass_large(torch, spqt, args.pmc_workload)
         return
 
-    # ---------------- headline: config 2, 4096 x 4096, 50 % -------------------------------
-    M, K = 4096, 4096
-    wl = Workload(torch, spqt, M, K, "laplace", CONFIG_SCALE_RANGE[2], 2, "q", 0.5)
-    cpu = CpuBaseline(enabled=not args.no_cpu and not args.pmc_pass)
+    # ---------------- headline: config 5 gate, 28672 x 8192, 50 % --------------------------
+    H = HEADLINE
+    M, K = H["M"], H["K"]
+    wl = Workload(torch, spqt, M, K, H["dist"], CONFIG_SCALE_RANGE[H["config"]], H["config"], H["tensor"], H["sparsity"],
+                  min_copies=8)
+    cpu = CpuBaseline(enabled=not args.no_cpu and not args.trace_pass)
     ok, max_err = wl.check_copy0(cpu)
     if not ok:
         print(f"bench.py: parity check against the oracle FAILED (max err {max_err})", file=sys.stderr)
         sys.exit(1)
-    if args.pmc_pass:
-        cal = Calib(torch)
-        a = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0").random_(0, 256)
-        b = torch.empty_like(a)
-        for _ in range(8):
-            cal.copy(b, a, 64 << 20)
-        for i in range(wl.copies):
-            wl.gemv_only(i)
-        torch.cuda.synchronize()
-        print(json.dumps({"pmc_pass": True, "copy_bytes": 64 << 20, "gemv_launches": wl.copies,
-                          "kept_bytes_per_launch": wl.mean_kept_bytes, "y_bytes_per_launch": 4 * M}))
-        return
+    if cpu.enabled:     # the one-launch kernels too
+        ref = cpu.gemv(wl.case0, wl.x_np[0:1], wl.thr[0])
+        for fn in (wl.fused, wl.fused_even_shares, wl.dense_only):
+            wl.y[0].fill_(float("nan"))
+            fn(0)
+            torch.cuda.synchronize()
+            want = ref if fn is not wl.dense_only else cpu.gemv(wl.case0, wl.x_np[0:1], 0.0)
+            if not cpu.close(wl.y[0].cpu().numpy(), want)[0]:
+                print(f"bench.py: parity check of {fn.__name__} FAILED", file=sys.stderr)
+                sys.exit(1)
     us_step = time_sequence(torch, wl.step, wl.copies, K_steps, W, use_graph, exact_warmup=True)
-    us_gemv = time_sequence(torch, wl.gemv_only, wl.copies, K_steps, W, use_graph)
-    us_gather = time_sequence(torch, wl.gather_only, wl.copies, K_steps, W, use_graph)
-    us_dense = time_sequence(torch, wl.dense_only, wl.copies, K_steps, W, use_graph)
-    # plain stream launches instead of graph replay, for context (only with --full: the default run then
-    # holds graph-replayed launches only, which is what the committed kernel-trace summary averages)
-    us_step_eager = time_sequence(torch, wl.step, wl.copies, min(K_steps, 2000), min(W, 200), False) if args.full else None
-    # one-launch variant (threshold + compaction inside the GEMV kernel); checked against the oracle too
-    if cpu.enabled:
-        wl.fused(0)
-        torch.cuda.synchronize()
-        if not cpu.close(wl.y[0].cpu().numpy(), cpu.gemv(wl.case0, wl.x_np[0:1], wl.thr[0]))[0]:
-            print("bench.py: fused path parity check FAILED", file=sys.stderr)
-            sys.exit(1)
-    us_fused = time_sequence(torch, wl.fused, wl.copies, K_steps, W, use_graph)
+    side_steps = max(K_steps, 1600)
+    us_gemv = time_sequence(torch, wl.gemv_only, wl.copies, side_steps, W, use_graph)
+    us_dense = time_sequence(torch, wl.dense_only, wl.copies, side_steps, W, use_graph)
+    us_fused = time_sequence(torch, wl.fused, wl.copies, side_steps, W, use_graph)
+    if args.trace_pass:
+        print(json.dumps({"trace_pass": True, "M": M, "K": K, "sparsity": H["sparsity"], "copies": wl.copies,
+                          "kept_bytes_per_launch": wl.mean_kept_bytes, "dense_bytes_per_launch": wl.dense_bytes,
+                          "events_us": {"gather_plus_gemv": round(us_step, 3), "spqt_gemv_list_kernel": round(us_gemv, 3),
+                                        "dense": round(us_dense, 3), "one_launch_static_ranges": round(us_fused, 3)}}))
+        return
+    us_gather = time_sequence(torch, wl.gather_only, wl.copies, side_steps, W, use_graph)
+    us_even = time_sequence(torch, wl.fused_even_shares, wl.copies, side_steps, W, use_graph)
+    us_step_eager = time_sequence(torch, wl.step, wl.copies, min(K_steps, 800), min(W, 200), False) if args.full else None
 
     achieved = wl.mean_kept_bytes / (us_gemv * 1e-6) / 1e9
     out = {
@@ -1082,22 +262,27 @@ def main():
         "vs_baseline": None,
         "dtype": "int4 weights x fp16 activations, fp32 accumulate",
         "data": "synthetic",
-        "config": {"workload": "configs[1]: 4096x4096 int4 group-128, x~Laplace(0,1) fp16, threshold=50% quantile, batch 1",
-                   "M": M, "K": K, "sparsity": 0.5, "copies_rotated": wl.copies,
+        "config": {"workload": "configs[4] gate: 28672x8192 int4 group-128 (70B MLP gate/up), scales fp16 U(0.003,0.015), "
+                               "x~Laplace(0,1) fp16, threshold=50% quantile, batch 1 (the largest single-GPU configuration)",
+                   "M": M, "K": K, "sparsity": H["sparsity"], "copies_rotated": wl.copies,
                    "rotated_MB": round(wl.copies * spqt.spqt_packed_bytes(M, K) / 1e6, 1),
                    "launch": "hipgraph replay" if use_graph else "stream launches",
+                   "step": "spqt_gather + spqt_gemv (two launches, index list in HBM)",
                    "mean_n_ns": float(np.mean(wl.n_ns))},
         "effective_GBps_kept_bytes": round(wl.mean_kept_bytes / (us_step * 1e-6) / 1e9, 1),
         "us_gemv_only": round(us_gemv, 3), "us_gather_only": round(us_gather, 3),
         "us_dense_gemv": round(us_dense, 3), "speedup_vs_dense": round(us_dense / us_gemv, 3),
+        "ideal_speedup_vs_dense": round(wl.dense_bytes / wl.mean_kept_bytes, 3),
         "us_step_stream_launches": None if us_step_eager is None else round(us_step_eager, 3),
-        "us_fused_step": round(us_fused, 3),
-        "fused_effective_GBps_kept_bytes": round(wl.mean_kept_bytes / (us_fused * 1e-6) / 1e9, 1),
+        "us_one_launch_step": round(us_fused, 3),
+        "one_launch_effective_GBps_kept_bytes": round(wl.mean_kept_bytes / (us_fused * 1e-6) / 1e9, 1),
+        "one_launch_speedup_vs_dense": round(us_dense / us_fused, 3),
+        "us_one_launch_even_shares_step": round(us_even, 3),
         "oracle_max_abs_err": max_err,
         "roofline": {"bound": "hbm", "kernel": "spqt_gemv_list_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "bytes_per_launch": wl.mean_kept_bytes, "us_per_launch": round(us_gemv, 3),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((M, K, 0.5))},
+                     "traffic": measured_traffic("spqt_gemv_list_kernel", M, K, H["sparsity"])},
     }
 
     # ---------------- context: what trivial kernels reach on this machine ----------------------
@@ -1108,76 +293,67 @@ def main():
                       "note": "plain streaming read of the same byte count, cold, same graph-replay timing: the practical floor for one launch"}
 
     # ---------------- sweeps ---------------------------------------------------------------
-    sweep = []
     if not args.no_sweep:
-        shapes = [(2, "q", 4096, 4096, "laplace", [0.0, 0.25, 0.4, 0.65], 1)]
-        shapes.append((5, "gate", 28672, 8192, "laplace", [0.5], 1))
+        rows = [(5, "down", 8192, 28672, "laplace", [0.5], 1),
+                (2, "q", 4096, 4096, "laplace", [0.0, 0.25, 0.4, 0.5, 0.65], 1)]
         if args.full:
-            shapes += [(3, "gate", 11008, 4096, "laplace", [0.4, 0.5], 1),
-                       (3, "down", 4096, 11008, "silu_product", [0.4, 0.5], 1),
-                       (4, "k", 1024, 4096, "laplace", [0.5], 1),
-                       (4, "gate", 14336, 4096, "laplace", [0.5], 1),
-                       (4, "down", 4096, 14336, "laplace", [0.5], 1),
-                       (5, "gate", 28672, 8192, "laplace", [0.3, 0.7], 1),
-                       (5, "down", 8192, 28672, "laplace", [0.3, 0.5, 0.7], 1),
-                       (5, "gate", 28672, 8192, "laplace", [0.3, 0.5, 0.7], 4),
-                       (5, "down", 8192, 28672, "laplace", [0.5], 4),
-                       (2, "q", 4096, 4096, "laplace", [0.5], 4)]
-        for config, tensor, m, k, dist, sps, batch in shapes:
+            rows += [(3, "gate", 11008, 4096, "laplace", [0.4, 0.5], 1),
+                     (3, "down", 4096, 11008, "silu_product", [0.4, 0.5], 1),
+                     (4, "k", 1024, 4096, "laplace", [0.5], 1),
+                     (4, "gate", 14336, 4096, "laplace", [0.5], 1),
+                     (4, "down", 4096, 14336, "laplace", [0.5], 1),
+                     (5, "gate", 28672, 8192, "laplace", [0.3, 0.7], 1),
+                     (5, "down", 8192, 28672, "laplace", [0.3, 0.7], 1),
+                     (5, "gate", 28672, 8192, "laplace", [0.3, 0.5, 0.7], 4),
+                     (5, "down", 8192, 28672, "laplace", [0.5], 4),
+                     (2, "q", 4096, 4096, "laplace", [0.5], 4)]
+        sweep = [sweep_row(torch, spqt, np, H["config"], H["tensor"], M, K, H["dist"], H["sparsity"], 1, K_steps, use_graph, reuse=wl)]
+        del wl.packed[1:]           # the headline's rotated copies are no longer needed
+        torch.cuda.empty_cache()
+        for config, tensor, m, k, dist, sps, batch in rows:
             for s in sps:
-                w = wl if (m, k, s, batch) == (M, K, 0.5, 1) else Workload(torch, spqt, m, k, dist, CONFIG_SCALE_RANGE[config], config, tensor, s, batch=batch)
-                steps = max(w.copies * 4, min(K_steps, 1600))
-                t_g = time_sequence(torch, w.gemv_only, w.copies, steps, w.copies, use_graph)
-                t_d = time_sequence(torch, w.dense_only, w.copies, steps, w.copies, use_graph)
-                t_s = time_sequence(torch, w.step, w.copies, steps, w.copies, use_graph)
-                t_f = time_sequence(torch, w.fused if batch == 1 else w.fused_rows, w.copies, steps, w.copies, use_graph)
-                t_r = time_sequence(torch, w.step_own_sets, w.copies, steps, w.copies, use_graph) if batch > 1 else None
-                t_fo = time_sequence(torch, w.fused_rows_own_sets, w.copies, steps, w.copies, use_graph) if batch > 1 else None
-                gb = w.mean_kept_bytes / (t_g * 1e-6) / 1e9
-                sweep.append({"config": config, "tensor": tensor, "M": m, "K": k, "batch": batch, "sparsity_per_row": s,
-                              "kept_frac": round(float(np.mean(w.n_ns)) / k, 4),
-                              "us_gemv": round(t_g, 3), "us_dense": round(t_d, 3), "us_gather_plus_gemv": round(t_s, 3), "us_fused": None if t_f is None else round(t_f, 3),
-                              "us_gather_rows_plus_gemv": None if t_r is None else round(t_r, 3),
-                              "us_fused_own_sets": None if t_fo is None else round(t_fo, 3),
-                              "GBps_kept": round(gb, 1), "frac_of_8TBps": round(gb / HBM_PEAK_GBPS, 4),
-                              "dense_GBps": round(w.dense_bytes / (t_d * 1e-6) / 1e9, 1),
-                              "speedup_vs_dense": round(t_d / t_g, 3)})
-                del w
+                sweep.append(sweep_row(torch, spqt, np, config, tensor, m, k, dist, s, batch, K_steps, use_graph))
                 torch.cuda.empty_cache()
         out["sweep"] = sweep
-        if not args.full:       # the paper's own grouping on the headline shape (all shapes with --full)
-            out["colblock_layout"] = colblock_rows(torch, spqt, use_graph, cpu, full=False)
+        # decoder-layer GEMV sequences with spqt_gather time included: Llama-3-8B full layer over 32 rotated
+        # layers (configuration 4), Llama-2-7B MLP over 16 (configuration 3), both at 50 %
+        seq_modes = ("strict", "shared", "fused", "merged_gather_gemv", "merged_fused", "dense", "merged_dense")
+        out["layer_sequences"] = [layer_sequence(torch, spqt, 4, 32, 0.5, use_graph, modes=None if args.full else seq_modes),
+                                  layer_sequence(torch, spqt, 3, 16, 0.5, use_graph, modes=None if args.full else seq_modes)]
         if args.full:
-            # decoder-layer sequences: Llama-2-7B MLP over 16 layers (config 3), Llama-3-8B full layer
-            # over 32 layers (config 4); spqt_gather time included
-            out["colblock_layout"] = colblock_rows(torch, spqt, use_graph, cpu)
-            out["ablations"] = ablations(torch, spqt, use_graph, cpu)
+            import bench_studies as st
+            out["layer_sequences"].append(layer_sequence(torch, spqt, 3, 16, 0.4, use_graph))
+            out["colblock_layout"] = st.colblock_rows(torch, spqt, use_graph, cpu)
+            out["ablations"] = st.ablations(torch, spqt, use_graph, cpu)
             if cpu.enabled:
                 out["quantization_error"] = cpu.quantization_error()
-            out["rowmajor_baseline"] = rowmajor_baseline(torch, spqt, use_graph, cpu)
-            out["eight_bit_layout"] = eight_bit_rows(torch, spqt, use_graph, cpu)
-            out["merged_gate_up_70b"] = merged_gate_up_70b(torch, spqt, use_graph, cpu)
-            out["dense_shape_sweep"] = dense_shape_sweep(torch, spqt, use_graph)
-            out["speedup_grid"] = speedup_grid(torch, spqt, use_graph)
-            out["layer_sequences"] = [layer_sequence(torch, spqt, 3, 16, 0.4, use_graph),
-                                      layer_sequence(torch, spqt, 3, 16, 0.5, use_graph),
-                                      layer_sequence(torch, spqt, 4, 32, 0.5, use_graph)]
+            out["rowmajor_baseline"] = st.rowmajor_baseline(torch, spqt, use_graph, cpu)
+            out["eight_bit_layout"] = st.eight_bit_rows(torch, spqt, use_graph, cpu)
+            out["merged_gate_up_70b"] = st.merged_gate_up_70b(torch, spqt, use_graph, cpu)
+            out["dense_shape_sweep"] = st.dense_shape_sweep(torch, spqt, use_graph)
+            out["speedup_grid"] = st.speedup_grid(torch, spqt, use_graph)
 
-    # ---------------- CPU oracle baseline --------------------------------------------------
+    # ---------------- CPU oracle baseline on the headline workload -------------------------
     if cpu.enabled:
-        us_cpu, reps, cores = cpu.time_gemv(wl.case0, wl.x_np[0:1], wl.thr[0])
-        out["cpu_baseline"] = {"value": round(us_cpu, 1), "unit": "us/GEMV", "cores": cores, "kind": "oracle",
-                               "sample": f"{reps} repeated oracle GEMVs (mask + dequantize + dot, fp64) on copy 0 of the same 4096x4096 50% workload"}
+        us_all, cores = cpu.time_gemv(wl.case0, wl.x_np[0:1], wl.thr[0], threads=0, runs=7)
+        us_one, _ = cpu.time_gemv(wl.case0, wl.x_np[0:1], wl.thr[0], threads=1, runs=5)
+        rm_bytes = M * K // 2 + M * (K // 128) * 2
+        out["cpu_baseline"] = {"value": round(us_all, 1), "unit": "us/GEMV", "cores": cores, "kind": "oracle",
+                               "sample": f"median of 7 oracle GEMVs (mask + dequantize the row-major row + dot, fp64) on copy 0 of "
+                                         f"the same {M}x{K} 50% workload, all host threads; single_thread_us is the median of 5 on one thread",
+                               "single_thread_us": round(us_one, 1),
+                               "GBps_kept_bytes": round(wl.mean_kept_bytes / (us_all * 1e-6) / 1e9, 2),
+                               "GBps_rowmajor_bytes_read": round(rm_bytes / (us_all * 1e-6) / 1e9, 2)}
         if args.full:
-            # the same oracle on one tensor of each larger configuration (about 3 s each)
             from workloads import make_case, quantile_threshold
             others = []
-            for config, tensor in ((3, "gate"), (4, "gate"), (5, "gate")):
+            for config, tensor in ((2, "q"), (3, "gate"), (4, "gate"), (5, "down")):
                 case = make_case(config, tensor, want_q=False)
                 thr = quantile_threshold(case["x"], 0.5)
-                us, reps, cores = cpu.time_gemv(case, case["x"], thr, budget_s=3.0)
+                us, cores = cpu.time_gemv(case, case["x"], thr, threads=0, runs=5)
+                us1, _ = cpu.time_gemv(case, case["x"], thr, threads=1, runs=5)
                 others.append({"config": config, "tensor": tensor, "M": case["M"], "K": case["K"], "sparsity": 0.5,
-                               "us_per_gemv": round(us, 1), "repetitions": reps, "cores": cores})
+                               "us_per_gemv": round(us, 1), "single_thread_us": round(us1, 1), "cores": cores})
                 del case
             out["cpu_baseline_other_shapes"] = others
     print(json.dumps(out))

@@ -147,6 +147,17 @@ typedef struct {
  * Skipping then saves memory traffic but no issue slots.  Same results as the default. */
 #define SPQT_CFG_NO_COMPACTION 1
 
+/* spqt_gemv_fused only - every wavefront of a block-row gets an EVEN share of the kept columns (Section
+ * 4.2.3: about n_ns / (n1 * n2) each, however the kept columns are spread) instead of an equal column
+ * range: every workgroup first counts the kept columns of x per 512-column stretch, which gives n_ns and
+ * the column at which each share begins, and each wavefront then compacts the stretches of its share
+ * into a small list in LDS as it goes.  For one launch shape the arithmetic is that of spqt_gather
+ * followed by spqt_gemv, in the same order: the same y bit for bit.  The counting makes the kernel's
+ * start about a microsecond longer, which pays when the kept columns are clustered (static ranges
+ * then starve some wavefronts) and not when they are spread evenly.  Needs K <= 32768 and x_dev
+ * 16-byte aligned (else SPQT_EINVAL); not combinable with SPQT_CFG_NO_COMPACTION. */
+#define SPQT_CFG_EVEN_SHARES 16
+
 /* y_dev is IEEE fp16 [batch][M] instead of fp32: the fp32 result rounded to nearest even at the
  * final store (2-byte aligned).  Accumulation and the exchange of partial sums stay fp32. */
 #define SPQT_CFG_Y_FP16 4
@@ -165,8 +176,9 @@ typedef struct {
  * on a block-row).
  *   packed_dev     device copy of spqt_pack's output, 128-byte aligned (else SPQT_EALIGN).
  *   x_dev          fp16[batch][K].
- *   idx_dev        int32 kept-column list from spqt_gather (ascending), or NULL for the
- *                  dense kernel, which visits every column and reads neither idx nor count.
+ *   idx_dev        int32 kept-column list from spqt_gather (distinct columns, ascending), or NULL for
+ *                  the dense kernel, which visits every column and reads neither idx nor count.  With one
+ *                  activation row a list of n_ns == K entries is taken to be 0..K-1 without being read.
  *   count_dev      int32[1] n_ns on the device (ignored when idx_dev == NULL).
  *   y_dev          fp32[batch][M], fully overwritten (zeros when n_ns == 0).
  *   workspace_dev  >= spqt_workspace_bytes(M, K, batch) bytes, prepared by
@@ -212,10 +224,12 @@ int spqt_gemv_static(const void *packed_dev, int64_t M, int64_t K, int group, co
  * is written and n_ns is never materialised.  Same y as spqt_gather followed by spqt_gemv (the
  * summation order differs, so the last bits may).  Because the index list does not exist, the
  * work of a block-row is split into equal COLUMN ranges instead of equal shares of the list
- * (Section 4.2.3): balanced when the kept columns are spread evenly, as with iid activations.
- * This is the combination the paper's threshold sharing aims at (Section 5: fewer index
- * collections per layer), taken to one collection per GEMV at no extra launch.
- * Arguments as for spqt_gemv_ex; cfg may be NULL. */
+ * (Section 4.2.3): balanced when the kept columns are spread evenly, as with iid activations;
+ * SPQT_CFG_EVEN_SHARES selects the kernel that splits the kept columns evenly instead.
+ * This is the combination the paper's threshold sharing aims at (Section 5: fewer index collections
+ * per layer), taken to one collection per GEMV at no extra launch.
+ * Arguments as for spqt_gemv_ex; cfg may be NULL; cfg->flags may hold SPQT_CFG_EVEN_SHARES,
+ * SPQT_CFG_NO_COMPACTION, SPQT_CFG_Y_FP16. */
 int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, const void *x_dev,
                     float threshold, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                     void *stream, const spqt_launch_cfg *cfg);

@@ -65,6 +65,8 @@ def _load():
         lib.spqt_oracle_unpack_g.argtypes = [p, c.c_int64, c.c_int64, c.c_int, p, p]
         lib.spqt_oracle_threads.restype = c.c_int
         lib.spqt_oracle_threads.argtypes = []
+        lib.spqt_oracle_set_threads.restype = None
+        lib.spqt_oracle_set_threads.argtypes = [c.c_int]
         _lib = lib
     return _lib
 
@@ -188,3 +190,8 @@ def unpack(packed: np.ndarray, M: int, K: int, group: int = 128):
 
 def threads() -> int:
     return int(_load().spqt_oracle_threads())
+
+
+def set_threads(n: int) -> None:
+    """Threads the row loops use from now on (the results do not depend on it)."""
+    _load().spqt_oracle_set_threads(int(n))

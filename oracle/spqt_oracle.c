@@ -292,3 +292,14 @@ int spqt_oracle_threads(void)
     return 1;
 #endif
 }
+
+/* How many threads the row loops may use from now on (timing legs: one thread, then all); no arithmetic
+ * depends on it - every output row is computed by one thread in the same order either way. */
+void spqt_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

@@ -23,6 +23,7 @@ MAX_SPLITS = 64
 CFG_NO_COMPACTION = 1
 CFG_Y_FP16 = 4
 CFG_GROUP_PASSES = 8
+CFG_EVEN_SHARES = 16
 
 EXPORTS = [
     "spqt_status_str", "spqt_packed_bytes", "spqt_workspace_bytes", "spqt_workspace_init",

@@ -15,7 +15,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspqt.so")
-SOURCES = ["pack.cpp", "quant_cb.cpp", "gather.hip", "gemv.hip", "gemv_cb.hip", "gemv_cb8.hip", "gemv_list.hip"]
+SOURCES = ["pack.cpp", "quant_cb.cpp", "gather.hip", "gemv.hip", "gemv_cb.hip", "gemv_cb8.hip", "gemv_list.hip",
+           "gemv_bal.hip"]
 CALIB_LIB = os.path.join(PKG, "libspqt_calib.so")       # benchmark-only helper kernels
 CALIB_SOURCES = ["calib.hip", "baseline_rowmajor.hip"]
 # The same kernels with wall-clock stamps per wavefront (python -m paper_2511_04477_amd.timeline).
@@ -65,6 +66,7 @@ def _build_one(lib: str, sources, verbose: bool, defines=(), tag: str = "") -> s
 
 def build(verbose: bool = False) -> str:
     _build_one(CALIB_LIB, CALIB_SOURCES, verbose)
+    _build_one(TIMELINE_LIB, SOURCES, verbose, defines=("SPQT_TIMELINE=1",), tag="tl_")
     return _build_one(LIB, SOURCES, verbose)
 
 

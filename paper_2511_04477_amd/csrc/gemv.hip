@@ -56,7 +56,7 @@
 
 #include <mutex>
 
-#include "gemv_common.hpp"
+#include "rowpass.hpp"
 
 namespace {
 
@@ -94,6 +94,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     // One activation row on the matrix cores: x as fp16, [column group cg][step u].
     __shared__ __attribute__((aligned(16))) uint16_t stage_x1[kMatrixCoreSingleRow && BATCH == 1 ? WAVES : 1][2][8][8];
 
+    SPQT_TL_BEGIN();
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -115,6 +116,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
     // (a count outside 0..K cannot come from spqt_gather; clamping keeps a corrupt one inside idx)
     const int n_raw = FUSED ? K / kPassCols : (DENSE ? K : __builtin_amdgcn_readfirstlane(*count));
     const int n_ns = n_raw < 0 ? 0 : (n_raw > K ? K : n_raw);
+    SPQT_TL(1);
     const int parts = S * WAVES;
     const int part = s * WAVES + wave;
     int pos = (int)(((int64_t)n_ns * part) / parts);
@@ -261,10 +263,8 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             __builtin_amdgcn_wave_barrier();
         };
 
-        // MULTIPLY stage for ONE activation row on the matrix cores.  Same operands as multiply_rows, but
-        // a 4x4x4 product has room for 4 rows of A and only one is needed: x is placed in row v of A
-        // (zeros elsewhere) for the v-th of four consecutive rows of W, so the four results land in the
-        // four registers of ONE accumulator tuple and the 32 rows of a lane need 8 tuples = 32 registers.
+        // MULTIPLY stage for ONE activation row on the matrix cores (row_products in rowpass.hpp: x sits in
+        // row v of A for the v-th of four consecutive rows of W, so a lane's 32 rows need 32 registers).
         auto multiply_one = [&](int n, uint32_t xraw, int slot, u32x4(&w)[8]) {
             if (FUSED) {    // the fused fetch stage has already staged x; xraw carries this lane's share
                 xsum[0] += as_float(xraw);
@@ -276,33 +276,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             __builtin_amdgcn_wave_barrier();
             const u32x4 xa = *reinterpret_cast<const u32x4 *>(&stage_x1[wave][slot][cg][0]);
             f32x4 accq[8];      // accq[2 d + half][p]: row 8 d + 4 half + p of the lane's 32
-#pragma unroll
-            for (int quad = 0; quad < 2; ++quad) {
-                if (quad == 0 || n > 32) {
-                    f16x4 a[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const bool mine = (lane & 3) == v;
-                        a[v] = as_f16x4(u32x2{mine ? (quad ? xa.z : xa.x) : 0u, mine ? (quad ? xa.w : xa.y) : 0u});
-                    }
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const uint32_t w0 = w[4 * quad + 0][d], w1 = w[4 * quad + 1][d];
-                        const uint32_t w2 = w[4 * quad + 2][d], w3 = w[4 * quad + 3][d];
-#pragma unroll
-                        for (int half = 0; half < 2; ++half) {
-                            u32x2 b[4];
-                            if (half) code_rows<1>(w0, w1, w2, w3, b);
-                            else code_rows<0>(w0, w1, w2, w3, b);
-                            const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-                            f32x4 c = quad ? accq[2 * d + half] : zero;
-#pragma unroll
-                            for (int p = 0; p < 4; ++p) c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[p], as_f16x4(b[p]), c, 0, 0, 0);
-                            accq[2 * d + half] = c;
-                        }
-                    }
-                }
-            }
+            row_products(w, xa, n > 32, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, lane, accq);
             float col[32], r4[4];
 #pragma unroll
             for (int q = 0; q < 32; ++q) col[q] = accq[q >> 2][q & 3];
@@ -537,7 +511,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
             }
         } else {
         kA = fetch_k(pos);
+        SPQT_TL_WAIT(2);
         fetch(kA, pos, 0, wA, nA, gA, xrA, scA, kB);
+        SPQT_TL_WAIT(3);
         if (BATCH > 1) {
             // Several activation rows: the accumulators take most of the register file, so there is
             // one weight buffer, refilled step by step while the pass is being multiplied.
@@ -591,14 +567,19 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_kernel(
         }
     }
 
+    SPQT_TL(4);
     // ---- combine the WAVES wavefronts through LDS ------------------------------------------
 #pragma unroll
     for (int b = 0; b < BATCH; ++b)
         reinterpret_cast<f32x4 *>(red[wave][b])[8 * seg + cgr] = f32x4{yacc[b][0], yacc[b][1], yacc[b][2], yacc[b][3]};
     __syncthreads();
-
+    SPQT_TL(5);
     combine_block_row<WAVES, BATCH>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
+    SPQT_TL_END(WAVES, wave, lane, S > 1 && s == S - 1);
 }
+
+SPQT_TL_SETTER(spqt_timeline_set_gemv)
+
 
 __global__ void spqt_fill_zero_kernel(uint32_t *p, size_t n_words) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -802,8 +783,13 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
     const int y_half = cfg && (cfg->flags & SPQT_CFG_Y_FP16) ? 1 : 0;
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
         return SPQT_EALIGN;
+    // Static column ranges by default; even shares of the kept columns (gemv_bal.hip) when the caller asks
+    // for them - that kernel reads x 16 bytes at a time and holds all of it in LDS (64 KB).
+    const bool even_shares = cfg && (cfg->flags & SPQT_CFG_EVEN_SHARES);
+    if (even_shares && ((cfg->flags & SPQT_CFG_NO_COMPACTION) || K > 32768 || (uintptr_t)x_dev % 16 != 0)) return SPQT_EINVAL;
+    const bool static_ranges = !even_shares;
     spqt_launch_cfg c;
-    choose_cfg(M, K, 1, Kernel::fused, &c);
+    choose_cfg(M, K, 1, static_ranges ? Kernel::fused : Kernel::list_rows, &c);
     if (cfg) {
         if (cfg->splits) c.splits = cfg->splits;
         if (cfg->waves) c.waves = cfg->waves;
@@ -828,6 +814,11 @@ extern "C" int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
     hipError_t err;
+    if (!static_ranges) {
+        err = launch_gemv_bal(c.waves, grid, st, pk, xp, threshold, (float *)y_dev, partials, ws_flags, (int)K, NG,
+                              c.splits, T, (int)M | (y_half ? kHalfOutputBit : 0));
+        return err == hipSuccess ? SPQT_OK : SPQT_EHIP;
+    }
     switch (c.waves) {
         case 1: err = launch_fused<1>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;
         case 2: err = launch_fused<2>(compact, grid, st, pk, xp, threshold, (float *)y_dev, partials, ws_flags, (int)K, NG, c.splits, T, (int)M, y_half); break;

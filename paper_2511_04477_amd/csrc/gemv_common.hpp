@@ -24,6 +24,37 @@ constexpr int kOwnSetsBit = 1 << 29;           // in the kernels' M argument: ev
 constexpr int kRowsMask = (1 << 25) - 1;       // the bits of that argument that hold M (M <= 2^24)
 constexpr int kMaxPolls = 1 << 18;             // bound on the reducer's wait for one batch of partials
 
+// Per-wavefront wall-clock stamps for the timeline build (-DSPQT_TIMELINE=1, libspqt_timeline.so): every
+// wavefront records when it started (0), knew its share of the list (1), had issued its first pass (2),
+// had that pass's weights (3, with a forced wait that the product build does not have), left its loop (4),
+// passed the workgroup's LDS reduction (5) and finished (6); word 7 tells whether it belongs to the
+// reducing workgroup and where it ran.  The product build compiles all of it away.
+#ifdef SPQT_TIMELINE
+static __device__ unsigned long long *spqt_tl_buf = nullptr;   // one per translation unit, set by its setter
+#define SPQT_TL_BEGIN() unsigned long long tl_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; tl_[0] = wall_clock64()
+#define SPQT_TL(i) tl_[i] = wall_clock64()
+#define SPQT_TL_WAIT(i) do { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); tl_[i] = wall_clock64(); } while (0)
+#define SPQT_TL_END(WAVES_, wave_, lane_, reducer_)                                                              \
+    do {                                                                                                         \
+        tl_[6] = wall_clock64();                                                                                 \
+        if (spqt_tl_buf && (lane_) == 0) {                                                                       \
+            unsigned long long *d_ = spqt_tl_buf + ((size_t)blockIdx.x * (WAVES_) + (wave_)) * 8;                \
+            for (int i_ = 0; i_ < 7; ++i_) d_[i_] = tl_[i_];                                                     \
+            d_[7] = (unsigned long long)((reducer_) ? 1 : 0) |                                                   \
+                    ((unsigned long long)__builtin_amdgcn_s_getreg(63492) << 8) |        /* HW_ID */             \
+                    ((unsigned long long)(__builtin_amdgcn_s_getreg(63508) & 15) << 40); /* XCC_ID */            \
+        }                                                                                                        \
+    } while (0)
+#define SPQT_TL_SETTER(name)                                                                          \
+    extern "C" int name(void *p) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(spqt_tl_buf), &p, sizeof(p)); }
+#else
+#define SPQT_TL_BEGIN()
+#define SPQT_TL(i)
+#define SPQT_TL_WAIT(i)
+#define SPQT_TL_END(WAVES_, wave_, lane_, reducer_)
+#define SPQT_TL_SETTER(name)
+#endif
+
 __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)h16);
 }
@@ -167,6 +198,10 @@ __device__ __forceinline__ void code_rows(uint32_t w0, uint32_t w1, uint32_t w2,
     b[2] = u32x2{s01 & 0x000F000Fu, s23 & 0x000F000Fu};
     b[3] = u32x2{s01 & 0x00F000F0u, s23 & 0x00F000F0u};
 }
+
+// The one-launch kernel for one activation row: list built in the kernel, even shares (gemv_bal.hip).
+hipError_t launch_gemv_bal(int waves, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x, float thr,
+                           float *y, void *partials, int32_t *ws_flags, int K, int NG, int S, int T, int m_and_flags);
 
 // The index-list kernel for one activation row with row-aligned passes (gemv_list.hip).
 hipError_t launch_gemv_list(int waves, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,

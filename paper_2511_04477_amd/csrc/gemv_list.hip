@@ -25,14 +25,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "gemv_common.hpp"
+#include "rowpass.hpp"
 
 namespace {
 
 using namespace spqt;
-
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ h2 as_h2(uint32_t bits) { return __builtin_bit_cast(h2, bits); }
 
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
@@ -45,6 +42,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
     __shared__ int32_t stage_grp[WAVES][2][8];                                         // group of each row
     __shared__ __attribute__((aligned(16))) float red[WAVES][1][kTileRows];
 
+    SPQT_TL_BEGIN();
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -62,10 +60,21 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
 
     const int n_raw = __builtin_amdgcn_readfirstlane(*count);
     const int n_ns = n_raw < 0 ? 0 : (n_raw > K ? K : n_raw);
+    SPQT_TL(1);
     const int parts = S * WAVES;
     const int part = s * WAVES + wave;
-    int pos = (int)(((int64_t)n_ns * part) / parts);
-    const int end = (int)(((int64_t)n_ns * (part + 1)) / parts);
+    // even shares [n_ns * part / parts, n_ns * (part + 1) / parts); 32-bit arithmetic when the products fit
+    int pos, end;
+    if (n_ns < (1 << 23)) {
+        pos = (int)(((uint32_t)n_ns * (uint32_t)part) / (uint32_t)parts);
+        end = (int)(((uint32_t)n_ns * (uint32_t)(part + 1)) / (uint32_t)parts);
+    } else {
+        pos = (int)(((int64_t)n_ns * part) / parts);
+        end = (int)(((int64_t)n_ns * (part + 1)) / parts);
+    }
+    // A list of all K columns is the identity (the entries are distinct columns in ascending order):
+    // its entries need not be fetched, which takes a dependent memory access off the start.
+    const bool all_kept = n_ns == K;
 
     const int log2g = (NG << 7) == K ? 7 : 6;
     const int chunk_b = kScaleBytes + (kColBytes << log2g);
@@ -79,7 +88,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         // List entry p + lane, or -1 past the slice (the load itself is never predicated).
         auto fetch_k = [&](int p) -> int {
             const int e = p + lane;
-            const int v = idx[e < n_ns ? e : n_ns - 1];
+            const int v = all_kept ? e : idx[e < n_ns ? e : n_ns - 1];
             return e < end ? v : -1;
         };
 
@@ -87,22 +96,12 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         // to rows, request the next pass's entries, this pass's x, its weights and its rows' scales.
         auto fetch = [&](int kk, int p, int slot, u32x4(&w)[8], u32x4(&sc)[4], int &n_out, bool &hi_out,
                          int &k_after, uint32_t &xraw, int &where) {
-            const bool cand = kk >= 0;
-            const int g = kk >> log2g;
-            const int gprev = __builtin_amdgcn_ds_bpermute((lane - 1) << 2, g);
-            const bool start = cand && (lane == 0 || g != gprev);            // first entry of a run of one group
-            const uint64_t starts = __ballot(start);
-            const int first = 63 - (int)__builtin_clzll((starts & upto) | 1ull);   // where this entry's run starts
-            const int rank = lane - first;                                     // position inside the run
-            const bool newrow = cand && (rank & 7) == 0;
-            const uint64_t rows = __ballot(newrow);
-            const int row = (int)__builtin_popcountll(rows & upto) - 1;
-            const bool take = cand && row < 8;
-            const int n = __builtin_amdgcn_readfirstlane((int)__popcll(__ballot(take)));
+            const RowDeal d = deal_rows(kk, log2g, lane, upto);
+            const bool take = d.take;
+            const int g = d.g, row = d.row, col = d.col, n = d.n;
             k_after = fetch_k(p + n);
-            const int col = rank & 7;
             where = take ? row * 8 + col : -1;
-            hi_out = __ballot(take && col >= 4) != 0ull;
+            hi_out = d.hi;
             xraw = x[take ? kk : 0];
             const uint32_t off_own = (uint32_t)g * (uint32_t)chunk_b + (uint32_t)(kk & ((1 << log2g) - 1)) * kColBytes;
             // Slots no entry lands in point at the pass's first column (a line that is fetched anyway)
@@ -136,55 +135,14 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
             n_out = n;
         };
 
-        // MULTIPLY stage of a fetched pass (see gemv.hip for the operand layout of the 4x4x4 products).
+        // MULTIPLY stage of a fetched pass: x goes to its slots, then the shared row-pass multiply.
         auto multiply = [&](int slot, u32x4(&w)[8], u32x4(&sc)[4], bool hi, uint32_t xraw, int where) {
             if (lane < 32) reinterpret_cast<uint32_t *>(&stage_x[wave][slot][0][0])[lane] = 0u;
             __builtin_amdgcn_wave_barrier();
             if (where >= 0) (&stage_x[wave][slot][0][0])[where] = (uint16_t)xraw;
             __builtin_amdgcn_wave_barrier();
             const u32x4 xa = *reinterpret_cast<const u32x4 *>(&stage_x[wave][slot][cg][0]);
-            // bias: -8 * (sum of the row's x), as the accumulators' initial value
-            const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-            float xs = __builtin_amdgcn_fdot2(as_h2(xa.x), ones, 0.0f, false);
-            xs = __builtin_amdgcn_fdot2(as_h2(xa.y), ones, xs, false);
-            xs = __builtin_amdgcn_fdot2(as_h2(xa.z), ones, xs, false);
-            xs = __builtin_amdgcn_fdot2(as_h2(xa.w), ones, xs, false);
-            const float be = xs * (-8.0f / kTwo24), bo = xs * (-128.0f / kTwo24);
-            const f32x4 init = {be, bo, be, bo};
-            f32x4 accq[8];      // accq[2 d + half][p]: row 8 d + 4 half + p of the lane's 32
-#pragma unroll
-            for (int quad = 0; quad < 2; ++quad) {
-                if (quad == 0 || hi) {
-                    f16x4 a[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const bool mine = (lane & 3) == v;
-                        a[v] = as_f16x4(u32x2{mine ? (quad ? xa.z : xa.x) : 0u, mine ? (quad ? xa.w : xa.y) : 0u});
-                    }
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const uint32_t w0 = w[4 * quad + 0][d], w1 = w[4 * quad + 1][d];
-                        const uint32_t w2 = w[4 * quad + 2][d], w3 = w[4 * quad + 3][d];
-#pragma unroll
-                        for (int half = 0; half < 2; ++half) {
-                            u32x2 b[4];
-                            if (half) code_rows<1>(w0, w1, w2, w3, b);
-                            else code_rows<0>(w0, w1, w2, w3, b);
-                            f32x4 c = quad ? accq[2 * d + half] : init;
-#pragma unroll
-                            for (int p = 0; p < 4; ++p) c = __builtin_amdgcn_mfma_f32_4x4x4f16(a[p], as_f16x4(b[p]), c, 0, 0, 0);
-                            accq[2 * d + half] = c;
-                        }
-                    }
-                }
-            }
-            // scale and add: row i = 4 tq + p of the lane's 32; its scale is half i of the 64 bytes
-#pragma unroll
-            for (int i = 0; i < 32; i += 2) {
-                const h2 sh = as_h2(sc[i >> 3][(i >> 1) & 3]);
-                acc[i] = __builtin_fmaf((float)sh.x, accq[i >> 2][i & 3], acc[i]);
-                acc[i + 1] = __builtin_fmaf((float)sh.y, accq[i >> 2][(i & 3) + 1], acc[i + 1]);
-            }
+            multiply_row_pass(w, sc, xa, hi, lane, acc);
             __builtin_amdgcn_wave_barrier();
         };
 
@@ -194,7 +152,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         int nA, nB, kA, kB, whA, whB;
         bool hiA, hiB;
         kA = fetch_k(pos);
+        SPQT_TL_WAIT(2);
         fetch(kA, pos, 0, wA, scA, nA, hiA, kB, xrA, whA);
+        SPQT_TL_WAIT(3);
         for (;;) {
             const int posB = pos + nA;
             if (posB >= end) {
@@ -214,6 +174,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         }
     }
 
+    SPQT_TL(4);
     // the 8 column-lanes are folded: lane (cg, seg) ends with rows 32 seg + 4 rev(cg) + j (the fold only adds
     // rows whose index is equal mod 4, so odd and even rows stay apart), then back to true units
     float r4[4];
@@ -221,12 +182,16 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
     reinterpret_cast<f32x4 *>(red[wave][0])[8 * seg + cgr] =
         f32x4{r4[0] * kTwo24, r4[1] * (kTwo24 * 0.0625f), r4[2] * kTwo24, r4[3] * (kTwo24 * 0.0625f)};
     __syncthreads();
+    SPQT_TL(5);
     combine_block_row<WAVES, 1>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
+    SPQT_TL_END(WAVES, wave, lane, S > 1 && s == S - 1);
 }
 
 }  // namespace
 
 namespace spqt {
+
+SPQT_TL_SETTER(spqt_timeline_set_list)
 
 hipError_t launch_gemv_list(int waves, int grid, hipStream_t stream, const uint8_t *packed, const uint16_t *x,
                             const int32_t *idx, const int32_t *count, float *y, void *partials, int32_t *ws_flags,

@@ -11,6 +11,7 @@ from workloads import make_case, make_weights, make_x, quantile_threshold
 pytestmark = pytest.mark.gpu
 
 ATOL, RTOL = 1e-2, 2e-3
+EVEN_SHARES = 16     # SPQT_CFG_EVEN_SHARES
 
 
 @pytest.fixture(scope="module")
@@ -306,6 +307,40 @@ def test_fused_gather_gemv(gpu, M, K, splits, waves, sparsity):
     assert_close(gpu_gemv_fused(gpu, w, x, thr, splits=splits, waves=waves), ref, "fused")
 
 
+@pytest.mark.parametrize("M,K", [(256, 128), (1024, 4096), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (7, 2), (16, 4)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_fused_even_shares(gpu, M, K, splits, waves, sparsity):
+    """The one-launch kernel that counts the kept columns first and gives every wavefront an even share."""
+    _, spqt, _ = gpu
+    w = make_weights(M, K, 7200 + M + K)
+    x = make_x(K, "laplace", 7201 + M + K)
+    thr = quantile_threshold(x, sparsity)
+    say(f"fused even shares M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    got = gpu_gemv_fused(gpu, w, x, thr, splits=splits, waves=waves, flags=spqt.CFG_EVEN_SHARES)
+    assert_close(got, ref, "fused, even shares")
+
+
+@pytest.mark.parametrize("M,K,dist", [(512, 1024, "laplace"), (1024, 4096, "laplace_clustered"), (768, 8192, "laplace"),
+                                      (256, 32768, "laplace"), (2048, 1152, "normal")])
+@pytest.mark.parametrize("sparsity", [0.0, 0.3, 0.5, 0.97, 1.0])
+def test_fused_equals_gather_then_list_kernel_bitwise(gpu, M, K, dist, sparsity):
+    """One launch with SPQT_CFG_EVEN_SHARES (list built inside the kernel) and spqt_gather + spqt_gemv perform the same
+    arithmetic in the same order when their launch shapes agree: the outputs are equal bit for bit, and
+    both are within the oracle's tolerance."""
+    w = make_weights(M, K, 7400 + M + K)
+    x = make_x(K, dist, 7401 + M + K)
+    thr = float("inf") if sparsity == 1.0 else quantile_threshold(x, sparsity)
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    for splits, waves in [(0, 0), (1, 1), (3, 2), (16, 4), (64, 4)]:
+        say(f"fused vs list M={M} K={K} {dist} s={sparsity} {splits}x{waves}")
+        a = gpu_gemv_fused(gpu, w, x, thr, splits=splits, waves=waves, flags=EVEN_SHARES)
+        b = gpu_gemv(gpu, w, x, thr, splits=splits, waves=waves)
+        assert_close(a, ref, "one launch")
+        assert np.array_equal(a, b), f"one launch != gather + list kernel at {splits}x{waves}"
+
+
 def test_fused_clustered_ties_and_exact(gpu):
     M, K = 1024, 2048
     w = make_weights(M, K, 61)
@@ -352,6 +387,23 @@ def test_fused_full_size_headline(gpu):
         thr = quantile_threshold(case["x"], s)
         ref = oracle.gemv(case["q_rowmajor"], case["scales"], case["x"], thr)
         assert_close(gpu_gemv_fused(gpu, case, case["x"], thr, packed=packed), ref, f"fused cfg2 s={s}")
+
+
+@pytest.mark.parametrize("tensor", ["gate", "down"])
+def test_fused_full_size_70b(gpu, tensor):
+    """The 70B MLP shapes through both one-launch kernels in the library's default launch shape."""
+    torch, spqt, dev = gpu
+    case = make_case(5, tensor, want_q=False)
+    packed = torch.from_numpy(spqt.spqt_pack(case["q_rowmajor"], case["scales"])).to(dev)
+    for s in (0.3, 0.5, 0.7):
+        thr = quantile_threshold(case["x"], s)
+        say(f"fused full size cfg5/{tensor} s={s}")
+        ref = oracle.gemv(case["q_rowmajor"], case["scales"], case["x"], thr)
+        assert_close(gpu_gemv_fused(gpu, case, case["x"], thr, packed=packed), ref, f"fused cfg5/{tensor} s={s}")
+        got = gpu_gemv_fused(gpu, case, case["x"], thr, packed=packed, flags=EVEN_SHARES)
+        assert_close(got, ref, f"fused, even shares cfg5/{tensor} s={s}")
+        splits, waves = spqt.spqt_default_cfg(case["M"], case["K"], 1, True)
+        assert np.array_equal(got, gpu_gemv(gpu, case, case["x"], thr, packed=packed)), "one launch != gather + list kernel"
 
 
 def test_longest_supported_k(gpu):
