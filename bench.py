@@ -227,11 +227,10 @@ def main():
         sys.exit(1)
     if cpu.enabled:     # the one-launch kernels too
         ref = cpu.gemv(wl.case0, wl.x_np[0:1], wl.thr[0])
-        for fn in (wl.fused, wl.fused_even_shares, wl.dense_only):
+        for fn, want in ((wl.fused, ref), (wl.fused_even_shares, ref), (wl.dense_only, cpu.gemv(wl.case0, wl.x_np[0:1], 0.0))):
             wl.y[0].fill_(float("nan"))
             fn(0)
             torch.cuda.synchronize()
-            want = ref if fn is not wl.dense_only else cpu.gemv(wl.case0, wl.x_np[0:1], 0.0)
             if not cpu.close(wl.y[0].cpu().numpy(), want)[0]:
                 print(f"bench.py: parity check of {fn.__name__} FAILED", file=sys.stderr)
                 sys.exit(1)

@@ -72,8 +72,9 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         pos = (int)(((int64_t)n_ns * part) / parts);
         end = (int)(((int64_t)n_ns * (part + 1)) / parts);
     }
-    // A list of all K columns is the identity (the entries are distinct columns in ascending order):
-    // its entries need not be fetched, which takes a dependent memory access off the start.
+    // A list of all K columns is the identity (the entries are distinct columns in ascending order): the
+    // FIRST pass then does not wait for its entries, which takes a dependent memory access off the start
+    // (later passes request theirs a pass ahead anyway, with the unconditional load the pipeline counts on).
     const bool all_kept = n_ns == K;
 
     const int log2g = (NG << 7) == K ? 7 : 6;
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         // List entry p + lane, or -1 past the slice (the load itself is never predicated).
         auto fetch_k = [&](int p) -> int {
             const int e = p + lane;
-            const int v = all_kept ? e : idx[e < n_ns ? e : n_ns - 1];
+            const int v = idx[e < n_ns ? e : n_ns - 1];
             return e < end ? v : -1;
         };
 
@@ -151,7 +152,8 @@ __global__ __launch_bounds__(WAVES * 64) void spqt_gemv_list_kernel(
         uint32_t xrA, xrB;
         int nA, nB, kA, kB, whA, whB;
         bool hiA, hiB;
-        kA = fetch_k(pos);
+        if (all_kept) kA = pos + lane < end ? pos + lane : -1;
+        else kA = fetch_k(pos);
         SPQT_TL_WAIT(2);
         fetch(kA, pos, 0, wA, scA, nA, hiA, kB, xrA, whA);
         SPQT_TL_WAIT(3);
