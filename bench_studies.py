@@ -394,7 +394,7 @@ def speedup_grid(torch, spqt, use_graph):
 
 def dense_shape_sweep(torch, spqt, use_graph):
     """The dense zigzag kernel on the 15 shapes of the paper's dense micro-benchmark
-    (Section 6.4: m in {2048, 4096, 8192} x k in {1024 ... 16384}); random packed bytes."""
+    (Section 6.3, dense GEMV comparison: m in {2048, 4096, 8192} x k in {1024 ... 16384}); random packed bytes."""
     dev = torch.device("cuda:0")
     rows = []
     for M in (2048, 4096, 8192):

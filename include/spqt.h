@@ -20,7 +20,7 @@
  *   - Shapes: W is M (outputs) x K (inputs).  1 <= M <= 2^24, K % 128 == 0, group 128 or 64,
  *     batch in 1..4; anything else is SPQT_ESHAPE.  M need not be a multiple of the block
  *     height: the last block-row is zero-padded in the packed form (the paper's claim of
- *     generality, Section 4.1.2, fixes no rule for a ragged edge; padding is this build's).
+ *     generality, Section 4.1.3, fixes no rule for a ragged edge; padding is this build's).
  *
  * Packed layout ("zigzag", paper Section 4.1.2: weights are grouped along a column - one
  * block is 256 consecutive rows of ONE column - and the blocks are stored row-major: all
@@ -29,7 +29,7 @@
  * is one chunk per (block-row t, group g):
  *
  *   (written for group = 128; with group = 64 - the paper's claim that other group sizes work the
- *    same way, Section 4.1.2 - read G = 64 for 128 in NG, in the column range of a chunk and in
+ *    same way, Section 4.1.3 - read G = 64 for 128 in NG, in the column range of a chunk and in
  *    its size, 512 + 128 G = 8704)
  *     T = ceil(M/256), NG = K/128, chunk (t, g) at byte offset (t*NG + g) * 16896
  *       bytes [0, 512)          fp16 bits of scale[256t + r][g], r = 0..255, little endian
@@ -122,7 +122,7 @@ int spqt_gather(const void *x_dev, int64_t K, int batch, float threshold, int32_
                 int32_t *count_out_dev, void *stream);
 
 /* DEVICE, async.  spqt_gather for several activation rows that each keep their OWN set (the
- * paper expects a small beam to work, Section 3.2, without saying how the rows' sets combine;
+ * paper expects a small beam to work, Section 3.3, without saying how the rows' sets combine;
  * spqt_gather's union lets every listed column contribute to every row).  Same idx and count
  * as spqt_gather (the union), and in the same launch a copy of x in which row b has the
  * entries it drops itself, |x[b][k]| < threshold, replaced by +0:
@@ -235,7 +235,7 @@ int spqt_gemv_fused(const void *packed_dev, int64_t M, int64_t K, int group, con
                     void *stream, const spqt_launch_cfg *cfg);
 
 /* DEVICE, async.  spqt_gemv_fused for 2..4 activation rows that share one pass over the weights
- * (Section 3.2 expects small beams to work; batch == 1 forwards to spqt_gemv_fused).  A column is
+ * (Section 3.3 expects small beams to work; batch == 1 forwards to spqt_gemv_fused).  A column is
  * visited if ANY row keeps it.
  *   x_dev      fp16[batch][K].
  *   own_sets   0: every row takes every visited column (the union, as spqt_gather + spqt_gemv do);

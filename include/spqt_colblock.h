@@ -79,10 +79,11 @@ int spqt_cb_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void 
                        const spqt_launch_cfg *cfg);
 
 /* ---- K-quant flavour of the column-block layout --------------------------------------------
- * Section 4.1.1: Q4_K - a superblock of 256 weights in eight blocks of 32, 4-bit codes, a 6-bit
- * scale and a 6-bit minimum per block, and two 16-bit superblock scales; a weight is decoded as
- * (d * sc_b) * q - dmin * m_b with q in 0..15.  Here the superblock is 256 consecutive rows of
- * one column (Section 4.1.2).  The decode rule is the format's; the quantizer is this build's own
+ * Section 4.1.1 names the paper's format: Q4_K - a superblock of 256 weights in eight blocks of 32,
+ * 4-bit codes, 6-bit block scales, a 16-bit superblock scale and min - and gives no more.  The per-block
+ * 6-bit minimum, the second 16-bit superblock scale for the minima and the decode formula
+ * (d * sc_b) * q - dmin * m_b with q in 0..15 are this build's reading, taken from the public K-quant
+ * format.  Here the superblock is 256 consecutive rows of one column (Section 4.1.2).  The quantizer is this build's own
  * plain min/max rule, in fp32 with round to nearest even:
  *     lo_b = min(min w, 0), hi_b = max(max w, 0), scale_b = (hi_b - lo_b) / 15, min_b = 0 - lo_b
  *     d = fp16(max_b scale_b / 63), dmin = fp16(max_b min_b / 63)
@@ -108,7 +109,7 @@ int spqt_cbk_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void
                         const spqt_launch_cfg *cfg);
 
 /* ---- 8-bit flavour of the column-block layout ("ZZ-CB32-W8") --------------------------------
- * Section 4.1.2 states that the layout carries over to other bit-widths without giving one.  This
+ * Section 4.1.3 states that the layout carries over to other bit-widths without giving one.  This
  * reading keeps one activation column's weights of a block-row in ONE 128-byte run, so a
  * block-row is 128 rows high; blocks stay 32 rows with one fp16 scale (fp32, round to nearest even):
  *     s = fp16(max|w| / 127),  q = clamp(rint(w / float(s)), -128, 127)  (0 if s is 0),  value q * float(s)

@@ -4,9 +4,11 @@ Only the tests, the smoke check and the benchmark's cpu_baseline leg may import 
 the product package never does.  Plain NumPy, written from the paper and the format text below,
 sharing nothing with the HIP path.
 
-What the paper uses (Section 4.1.1): Q4_K - a superblock of 256 weights split into eight blocks
-of 32; weights stored in 4 bits; per block a 6-bit scale and a 6-bit minimum; per superblock a
-16-bit scale for the block scales and one for the block minima.  A weight is decoded as
+What the paper says of its format (Section 4.1.1): Q4_K - a superblock of 256 weights split into eight
+blocks of 32, weights stored in 4 bits, "shared 6-bit block scales and a 16-bit superblock scale and min".
+The paper gives no more than that.  THIS BUILD'S READING, taken from the public K-quant format and not
+from the paper: besides its 6-bit scale every block also has a 6-bit MINIMUM; a superblock has one
+16-bit scale d for the block scales and one, dmin, for the block minima; a weight is decoded as
 (d * sc_b) * q - (dmin * m_b) with q in 0..15.  In the zigzag layout (Section 4.1.2) a
 superblock is 256 consecutive rows of ONE column and superblocks are stored row-major by
 superblock-row; the model is re-quantized offline into this form (Section 5).

@@ -4,7 +4,7 @@ Only the tests, the smoke check and the benchmark's cpu_baseline leg may import 
 the product package never does.  Plain NumPy, written from the paper and the format text below,
 sharing nothing with the HIP path.
 
-The paper states that the layout carries over to other bit-widths (Section 4.1.2) without
+The paper states that the layout carries over to other bit-widths (Section 4.1.3) without
 giving one.  This build's 8-bit reading keeps what the 4-bit layout is built around - one
 activation column's weights of a block-row are ONE 128-byte run - so a block-row is 128 rows
 high instead of 256, and keeps the 32-row blocks with one fp16 scale each (Section 4.1.1's block

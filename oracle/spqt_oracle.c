@@ -176,7 +176,7 @@ void spqt_oracle_partition(int64_t n_ns, int64_t parts, int64_t j, int64_t *begi
  * choice, because the quantization groups stay along K (no requantization):
  *
  *   R = 256 rows per tile, G columns per quantization group (128 in the workloads of record; the
- *   paper says other group sizes work the same way, Section 4.1.2, and G = 64 is the second one
+ *   paper says other group sizes work the same way, Section 4.1.3, and G = 64 is the second one
  *   built: read 64 for 128 in the column range and the size of a chunk below),
  *   T = ceil(M / R) block-rows, NG = K / G groups.  When M is not a multiple of R the rows
  *   M .. R*T-1 of the last block-row do not exist; they are stored as weight 0 (code 8) under

@@ -691,7 +691,8 @@ int gemv_run(const void *packed_dev, int64_t M, int64_t K, int group, const void
         if (cfg->waves) c.waves = cfg->waves;
     }
     if (c.splits < 1 || c.splits > SPQT_MAX_SPLITS) return SPQT_EINVAL;
-    if (c.waves != 1 && c.waves != 2 && c.waves != 4) return SPQT_EINVAL;
+    // 8 wavefronts per workgroup (two per SIMD) exist for the index-list kernel with one activation row only
+    if (c.waves != 1 && c.waves != 2 && c.waves != 4 && !(c.waves == 8 && row_passes)) return SPQT_EINVAL;
 
     size_t need = 0;
     spqt_workspace_bytes(M, K, batch, &need);

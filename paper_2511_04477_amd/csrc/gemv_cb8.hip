@@ -1,6 +1,6 @@
 // spqt_cb8_gemv: the column-block GEMV for 8-bit codes ("ZZ-CB32-W8", spqt_colblock.h).
 //
-// Paper Section 4.1.2 states that the column-wise layout carries over to other bit-widths.  What
+// Paper Section 4.1.3 states that the column-wise layout carries over to other bit-widths.  What
 // the 4-bit kernels are built around is kept: one activation column's weights of a block-row are
 // ONE 128-byte run, read by 8 lanes with one 16-byte load each, 8 columns per wavefront load, 64
 // list entries per pass.  With 8-bit codes that run is 128 rows, so a block-row is 128 rows high,

@@ -201,6 +201,7 @@ hipError_t launch_gemv_list(int waves, int grid, hipStream_t stream, const uint8
     switch (waves) {
         case 1: hipLaunchKernelGGL((spqt_gemv_list_kernel<1>), dim3(grid), dim3(64), 0, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, m_and_flags); break;
         case 2: hipLaunchKernelGGL((spqt_gemv_list_kernel<2>), dim3(grid), dim3(128), 0, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, m_and_flags); break;
+        case 8: hipLaunchKernelGGL((spqt_gemv_list_kernel<8>), dim3(grid), dim3(512), 0, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, m_and_flags); break;
         default: hipLaunchKernelGGL((spqt_gemv_list_kernel<4>), dim3(grid), dim3(256), 0, stream, packed, x, idx, count, y, partials, ws_flags, K, NG, S, T, m_and_flags); break;
     }
     return hipGetLastError();

@@ -126,6 +126,15 @@ def main(argv=None) -> int:
     cuid = ((xcc * 8 + se) * 2 + sh) * 16 + cu
     ids, per_cu = np.unique(cuid, return_counts=True)
     print(f"\nCUs used: {len(ids)}; wavefronts per CU: min {per_cu.min()}, median {int(np.median(per_cu))}, max {per_cu.max()}")
+    # how uneven the wavefronts finish their loops: inside a workgroup, and between workgroups
+    full = stamps.cpu().numpy().reshape(grid, W, 8)
+    full = full[full[:, 0, 0] > 0]
+    if full.shape[0]:
+        done = 0.01 * (full[:, :, 4].astype(np.float64) - t0)
+        inside = done.max(axis=1) - done.min(axis=1)
+        last = done.max(axis=1)
+        print(f"loop done, spread inside a workgroup (last - first wavefront): median {np.median(inside):.2f} us, max {inside.max():.2f} us; "
+              f"last wavefront of a workgroup: min {last.min():.2f}, median {np.median(last):.2f}, max {last.max():.2f} us")
     stream = us(d[:, 4]) - us(d[:, 3])
     print(f"first weights -> loop done per wavefront: median {np.median(stream):.2f} us, max {stream.max():.2f} us")
     return 0

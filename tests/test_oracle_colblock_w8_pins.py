@@ -2,7 +2,7 @@
 something other than its own formula - exactly representable inputs, error bounds, symmetries,
 hand-made rounding cases, pure-Python brute force, independent NumPy expressions, closed-form byte
 positions, and the 4-bit oracle (a finer grid must not be less accurate).  The paper (Section
-4.1.2) only states that the layout carries over to other bit-widths; format and rule are this
+4.1.3) only states that the layout carries over to other bit-widths; format and rule are this
 build's reading, stated in the oracle's header."""
 import numpy as np
 import pytest
