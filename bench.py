@@ -315,10 +315,12 @@ def main():
                 torch.cuda.empty_cache()
         out["sweep"] = sweep
         # decoder-layer GEMV sequences with spqt_gather time included: Llama-3-8B full layer over 32 rotated
-        # layers (configuration 4), Llama-2-7B MLP over 16 (configuration 3), both at 50 %
+        # layers (configuration 4), Llama-2-7B MLP over 16 (configuration 3), 70B-shaped MLP over 8
+        # (configuration 5), all at 50 %
         seq_modes = ("strict", "shared", "fused", "merged_gather_gemv", "merged_fused", "dense", "merged_dense")
         out["layer_sequences"] = [layer_sequence(torch, spqt, 4, 32, 0.5, use_graph, modes=None if args.full else seq_modes),
-                                  layer_sequence(torch, spqt, 3, 16, 0.5, use_graph, modes=None if args.full else seq_modes)]
+                                  layer_sequence(torch, spqt, 3, 16, 0.5, use_graph, modes=None if args.full else seq_modes),
+                                  layer_sequence(torch, spqt, 5, 8, 0.5, use_graph, modes=None if args.full else seq_modes)]
         if args.full:
             import bench_studies as st
             out["layer_sequences"].append(layer_sequence(torch, spqt, 3, 16, 0.4, use_graph))

@@ -117,7 +117,7 @@ def main(argv=None) -> int:
     L += ["## Kernel durations, isolated stream launches", "",
           f"    rocprofv3 --kernel-trace --stats --output-format csv -d D/kt -o kt -- python3 bench.py --pmc-pass --pmc-workload {W}", "",
           "Every kernel launched once per weight copy with plain stream launches: the profiler brackets every dispatch and the GPU "
-          "idles between them, so these read higher than the graph-replay figures above.", "",
+          "idles between them, so these read higher than back-to-back launches from a HIP graph do.", "",
           "| kernel | calls | average ns | min ns | max ns | GB/s on its algorithmic bytes |", "|---|---|---|---|---|---|"]
     for name, calls, avg, mn, mx in stats(os.path.join(D, "kt"), lambda n: kname in n or "spqt_gather" in n or ("copy_kernel" in n and "anonymous" in n and "at::" not in n)):
         if "copy_kernel" in name:
