@@ -135,6 +135,12 @@ def main(argv=None) -> int:
         last = done.max(axis=1)
         print(f"loop done, spread inside a workgroup (last - first wavefront): median {np.median(inside):.2f} us, max {inside.max():.2f} us; "
               f"last wavefront of a workgroup: min {last.min():.2f}, median {np.median(last):.2f}, max {last.max():.2f} us")
+    # where the slow wavefronts are: by XCD, by position inside the workgroup, by split index of the block-row
+    done_all = us(d[:, 4])
+    print("loop done, median per XCD: " + ", ".join(f"{np.median(done_all[xcc == i]):.2f}" for i in sorted(set(xcc.tolist()))))
+    if full.shape[0]:
+        print("loop done, median per wavefront index in the workgroup: " + ", ".join(f"{np.median(done[:, w]):.2f}" for w in range(W)))
+        print("start, median per wavefront index in the workgroup: " + ", ".join(f"{np.median(0.01 * (full[:, w, 0] - t0)):.2f}" for w in range(W)))
     stream = us(d[:, 4]) - us(d[:, 3])
     print(f"first weights -> loop done per wavefront: median {np.median(stream):.2f} us, max {stream.max():.2f} us")
     return 0
