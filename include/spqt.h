@@ -182,6 +182,10 @@ typedef struct {
  *                  activation row a list of n_ns == K entries is taken to be 0..K-1 without being read.
  *   count_dev      int32[1] n_ns on the device (ignored when idx_dev == NULL).
  *   y_dev          fp32[batch][M], fully overwritten (zeros when n_ns == 0).
+ *                  Non-finite activations: a kept NaN or +-Inf in x[b] makes EVERY output of row b NaN.
+ *                  (The stored codes are q + 8 and the bias is removed as -8 * sum of the kept x, so an
+ *                  infinite x meets its opposite infinity; the definition w * x would give +-Inf, and NaN
+ *                  only where q == 0.  Finite inputs are what the method is for; this pins the rest.)
  *   workspace_dev  >= spqt_workspace_bytes(M, K, batch) bytes, prepared by
  *                  spqt_workspace_init (else SPQT_ESIZE / SPQT_EINVAL).
  * Deterministic: partial sums are combined in a fixed order, no floating-point atomics.

@@ -565,3 +565,70 @@ def test_full_size_four_rows_union_list(gpu, tensor):
         assert not np.isnan(got).any()
         e = assert_close(got[:, rows], oracle.gemv_rows(q, sc, x_np, thr, rows), f"{tensor} 4 rows s={s}")
         say(f"   kept {n}/{K}, max|err|={e:.3e}")
+
+
+# ------------------------------------------------------------------------------ pinned corner behaviour
+
+def test_non_finite_activation_makes_every_output_nan(gpu):
+    """A kept Inf (or NaN) activation: the offset-binary bias (-8 * sum of kept x) meets the products'
+    opposite infinity, so every output is NaN in every kernel - the behaviour the header states.  The
+    oracle (w * x per weight) is non-finite in every row as well."""
+    M, K = 512, 1024
+    w = make_weights(M, K, 8801)
+    for bad in (np.inf, -np.inf, np.nan):
+        x = make_x(K, "laplace", 8802)
+        x[0, 300] = bad
+        thr = quantile_threshold(x[:, :256], 0.5)
+        ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+        assert not np.isfinite(ref).any()
+        for got in (gpu_gemv(gpu, w, x, thr), gpu_gemv(gpu, w, x, 0.0, dense=True), gpu_gemv_fused(gpu, w, x, thr),
+                    gpu_gemv_fused(gpu, w, x, thr, flags=EVEN_SHARES), gpu_gemv(gpu, w, x, thr, flags=8)):
+            assert np.isnan(got).all(), bad
+
+
+def test_matrix_cores_take_fp16_subnormals_unflushed(gpu):
+    """The multiply feeds the 4-bit codes to v_mfma_f32_4x4x4_16B_f16 as fp16 SUBNORMALS (code * 2^-24).  Were
+    subnormal inputs flushed to zero, every product would vanish and y would be -8 * scale * sum(x) for every
+    row.  Codes 1 (q = -7) and 15 (q = +7) with scale 1 and x = 1 on the kept columns: y = -7 n or +7 n exactly."""
+    M, K = 512, 1024
+    q = np.empty((M, K // 2), dtype=np.uint8)
+    q[0::2] = 0x99          # two's-complement nibble 9 = -7 in every position: stored code 1
+    q[1::2] = 0x77          # +7: stored code 15
+    w = {"q_rowmajor": q, "scales": np.ones((M, K // 128), dtype=np.float16)}
+    x = np.zeros((1, K), dtype=np.float16)
+    kept = np.arange(0, K, 3)
+    x[0, kept] = 1.0
+    want = np.where(np.arange(M) % 2 == 0, -7.0, 7.0) * len(kept)
+    assert np.array_equal(oracle.gemv(q, w["scales"], x, 0.5)[0], want)
+    for got in (gpu_gemv(gpu, w, x, 0.5), gpu_gemv(gpu, w, x, 0.0, dense=True), gpu_gemv_fused(gpu, w, x, 0.5),
+                gpu_gemv_fused(gpu, w, x, 0.5, flags=EVEN_SHARES), gpu_gemv(gpu, w, np.repeat(x, 3, axis=0), 0.5)):
+        assert np.array_equal(got.astype(np.float64), np.broadcast_to(want, got.shape))
+
+
+@pytest.mark.parametrize("M", [1, 255, 257, 1000, 3000, 5000, 9000])
+@pytest.mark.parametrize("K", [128, 384, 1152, 5120, 9216])
+def test_default_launch_shape_off_the_tuned_shapes(gpu, M, K):
+    """The launch shape the library picks (spqt_default_cfg) on shapes it was not tuned on - ragged M, K that
+    is no power of two, very flat and very tall matrices - through every batch-1 entry point, against the oracle."""
+    torch, spqt, dev = gpu
+    Mp = 256 * ((M + 255) // 256)
+    full = make_weights(Mp, K, 8900 + M + K)
+    w = {"q_rowmajor": np.ascontiguousarray(full["q_rowmajor"][:M]), "scales": np.ascontiguousarray(full["scales"][:M])}
+    x = make_x(K, "laplace", 8901 + M + K)
+    thr = quantile_threshold(x, 0.5)
+    say(f"off-grid default launch M={M} K={K} cfg={spqt.spqt_default_cfg(M, K, 1, True)} dense cfg={spqt.spqt_default_cfg(M, K, 1, False)}")
+    ref = oracle.gemv(w["q_rowmajor"], w["scales"], x, thr)
+    assert_close(gpu_gemv(gpu, w, x, thr), ref, "list")
+    assert_close(gpu_gemv_fused(gpu, w, x, thr), ref, "one launch")
+    assert_close(gpu_gemv_fused(gpu, w, x, thr, flags=EVEN_SHARES), ref, "one launch, even shares")
+    assert_close(gpu_gemv(gpu, w, x, 0.0, dense=True), oracle.gemv(w["q_rowmajor"], w["scales"], x, 0.0), "dense")
+    # and the allocation-free entry point, which uses the same default shape with the static scratch
+    packed = torch.from_numpy(spqt.spqt_pack(w["q_rowmajor"], w["scales"])).to(dev)
+    xd = torch.from_numpy(x[0]).to(dev)
+    idx = torch.empty(K, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    y = torch.full((M,), float("nan"), dtype=torch.float32, device=dev)
+    spqt.spqt_gather(xd, thr, idx, cnt)
+    spqt.spqt_gemv_static(packed, M, K, xd, idx, cnt, y)
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy()[None, :], ref, "static scratch")
