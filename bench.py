@@ -76,6 +76,12 @@ class CpuBaseline:
         q, s = c8.quantize(W_rows)
         return c8.gemv(q, s, x_np, thr)[0]
 
+    def colblock_w2(self, W_rows, x_np, thr):
+        """2-bit column-block reference on a subset of whole 512-row block-rows of fp32 weights."""
+        from oracle import colblock_w2 as c2
+        c, s = c2.quantize(W_rows)
+        return c2.gemv(c, s, x_np, thr)[0]
+
     def colblock_k(self, W_rows, x_np, thr):
         """K-quant column-block reference on a subset of whole 256-row tiles of fp32 weights."""
         from oracle import colblock_k as ck
@@ -92,7 +98,7 @@ class CpuBaseline:
         counterpart of the column-block rule.  Host only (NumPy and the oracles); says nothing about
         trained weights."""
         import numpy as np
-        from oracle import colblock as cb, colblock_k as ck, colblock_w8 as c8
+        from oracle import colblock as cb, colblock_k as ck, colblock_w8 as c8, colblock_w2 as c2
         from workloads import make_fp_weights, make_x
         M, K = 2048, 4096
         x = make_x(K, "laplace", 424243)[0].astype(np.float64)
@@ -114,11 +120,13 @@ class CpuBaseline:
             y = W @ x
             q4, s4 = cb.quantize(Wf)
             q8, s8 = c8.quantize(Wf)
+            q2, s2 = c2.quantize(Wf)
             forms = [("group layout, 128 along K", 4 + 16 / 128, row_groups(Wf, 128)),
                      ("group layout, 64 along K", 4 + 16 / 64, row_groups(Wf, 64)),
                      ("column blocks of 32 rows", 4 + 16 / 32, cb.dequant(q4, s4)),
                      ("column blocks, 6-bit scales and minima", 4.5, ck.dequant(ck.quantize(Wf))),
-                     ("column blocks of 32 rows, 8-bit", 8 + 16 / 32, c8.dequant(q8, s8))]
+                     ("column blocks of 32 rows, 8-bit", 8 + 16 / 32, c8.dequant(q8, s8)),
+                     ("column blocks of 32 rows, 2-bit", 2 + 16 / 32, c2.dequant(q2, s2))]
             rows += [{"weights": label, "format": name, "bits_per_weight": round(bits, 3),
                       "rel_rms_weight_error": round(rel(Wd, W), 5), "rel_rms_gemv_error": round(rel(Wd @ x, y), 5)}
                      for name, bits, Wd in forms]
@@ -188,7 +196,7 @@ def main():
     ap.add_argument("--pmc-pass", action="store_true",
                     help="for hardware-counter runs: launch only a 64 MiB calibration copy (x8) and the kernels "
                          "of --pmc-workload once per weight copy, eagerly, and exit")
-    ap.add_argument("--pmc-workload", choices=["gate70b", "q4096", "gate70b_colblock", "gate70b_w8"], default="gate70b",
+    ap.add_argument("--pmc-workload", choices=["gate70b", "q4096", "gate70b_colblock", "gate70b_w8", "gate70b_w2"], default="gate70b",
                     help="with --pmc-pass: 28672x8192 group layout (the headline), 4096x4096 group layout, "
                          "28672x8192 column-block layout, 28672x8192 8-bit column-block layout, all at 50 %%")
     args = ap.parse_args()
@@ -330,6 +338,7 @@ def main():
                 out["quantization_error"] = cpu.quantization_error()
             out["rowmajor_baseline"] = st.rowmajor_baseline(torch, spqt, use_graph, cpu)
             out["eight_bit_layout"] = st.eight_bit_rows(torch, spqt, use_graph, cpu)
+            out["two_bit_layout"] = st.two_bit_rows(torch, spqt, use_graph, cpu)
             out["merged_gate_up_70b"] = st.merged_gate_up_70b(torch, spqt, use_graph, cpu)
             out["dense_shape_sweep"] = st.dense_shape_sweep(torch, spqt, use_graph)
             out["speedup_grid"] = st.speedup_grid(torch, spqt, use_graph)

@@ -167,33 +167,40 @@ def merged_gate_up_70b(torch, spqt, use_graph, cpu):
     return rows
 
 
-def eight_bit_rows(torch, spqt, use_graph, cpu):
-    """The 8-bit flavour of the column-block layout (128-row block-rows, one column still one
-    128-byte run) on the headline and the 70B gate shape at 50 % and dense.  Copy 0 is quantized
-    from seeded fp32 weights by the library and checked against the NumPy oracle on sampled
+def other_width_rows(torch, spqt, use_graph, cpu, bits):
+    """The 8-bit or 2-bit flavour of the column-block layout (block-rows of 128 or 512 rows, one column
+    still one 128-byte run) on the headline and the 70B gate shape at 50 % and dense.  Copy 0 is
+    quantized from seeded fp32 weights by the library and checked against the NumPy oracle on sampled
     block-rows; the other copies are random codes under valid fp16 scales."""
     import numpy as np
     from workloads import make_fp_weights, make_x, quantile_threshold
     dev = torch.device("cuda:0")
+    if bits == 8:
+        tile_rows, chunk_bytes, seed = 128, spqt.CB8_CHUNK_BYTES, 9100
+        packed_bytes, quantize, gemv, reference = spqt.spqt_cb8_packed_bytes, spqt.spqt_cb8_quantize, spqt.spqt_cb8_gemv, cpu.colblock_w8
+    else:
+        tile_rows, chunk_bytes, seed = 512, spqt.CB2_CHUNK_BYTES, 9200
+        packed_bytes, quantize, gemv, reference = spqt.spqt_cb2_packed_bytes, spqt.spqt_cb2_quantize, spqt.spqt_cb2_gemv, cpu.colblock_w2
+    scale_bytes = 128 * 2 * (tile_rows // 32)
     rows = []
     for M, K in ((4096, 4096), (28672, 8192)):
-        pbytes = spqt.spqt_cb8_packed_bytes(M, K)
+        pbytes = packed_bytes(M, K)
         copies = max(2, -(-ROTATE_BYTES // pbytes))
-        T, NC = M // 128, K // 128
-        W0 = make_fp_weights(M, K, 9100 + M)
-        packed = [torch.from_numpy(spqt.spqt_cb8_quantize(W0)).to(dev)]
+        T, NC = M // tile_rows, K // 128
+        W0 = make_fp_weights(M, K, seed + M)
+        packed = [torch.from_numpy(quantize(W0)).to(dev)]
         g = torch.Generator(device=dev)
-        g.manual_seed(9101 + M)
+        g.manual_seed(seed + 1 + M)
         for _ in range(1, copies):
-            buf = torch.randint(0, 256, (T * NC, spqt.CB8_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NC, 512), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
-            buf[:, :1024] = sc.view(torch.uint8)
+            buf = torch.randint(0, 256, (T * NC, chunk_bytes), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NC, scale_bytes // 2), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
+            buf[:, :scale_bytes] = sc.view(torch.uint8)
             packed.append(buf.reshape(-1))
         tiles = np.unique(np.array([0, T // 2, T - 1]))
-        sample = (tiles[:, None] * 128 + np.arange(128)[None, :]).ravel()
+        sample = (tiles[:, None] * tile_rows + np.arange(tile_rows)[None, :]).ravel()
         W0_sample = W0[sample].copy()
         del W0
-        x_np = make_x(K, "laplace", 9102 + M)
+        x_np = make_x(K, "laplace", seed + 2 + M)
         thr = quantile_threshold(x_np, 0.5)
         x = torch.from_numpy(x_np[0]).to(dev)
         idx = torch.empty(K, dtype=torch.int32, device=dev)
@@ -205,18 +212,18 @@ def eight_bit_rows(torch, spqt, use_graph, cpu):
         n = int(cnt.item())
         if cpu.enabled:
             y.fill_(float("nan"))
-            spqt.spqt_cb8_gemv(packed[0], M, K, x, idx, cnt, y, ws)
+            gemv(packed[0], M, K, x, idx, cnt, y, ws)
             torch.cuda.synchronize()
-            if not cpu.close(y.cpu().numpy()[sample], cpu.colblock_w8(W0_sample, x_np, thr))[0]:
-                print(f"bench.py: 8-bit column-block parity check FAILED ({M}x{K})", file=sys.stderr)
+            if not cpu.close(y.cpu().numpy()[sample], reference(W0_sample, x_np, thr))[0]:
+                print(f"bench.py: {bits}-bit column-block parity check FAILED ({M}x{K})", file=sys.stderr)
                 sys.exit(1)
-        fns = {"us_gemv": lambda i: spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws),
-               "us_dense": lambda i: spqt.spqt_cb8_gemv(packed[i], M, K, x, None, None, y, ws),
+        fns = {"us_gemv": lambda i: gemv(packed[i], M, K, x, idx, cnt, y, ws),
+               "us_dense": lambda i: gemv(packed[i], M, K, x, None, None, y, ws),
                "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
-                                                 spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws))}
+                                                 gemv(packed[i], M, K, x, idx, cnt, y, ws))}
         t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
-        kept = n * (M + M // 16)
-        rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(n / K, 4), "bits_per_weight": 8.5,
+        kept = n * (M * bits // 8 + M // 16)
+        rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(n / K, 4), "bits_per_weight": bits + 0.5,
                      "kept_bytes": kept, **{k: round(v, 3) for k, v in t.items()},
                      "GBps_kept": round(kept / (t["us_gemv"] * 1e-6) / 1e9, 1),
                      "frac_of_8TBps": round(kept / (t["us_gemv"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -225,6 +232,14 @@ def eight_bit_rows(torch, spqt, use_graph, cpu):
         del packed
         torch.cuda.empty_cache()
     return rows
+
+
+def eight_bit_rows(torch, spqt, use_graph, cpu):
+    return other_width_rows(torch, spqt, use_graph, cpu, 8)
+
+
+def two_bit_rows(torch, spqt, use_graph, cpu):
+    return other_width_rows(torch, spqt, use_graph, cpu, 2)
 
 
 def colblock_rows(torch, spqt, use_graph, cpu, full=True):
@@ -459,17 +474,24 @@ def pmc_pass_large(torch, spqt, which):
             for i in range(wl.copies):
                 fn(i)
         kept, dense, copies = wl.mean_kept_bytes, wl.dense_bytes, wl.copies
-    elif which == "gate70b_w8":
-        pbytes = spqt.spqt_cb8_packed_bytes(M, K)
+    elif which in ("gate70b_w8", "gate70b_w2"):
+        if which == "gate70b_w8":
+            bits, tile_rows, chunk_bytes = 8, 128, spqt.CB8_CHUNK_BYTES
+            packed_bytes, gemv = spqt.spqt_cb8_packed_bytes, spqt.spqt_cb8_gemv
+        else:
+            bits, tile_rows, chunk_bytes = 2, 512, spqt.CB2_CHUNK_BYTES
+            packed_bytes, gemv = spqt.spqt_cb2_packed_bytes, spqt.spqt_cb2_gemv
+        scale_bytes = 128 * 2 * (tile_rows // 32)
+        pbytes = packed_bytes(M, K)
         copies = max(2, -(-ROTATE_BYTES // pbytes))
-        T, NC = M // 128, K // 128
+        T, NC = M // tile_rows, K // 128
         g = torch.Generator(device=dev)
         g.manual_seed(9201)
         packed = []
         for _ in range(copies):
-            buf = torch.randint(0, 256, (T * NC, spqt.CB8_CHUNK_BYTES), dtype=torch.uint8, device=dev, generator=g)
-            sc = (torch.rand((T * NC, 512), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
-            buf[:, :1024] = sc.view(torch.uint8)
+            buf = torch.randint(0, 256, (T * NC, chunk_bytes), dtype=torch.uint8, device=dev, generator=g)
+            sc = (torch.rand((T * NC, scale_bytes // 2), device=dev, generator=g) * 0.0008 + 0.0003).to(torch.float16)
+            buf[:, :scale_bytes] = sc.view(torch.uint8)
             packed.append(buf.reshape(-1))
         x_np = make_x(K, "laplace", 9202)
         thr = quantile_threshold(x_np, s)
@@ -481,10 +503,10 @@ def pmc_pass_large(torch, spqt, which):
         spqt.spqt_gather(x, thr, idx, cnt)
         torch.cuda.synchronize()
         for i in range(copies):
-            spqt.spqt_cb8_gemv(packed[i], M, K, x, idx, cnt, y, ws)
+            gemv(packed[i], M, K, x, idx, cnt, y, ws)
         for i in range(copies):
-            spqt.spqt_cb8_gemv(packed[i], M, K, x, None, None, y, ws)
-        kept, dense = int(cnt.item()) * (M + M // 16), pbytes
+            gemv(packed[i], M, K, x, None, None, y, ws)
+        kept, dense = int(cnt.item()) * (M * bits // 8 + M // 16), pbytes
     else:
         pbytes = spqt.spqt_cb_packed_bytes(M, K)
         copies = max(2, -(-ROTATE_BYTES // pbytes))

@@ -125,10 +125,36 @@ int spqt_cb8_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_p
 /* HOST.  w_out[m][k] = q * float(s), float[M][K]. */
 int spqt_cb8_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 /* DEVICE, async.  As spqt_cb_gemv with batch 1, on spqt_cb8_quantize's output.  The workspace
- * has the size spqt_workspace_bytes(M, K, 1) gives, but its contents are laid out for 128-row
- * block-rows: do not share one workspace between this entry point and the 4-bit ones without a
- * spqt_workspace_init in between. */
+ * has the size spqt_workspace_bytes(M, K, 1) gives and may be the one the other entry points use. */
 int spqt_cb8_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+                  const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
+                  void *stream, const spqt_launch_cfg *cfg);
+
+/* ---- 2-bit flavour of the column-block layout ("ZZ-CB32-W2") --------------------------------
+ * Section 4.1.3 names 2 to 8 bits as the widths the layout carries over to and gives no format.  This
+ * reading again keeps one activation column's weights of a block-row in ONE 128-byte run, so a
+ * block-row is 512 rows high; blocks stay 32 rows with one fp16 scale.  Four levels cannot hold a zero
+ * level and a symmetric range at once; the rule is the plain mid-rise one, levels -1.5 s, -0.5 s,
+ * +0.5 s, +1.5 s (fp32, round to nearest even, ties of rint to even):
+ *     s = fp16(max|w| / 1.5),  c = clamp(rint(w / float(s) + 1.5), 0, 3)  (0 if s is 0),  value (c - 1.5) * float(s)
+ * Packed form: T = ceil(M/512), NC = K/128, chunk (t, c) at (t*NC + c) * 20480:
+ *     bytes [32 j + 2 b], b = 0..15         fp16 scale of rows 512t + 32b .. +31 of column 128c + j
+ *     bytes [4096 + 128 j + i], i < 128     codes of rows 512t + 4i + e, e = 0..3, of column 128c + j,
+ *                                           row 4i + e in bits 2e, 2e + 1
+ * total = T*NC*20480 bytes (2.5 bits per weight when M % 512 == 0).  Rows past M in the last
+ * block-row are quantized as zero weights (code 0 under a zero scale) and never written back. */
+#define SPQT_CB2_TILE_ROWS 512
+#define SPQT_CB2_CHUNK_BYTES 20480
+int spqt_cb2_packed_bytes(int64_t M, int64_t K, size_t *out_bytes);
+/* HOST, offline.  As spqt_cb_quantize, by the 2-bit rule above. */
+int spqt_cb2_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_packed, size_t out_bytes);
+/* HOST.  w_out[m][k] = (c - 1.5) * float(s), float[M][K]. */
+int spqt_cb2_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
+/* DEVICE, async.  As spqt_cb_gemv with batch 1, on spqt_cb2_quantize's output:
+ * y[m] = sum over the listed columns k of (c[m][k] - 1.5) * s[m/32][k] * x[k], fp32 accumulation.
+ * cfg->splits at most 16, cfg->waves 1, 2 or 4 (else SPQT_EINVAL).  The workspace has the size
+ * spqt_workspace_bytes(M, K, 1) gives and may be the one the other entry points use. */
+int spqt_cb2_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
                   const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                   void *stream, const spqt_launch_cfg *cfg);
 

@@ -34,9 +34,11 @@ EXPORTS = [
 
 CB_EXPORTS = ["spqt_cb_packed_bytes", "spqt_cb_quantize", "spqt_cb_dequantize", "spqt_cb_gemv",
               "spqt_cb_gemv_fused", "spqt_cbk_quantize", "spqt_cbk_dequantize", "spqt_cbk_gemv", "spqt_cbk_gemv_fused",
-              "spqt_cb8_packed_bytes", "spqt_cb8_quantize", "spqt_cb8_dequantize", "spqt_cb8_gemv"]
+              "spqt_cb8_packed_bytes", "spqt_cb8_quantize", "spqt_cb8_dequantize", "spqt_cb8_gemv",
+              "spqt_cb2_packed_bytes", "spqt_cb2_quantize", "spqt_cb2_dequantize", "spqt_cb2_gemv"]
 CB_CHUNK_BYTES = 18432
 CB8_CHUNK_BYTES = 17408
+CB2_CHUNK_BYTES = 20480
 
 
 class SpqtError(RuntimeError):
@@ -89,6 +91,10 @@ def lib() -> ctypes.CDLL:
         L.spqt_cb8_quantize.argtypes = [vp, i64, i64, vp, sz]
         L.spqt_cb8_dequantize.argtypes = [vp, i64, i64, vp]
         L.spqt_cb8_gemv.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cb2_packed_bytes.argtypes = [i64, i64, c.POINTER(sz)]
+        L.spqt_cb2_quantize.argtypes = [vp, i64, i64, vp, sz]
+        L.spqt_cb2_dequantize.argtypes = [vp, i64, i64, vp]
+        L.spqt_cb2_gemv.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         for name in EXPORTS[1:] + CB_EXPORTS:
             getattr(L, name).restype = i32
         _lib = L
@@ -459,8 +465,7 @@ def spqt_cb8_dequantize(packed: np.ndarray, M: int, K: int) -> np.ndarray:
 
 def spqt_cb8_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
                   waves: int = 0) -> None:
-    """8-bit column-block GEMV, batch 1 (idx/count None/None for the dense kernel).  Give it a
-    workspace of its own (new_workspace): its contents are laid out for 128-row block-rows."""
+    """8-bit column-block GEMV, batch 1 (idx/count None/None for the dense kernel)."""
     import torch
     pp = _dev(packed, torch.uint8, "packed")
     xp = _dev(x, torch.float16, "x")
@@ -476,3 +481,51 @@ def spqt_cb8_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=No
         wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
     cfg = _cfg(splits, waves, yflags)
     _check(lib().spqt_cb8_gemv(pp, M, K, xp, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
+
+
+# ------------------------------------------------------------------ 2-bit flavour (spqt_colblock.h)
+
+def spqt_cb2_packed_bytes(M: int, K: int) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().spqt_cb2_packed_bytes(M, K, ctypes.byref(out)))
+    return out.value
+
+
+def spqt_cb2_quantize(w: np.ndarray) -> np.ndarray:
+    """fp32 [M, K] -> packed 2-bit column-block bytes (host)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if w.ndim != 2:
+        raise SpqtError("spqt_cb2_quantize: need float32[M, K]")
+    M, K = w.shape
+    out = np.empty(spqt_cb2_packed_bytes(M, K), dtype=np.uint8)
+    _check(lib().spqt_cb2_quantize(_np_ptr(w), M, K, _np_ptr(out), out.nbytes))
+    return out
+
+
+def spqt_cb2_dequantize(packed: np.ndarray, M: int, K: int) -> np.ndarray:
+    p = np.ascontiguousarray(packed, dtype=np.uint8)
+    if p.nbytes < spqt_cb2_packed_bytes(M, K):
+        raise SpqtError("spqt_cb2_dequantize: packed buffer too small")
+    out = np.empty((M, K), dtype=np.float32)
+    _check(lib().spqt_cb2_dequantize(_np_ptr(p), M, K, _np_ptr(out)))
+    return out
+
+
+def spqt_cb2_gemv(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
+                  waves: int = 0) -> None:
+    """2-bit column-block GEMV, batch 1 (idx/count None/None for the dense kernel)."""
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp, yflags = _y_out(y)
+    if x.numel() != K or y.numel() != M or packed.numel() < spqt_cb2_packed_bytes(M, K):
+        raise SpqtError("spqt_cb2_gemv: x / y / packed sizes do not match M, K (batch 1 only)")
+    ip = cp = None
+    if idx is not None:
+        ip = _dev(idx, torch.int32, "idx")
+        cp = _dev(count, torch.int32, "count")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    cfg = _cfg(splits, waves, yflags)
+    _check(lib().spqt_cb2_gemv(pp, M, K, xp, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))

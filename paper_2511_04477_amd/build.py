@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspqt.so")
-SOURCES = ["pack.cpp", "quant_cb.cpp", "gather.hip", "gemv.hip", "gemv_cb.hip", "gemv_cb8.hip", "gemv_list.hip",
+SOURCES = ["pack.cpp", "quant_cb.cpp", "gather.hip", "gemv.hip", "gemv_cb.hip", "gemv_cb8.hip", "gemv_cb2.hip", "gemv_list.hip",
            "gemv_bal.hip"]
 CALIB_LIB = os.path.join(PKG, "libspqt_calib.so")       # benchmark-only helper kernels
 CALIB_SOURCES = ["calib.hip", "baseline_rowmajor.hip"]

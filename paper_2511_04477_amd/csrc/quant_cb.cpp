@@ -381,3 +381,86 @@ extern "C" int spqt_cb8_dequantize(const void *packed, int64_t M, int64_t K, flo
     });
     return SPQT_OK;
 }
+
+// ---- 2-bit flavour: block-rows of 512 rows, four mid-rise levels (c - 1.5) * s ------------------------
+
+namespace {
+
+constexpr int kRows2 = SPQT_CB2_TILE_ROWS;
+constexpr int kBlocks2 = kRows2 / kBlockRows;                    // 16
+constexpr int kScaleBytes2 = kGroup * 2 * kBlocks2;              // 4096
+constexpr int kChunkBytes2 = SPQT_CB2_CHUNK_BYTES;
+static_assert(kChunkBytes2 == kScaleBytes2 + kGroup * (kRows2 / 4), "2-bit chunk size");
+
+inline int64_t tiles2(int64_t M) { return (M + kRows2 - 1) / kRows2; }
+
+}  // namespace
+
+extern "C" int spqt_cb2_packed_bytes(int64_t M, int64_t K, size_t *out_bytes) {
+    if (!out_bytes) return SPQT_EINVAL;
+    if (int rc = check_cb_shape(M, K)) return rc;
+    *out_bytes = (size_t)tiles2(M) * (size_t)(K / kGroup) * (size_t)kChunkBytes2;
+    return SPQT_OK;
+}
+
+extern "C" int spqt_cb2_quantize(const float *w, int64_t M, int64_t K, void *out_packed, size_t out_bytes) {
+    if (!w || !out_packed) return SPQT_EINVAL;
+    size_t need = 0;
+    if (int rc = spqt_cb2_packed_bytes(M, K, &need)) return rc;
+    if (out_bytes < need) return SPQT_ESIZE;
+    const int64_t T = tiles2(M), NC = K / kGroup;
+    uint8_t *out = (uint8_t *)out_packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        for (int64_t c = 0; c < NC; ++c) {
+            uint8_t *chunk = out + (size_t)(t * NC + c) * kChunkBytes2;
+            for (int j = 0; j < kGroup; ++j) {
+                const int64_t k = c * kGroup + j;
+                for (int b = 0; b < kBlocks2; ++b) {
+                    // rows past M count as zero weights
+                    float v[kBlockRows];
+                    float amax = 0.0f;
+                    for (int r = 0; r < kBlockRows; ++r) {
+                        const int64_t m = t * kRows2 + b * kBlockRows + r;
+                        v[r] = m < M ? w[(size_t)m * K + k] : 0.0f;
+                        amax = std::max(amax, std::fabs(v[r]));
+                    }
+                    const uint16_t h = float_to_half_bits(amax / 1.5f);
+                    chunk[32 * j + 2 * b] = (uint8_t)(h & 0xFF);
+                    chunk[32 * j + 2 * b + 1] = (uint8_t)(h >> 8);
+                    const float sc = half_bits_to_float(h);
+                    // four rows to a byte, row 4 i + e in bits 2 e, 2 e + 1
+                    for (int r = 0; r < kBlockRows; r += 4) {
+                        unsigned byte = 0;
+                        for (int e = 0; e < 4; ++e) {
+                            int code = 0;
+                            if (sc > 0.0f) code = (int)std::min(3.0f, std::max(0.0f, std::nearbyintf(v[r + e] / sc + 1.5f)));
+                            byte |= (unsigned)code << (2 * e);
+                        }
+                        chunk[kScaleBytes2 + 128 * j + (b * kBlockRows + r) / 4] = (uint8_t)byte;
+                    }
+                }
+            }
+        }
+    });
+    return SPQT_OK;
+}
+
+extern "C" int spqt_cb2_dequantize(const void *packed, int64_t M, int64_t K, float *w_out) {
+    if (!packed || !w_out) return SPQT_EINVAL;
+    if (int rc = check_cb_shape(M, K)) return rc;
+    const int64_t T = tiles2(M), NC = K / kGroup;
+    const uint8_t *in = (const uint8_t *)packed;
+    for_each_tile_row(T, [=](int64_t t) {
+        for (int64_t c = 0; c < NC; ++c) {
+            const uint8_t *chunk = in + (size_t)(t * NC + c) * kChunkBytes2;
+            for (int j = 0; j < kGroup; ++j)
+                for (int r = 0; r < kRows2 && t * kRows2 + r < M; ++r) {
+                    const int b = r / kBlockRows;
+                    const uint16_t h = (uint16_t)(chunk[32 * j + 2 * b] | (chunk[32 * j + 2 * b + 1] << 8));
+                    const int code = (chunk[kScaleBytes2 + 128 * j + r / 4] >> (2 * (r & 3))) & 3;
+                    w_out[(size_t)(t * kRows2 + r) * K + c * kGroup + j] = ((float)code - 1.5f) * half_bits_to_float(h);
+                }
+        }
+    });
+    return SPQT_OK;
+}

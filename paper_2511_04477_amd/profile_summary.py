@@ -1,7 +1,7 @@
 """Turn the CSV output of a few rocprofv3 runs of bench.py into a short Markdown summary under profiles/
 and refresh profiles/hbm_traffic.txt (the table bench.py reads `roofline.traffic` from).
 
-The runs (on the MI355X machine, from /tmp with TMPDIR=/tmp; W = gate70b, q4096, gate70b_colblock, gate70b_w8):
+The runs (on the MI355X machine, from /tmp with TMPDIR=/tmp; W = gate70b, q4096, gate70b_colblock, gate70b_w8, gate70b_w2):
 
     rocprofv3 --kernel-trace --stats --output-format csv -d D/trace -o kt -- python3 bench.py --trace-pass  > D/trace.log
     rocprofv3 --kernel-trace --stats --output-format csv -d D/kt    -o kt -- python3 bench.py --pmc-pass --pmc-workload W > D/kt.log
@@ -33,7 +33,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 TRAFFIC = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 LAYOUT = {"gate70b": ("group-layout", "spqt_gemv_", 0.515625), "q4096": ("group-layout", "spqt_gemv_", 0.515625),
           "gate70b_colblock": ("column-block", "spqt_cb_gemv_kernel", 0.5625),
-          "gate70b_w8": ("8-bit column-block", "spqt_cb8_gemv_kernel", 1.0625)}
+          "gate70b_w8": ("8-bit column-block", "spqt_cb8_gemv_kernel", 1.0625),
+          "gate70b_w2": ("2-bit column-block", "spqt_cb2_gemv_kernel", 0.3125)}
 
 
 def short(name: str) -> str:
@@ -91,7 +92,7 @@ def main(argv=None) -> int:
     info = info_line(os.path.join(D, "kt.log"), "pmc_pass")
     M, K = info["M"], info["K"]
     L = [f"# rocprofv3 summary: {lay} GEMV kernels on {M} x {K}, 50 % activation sparsity", "",
-         f"Workload: {M} x {K} {'int8' if 'w8' in W else 'int4'}, x ~ Laplace(0,1) fp16, threshold = 50 % quantile, batch 1; "
+         f"Workload: {M} x {K} {'int8' if 'w8' in W else ('2-bit' if 'w2' in W else 'int4')}, x ~ Laplace(0,1) fp16, threshold = 50 % quantile, batch 1; "
          f"{info['launches_per_kernel']} rotated weight copies. Kept bytes per sparse launch: {info['kept_bytes_per_launch']:,.0f}; "
          f"dense bytes: {info['dense_bytes_per_launch']:,.0f}.", "",
          "All commands run on the MI355X box from /tmp with TMPDIR=/tmp; summarized by",

@@ -91,6 +91,13 @@ static void column_blocks(int64_t M, int64_t K) {
     REQUIRE(spqt_cb8_quantize(w.data(), M, K, p8.data(), nb8) == SPQT_OK);
     REQUIRE(spqt_cb8_dequantize(p8.data(), M, K, back.data()) == SPQT_OK);
     for (size_t i = 0; i < back.size(); ++i) REQUIRE(std::isfinite(back[i]));
+    size_t nb2 = 0;
+    REQUIRE(spqt_cb2_packed_bytes(M, K, &nb2) == SPQT_OK);
+    std::vector<uint8_t> p2(nb2);
+    REQUIRE(spqt_cb2_quantize(w.data(), M, K, p2.data(), nb2) == SPQT_OK);
+    REQUIRE(spqt_cb2_quantize(w.data(), M, K, p2.data(), nb2 - 1) == SPQT_ESIZE);
+    REQUIRE(spqt_cb2_dequantize(p2.data(), M, K, back.data()) == SPQT_OK);
+    for (size_t i = 0; i < back.size(); ++i) REQUIRE(std::isfinite(back[i]));
 }
 
 int main() {

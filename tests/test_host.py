@@ -117,6 +117,28 @@ def test_eight_bit_quantizer_matches_oracle_bit_exact(M, K):
     assert back.shape == (M, K) and np.array_equal(back.astype(np.float64), c8.dequant(q, s)[:M])
 
 
+@pytest.mark.parametrize("M,K", [(512, 128), (1024, 384), (700, 256), (1, 128), (33, 128)])
+def test_two_bit_quantizer_matches_oracle_bit_exact(M, K):
+    """2-bit flavour: every scale bit and every code of the library's quantizer equals the oracle's
+    (independent NumPy code, same fp32 rule), also on a ragged M (missing rows count as zero weights);
+    the library's dequantizer gives the oracle's values."""
+    from oracle import colblock_w2 as c2
+    from workloads import make_fp_weights
+    W = make_fp_weights(512 * ((M + 511) // 512), K, 720 + M + K)[:M].copy()
+    if M >= 128:
+        W[0:32, 3] = 0.0                      # an all-zero block
+        W[32:64, 7] = np.float32(1e-9)        # a block whose scale underflows to zero
+        W[64:96, 11] = [(-1) ** r * 0.25 * (r % 7) for r in range(32)]    # max 1.5 -> scale 1: exact ties at 0, +-1
+        W[96:128, 13] = [1.5, -1.5] + [0.0, 1.0, -1.0, 0.5, -0.5] * 6     # every decision boundary of the four levels
+    got = spqt.spqt_cb2_quantize(W)
+    c, s = c2.quantize(c2.pad_rows(W))
+    want = c2.pack(c, s)
+    assert got.nbytes == want.nbytes == spqt.spqt_cb2_packed_bytes(M, K) == ((M + 511) // 512) * (K // 128) * spqt.CB2_CHUNK_BYTES
+    assert np.array_equal(got, want)
+    back = spqt.spqt_cb2_dequantize(got, M, K)
+    assert back.shape == (M, K) and np.array_equal(back.astype(np.float64), c2.dequant(c, s)[:M])
+
+
 def test_colblock_bad_arguments():
     L = spqt.lib()
     out = ctypes.c_size_t()
@@ -146,6 +168,17 @@ def test_colblock_bad_arguments():
     assert L.spqt_cb8_gemv(128, 256, 100, 16, None, None, 16, None, 0, None, None) == -2
     assert L.spqt_cb8_gemv(64, 256, 128, 16, None, None, 16, None, 0, None, None) == -3
     assert L.spqt_cb8_gemv(128, 256, 128, 16, 16, None, 16, None, 0, None, None) == -1   # idx without count
+    assert L.spqt_cb2_packed_bytes(512, 100, ctypes.byref(out)) == -2
+    assert L.spqt_cb2_packed_bytes(512, 128, None) == -1
+    assert L.spqt_cb2_quantize(vp(w), 256, 128, vp(small), small.nbytes) == -4
+    assert L.spqt_cb2_quantize(None, 256, 128, vp(small), small.nbytes) == -1
+    assert L.spqt_cb2_dequantize(None, 256, 128, vp(w)) == -1
+    assert L.spqt_cb2_gemv(None, 256, 128, 16, None, None, 16, None, 0, None, None) == -1
+    assert L.spqt_cb2_gemv(128, 256, 100, 16, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb2_gemv(64, 256, 128, 16, None, None, 16, None, 0, None, None) == -3
+    assert L.spqt_cb2_gemv(128, 256, 128, 16, 16, None, 16, None, 0, None, None) == -1   # idx without count
+    cfg = spqt.LaunchCfg(17, 4, 0)
+    assert L.spqt_cb2_gemv(128, 256, 128, 16, None, None, 16, None, 0, None, ctypes.byref(cfg)) == -1   # more than 16 splits
 
 
 def test_status_strings():
