@@ -178,9 +178,11 @@ def other_width_rows(torch, spqt, use_graph, cpu, bits):
     if bits == 8:
         tile_rows, chunk_bytes, seed = 128, spqt.CB8_CHUNK_BYTES, 9100
         packed_bytes, quantize, gemv, reference = spqt.spqt_cb8_packed_bytes, spqt.spqt_cb8_quantize, spqt.spqt_cb8_gemv, cpu.colblock_w8
+        one_launch = spqt.spqt_cb8_gemv_fused
     else:
         tile_rows, chunk_bytes, seed = 512, spqt.CB2_CHUNK_BYTES, 9200
         packed_bytes, quantize, gemv, reference = spqt.spqt_cb2_packed_bytes, spqt.spqt_cb2_quantize, spqt.spqt_cb2_gemv, cpu.colblock_w2
+        one_launch = spqt.spqt_cb2_gemv_fused
     scale_bytes = 128 * 2 * (tile_rows // 32)
     rows = []
     for M, K in ((4096, 4096), (28672, 8192)):
@@ -214,13 +216,19 @@ def other_width_rows(torch, spqt, use_graph, cpu, bits):
             y.fill_(float("nan"))
             gemv(packed[0], M, K, x, idx, cnt, y, ws)
             torch.cuda.synchronize()
-            if not cpu.close(y.cpu().numpy()[sample], reference(W0_sample, x_np, thr))[0]:
+            want = reference(W0_sample, x_np, thr)
+            ok = cpu.close(y.cpu().numpy()[sample], want)[0]
+            y.fill_(float("nan"))
+            one_launch(packed[0], M, K, x, thr, y, ws)
+            torch.cuda.synchronize()
+            if not (ok and cpu.close(y.cpu().numpy()[sample], want)[0]):
                 print(f"bench.py: {bits}-bit column-block parity check FAILED ({M}x{K})", file=sys.stderr)
                 sys.exit(1)
         fns = {"us_gemv": lambda i: gemv(packed[i], M, K, x, idx, cnt, y, ws),
                "us_dense": lambda i: gemv(packed[i], M, K, x, None, None, y, ws),
                "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
-                                                 gemv(packed[i], M, K, x, idx, cnt, y, ws))}
+                                                 gemv(packed[i], M, K, x, idx, cnt, y, ws)),
+               "us_one_launch": lambda i: one_launch(packed[i], M, K, x, thr, y, ws)}
         t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
         kept = n * (M * bits // 8 + M // 16)
         rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(n / K, 4), "bits_per_weight": bits + 0.5,

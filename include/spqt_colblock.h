@@ -129,6 +129,11 @@ int spqt_cb8_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 int spqt_cb8_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
                   const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                   void *stream, const spqt_launch_cfg *cfg);
+/* DEVICE, async.  As spqt_cb_gemv_fused (gather and GEMV in one launch, batch 1: the sparsity test of
+ * Section 2 runs inside the kernel on static 64-column ranges), on spqt_cb8_quantize's output. */
+int spqt_cb8_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, float threshold,
+                        void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
+                        const spqt_launch_cfg *cfg);
 
 /* ---- 2-bit flavour of the column-block layout ("ZZ-CB32-W2") --------------------------------
  * Section 4.1.3 names 2 to 8 bits as the widths the layout carries over to and gives no format.  This
@@ -157,6 +162,11 @@ int spqt_cb2_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 int spqt_cb2_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
                   const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                   void *stream, const spqt_launch_cfg *cfg);
+/* DEVICE, async.  As spqt_cb_gemv_fused (gather and GEMV in one launch, batch 1), on spqt_cb2_quantize's
+ * output; cfg as for spqt_cb2_gemv. */
+int spqt_cb2_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, float threshold,
+                        void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
+                        const spqt_launch_cfg *cfg);
 
 #ifdef __cplusplus
 }

@@ -209,3 +209,54 @@ def test_cb2_full_size_sampled_tiles_and_repeat(gpu):
         rows = slice(512 * t, 512 * t + 512)
         c, s = c2.quantize(W[rows])
         assert_close(yd.cpu().numpy()[None, rows], c2.gemv(c, s, x, 0.0), f"dense block-row {t}")
+
+
+def run_one_launch(gpu, packed_np, M, K, x_np, thr, splits=0, waves=0, half=False):
+    torch, spqt, dev = gpu
+    packed = torch.from_numpy(packed_np).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)[0]
+    buf = torch.full((M + 256,), 321.0, dtype=torch.float16 if half else torch.float32, device=dev)
+    y = buf[128:128 + M]
+    spqt.spqt_cb2_gemv_fused(packed, M, K, x, thr, y, spqt.new_workspace(M, K), splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert np.all(out[:128] == 321.0) and np.all(out[128 + M:] == 321.0), "write outside y"
+    return out[128:128 + M][None, :]
+
+
+@pytest.mark.parametrize("M,K", [(512, 128), (1024, 1024), (2048, 4096), (1, 256), (300, 1024), (1536, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (2, 4), (7, 2), (16, 4)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_cb2_one_launch(gpu, M, K, splits, waves, sparsity):
+    """Gather and GEMV in one launch: the oracle's y for the same threshold (no list exists to compare)."""
+    import paper_2511_04477_amd as spqt
+    W = make_fp_weights(512 * ((M + 511) // 512), K, 9002 + M + K)[:M].copy()
+    x = make_x(K, "laplace", 9102 + M + K)
+    thr = quantile_threshold(x, sparsity) if sparsity < 1.0 else float("inf")
+    say(f"cb2 one launch M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    q, s = c2.quantize(c2.pad_rows(W))
+    ref = c2.gemv(q, s, x, thr)[:, :M]
+    got = run_one_launch(gpu, spqt.spqt_cb2_quantize(W), M, K, x, thr, splits=splits, waves=waves)
+    assert_close(got, ref, "cb2 one launch")
+
+
+def test_cb2_one_launch_clustered_ties_and_fp16(gpu):
+    """Kept columns all in one corner of x (whole units empty), entries equal to the threshold (kept), fp16 y."""
+    import paper_2511_04477_amd as spqt
+    M, K = 1536, 1024
+    W = make_fp_weights(M, K, 9302)
+    x = np.zeros((1, K), dtype=np.float16)
+    rng = np.random.default_rng(9402)
+    x[0, 640:768] = rng.standard_normal(128).astype(np.float16)
+    x[0, 5] = 0.5
+    x[0, 1023] = -0.5
+    thr = 0.5
+    q, s = c2.quantize(W)
+    ref = c2.gemv(q, s, x, thr)
+    assert c2.keep_mask(x, thr)[5] and c2.keep_mask(x, thr)[1023]
+    say("cb2 one launch clustered")
+    packed = spqt.spqt_cb2_quantize(W)
+    got = run_one_launch(gpu, packed, M, K, x, thr, splits=4, waves=4)
+    assert_close(got, ref, "clustered")
+    h = run_one_launch(gpu, packed, M, K, x, thr, splits=4, waves=4, half=True)
+    assert np.array_equal(h.view(np.uint16), got.astype(np.float16).view(np.uint16))

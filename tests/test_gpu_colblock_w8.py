@@ -142,3 +142,54 @@ def test_cb8_full_size_sampled_tiles_and_repeat(gpu):
         rows = slice(128 * t, 128 * t + 128)
         q, s = c8.quantize(W[rows])
         assert_close(first[None, rows], c8.gemv(q, s, x, thr), f"block-row {t}")
+
+
+def run_one_launch(gpu, packed_np, M, K, x_np, thr, splits=0, waves=0, half=False):
+    torch, spqt, dev = gpu
+    packed = torch.from_numpy(packed_np).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)[0]
+    buf = torch.full((M + 256,), 321.0, dtype=torch.float16 if half else torch.float32, device=dev)
+    y = buf[128:128 + M]
+    spqt.spqt_cb8_gemv_fused(packed, M, K, x, thr, y, spqt.new_workspace(M, K), splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert np.all(out[:128] == 321.0) and np.all(out[128 + M:] == 321.0), "write outside y"
+    return out[128:128 + M][None, :]
+
+
+@pytest.mark.parametrize("M,K", [(128, 128), (512, 1024), (1024, 4096), (1, 256), (300, 1024), (2048, 1152)])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (2, 4), (7, 2), (16, 4)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9, 1.0])
+def test_cb8_one_launch(gpu, M, K, splits, waves, sparsity):
+    """Gather and GEMV in one launch: the oracle's y for the same threshold (no list exists to compare)."""
+    import paper_2511_04477_amd as spqt
+    W = make_fp_weights(128 * ((M + 127) // 128), K, 9008 + M + K)[:M].copy()
+    x = make_x(K, "laplace", 9108 + M + K)
+    thr = quantile_threshold(x, sparsity) if sparsity < 1.0 else float("inf")
+    say(f"cb8 one launch M={M} K={K} splits={splits} waves={waves} s={sparsity}")
+    q, s = c8.quantize(c8.pad_rows(W))
+    ref = c8.gemv(q, s, x, thr)[:, :M]
+    got = run_one_launch(gpu, spqt.spqt_cb8_quantize(W), M, K, x, thr, splits=splits, waves=waves)
+    assert_close(got, ref, "cb8 one launch")
+
+
+def test_cb8_one_launch_clustered_ties_and_fp16(gpu):
+    """Kept columns all in one corner of x (whole units empty), entries equal to the threshold (kept), fp16 y."""
+    import paper_2511_04477_amd as spqt
+    M, K = 384, 1024
+    W = make_fp_weights(M, K, 9308)
+    x = np.zeros((1, K), dtype=np.float16)
+    rng = np.random.default_rng(9408)
+    x[0, 640:768] = rng.standard_normal(128).astype(np.float16)
+    x[0, 5] = 0.5
+    x[0, 1023] = -0.5
+    thr = 0.5
+    q, s = c8.quantize(W)
+    ref = c8.gemv(q, s, x, thr)
+    assert c8.keep_mask(x, thr)[5] and c8.keep_mask(x, thr)[1023]
+    say("cb8 one launch clustered")
+    packed = spqt.spqt_cb8_quantize(W)
+    got = run_one_launch(gpu, packed, M, K, x, thr, splits=4, waves=4)
+    assert_close(got, ref, "clustered")
+    h = run_one_launch(gpu, packed, M, K, x, thr, splits=4, waves=4, half=True)
+    assert np.array_equal(h.view(np.uint16), got.astype(np.float16).view(np.uint16))
