@@ -178,11 +178,11 @@ def other_width_rows(torch, spqt, use_graph, cpu, bits):
     if bits == 8:
         tile_rows, chunk_bytes, seed = 128, spqt.CB8_CHUNK_BYTES, 9100
         packed_bytes, quantize, gemv, reference = spqt.spqt_cb8_packed_bytes, spqt.spqt_cb8_quantize, spqt.spqt_cb8_gemv, cpu.colblock_w8
-        one_launch = spqt.spqt_cb8_gemv_fused
+        one_launch, rows_fn = spqt.spqt_cb8_gemv_fused, spqt.spqt_cb8_gemv_rows
     else:
         tile_rows, chunk_bytes, seed = 512, spqt.CB2_CHUNK_BYTES, 9200
         packed_bytes, quantize, gemv, reference = spqt.spqt_cb2_packed_bytes, spqt.spqt_cb2_quantize, spqt.spqt_cb2_gemv, cpu.colblock_w2
-        one_launch = spqt.spqt_cb2_gemv_fused
+        one_launch, rows_fn = spqt.spqt_cb2_gemv_fused, spqt.spqt_cb2_gemv_rows
     scale_bytes = 128 * 2 * (tile_rows // 32)
     rows = []
     for M, K in ((4096, 4096), (28672, 8192)):
@@ -229,6 +229,15 @@ def other_width_rows(torch, spqt, use_graph, cpu, bits):
                "us_gather_plus_gemv": lambda i: (spqt.spqt_gather(x, thr, idx, cnt),
                                                  gemv(packed[i], M, K, x, idx, cnt, y, ws)),
                "us_one_launch": lambda i: one_launch(packed[i], M, K, x, thr, y, ws)}
+        # two activation rows on the union of their kept columns (each row 50 %: the union keeps about 75 %)
+        x2_np = np.concatenate([x_np, make_x(K, "laplace", seed + 3 + M)], axis=0)
+        x2 = torch.from_numpy(x2_np).to(dev)
+        idx2 = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt2 = torch.zeros(1, dtype=torch.int32, device=dev)
+        y2 = torch.empty(2 * M, dtype=torch.float32, device=dev)
+        ws2 = spqt.new_workspace(M, K, 2)
+        spqt.spqt_gather(x2, thr, idx2, cnt2)
+        fns["us_two_rows_union"] = lambda i: rows_fn(packed[i], M, K, x2, idx2, cnt2, y2, ws2)
         t = {k: time_sequence(torch, f, copies, max(copies * 4, 800), copies, use_graph) for k, f in fns.items()}
         kept = n * (M * bits // 8 + M // 16)
         rows.append({"M": M, "K": K, "sparsity": 0.5, "kept_frac": round(n / K, 4), "bits_per_weight": bits + 0.5,

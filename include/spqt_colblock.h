@@ -129,6 +129,12 @@ int spqt_cb8_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 int spqt_cb8_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
                   const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                   void *stream, const spqt_launch_cfg *cfg);
+/* DEVICE, async.  As spqt_cb_gemv for 1..SPQT_MAX_BATCH activation rows (Section 3.3: small beams) that share
+ * the union index list and one pass over the weights: x_dev fp16[batch][K], y_dev [batch][M], workspace of
+ * spqt_workspace_bytes(M, K, batch). */
+int spqt_cb8_gemv_rows(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
+                       const int32_t *idx_dev, const int32_t *count_dev, void *y_dev, void *workspace_dev,
+                       size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg);
 /* DEVICE, async.  As spqt_cb_gemv_fused (gather and GEMV in one launch, batch 1: the sparsity test of
  * Section 2 runs inside the kernel on static 64-column ranges), on spqt_cb8_quantize's output. */
 int spqt_cb8_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, float threshold,
@@ -150,6 +156,7 @@ int spqt_cb8_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void
  * block-row are quantized as zero weights (code 0 under a zero scale) and never written back. */
 #define SPQT_CB2_TILE_ROWS 512
 #define SPQT_CB2_CHUNK_BYTES 20480
+#define SPQT_CB2_MAX_BATCH 3
 int spqt_cb2_packed_bytes(int64_t M, int64_t K, size_t *out_bytes);
 /* HOST, offline.  As spqt_cb_quantize, by the 2-bit rule above. */
 int spqt_cb2_quantize(const float *w_rowmajor, int64_t M, int64_t K, void *out_packed, size_t out_bytes);
@@ -162,6 +169,11 @@ int spqt_cb2_dequantize(const void *packed, int64_t M, int64_t K, float *w_out);
 int spqt_cb2_gemv(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
                   const int32_t *count_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
                   void *stream, const spqt_launch_cfg *cfg);
+/* DEVICE, async.  As spqt_cb8_gemv_rows, for 1..SPQT_CB2_MAX_BATCH activation rows (SPQT_ESHAPE beyond: a lane
+ * keeps 64 accumulators per row); cfg as for spqt_cb2_gemv. */
+int spqt_cb2_gemv_rows(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
+                       const int32_t *idx_dev, const int32_t *count_dev, void *y_dev, void *workspace_dev,
+                       size_t workspace_bytes, void *stream, const spqt_launch_cfg *cfg);
 /* DEVICE, async.  As spqt_cb_gemv_fused (gather and GEMV in one launch, batch 1), on spqt_cb2_quantize's
  * output; cfg as for spqt_cb2_gemv. */
 int spqt_cb2_gemv_fused(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, float threshold,

@@ -34,8 +34,8 @@ EXPORTS = [
 
 CB_EXPORTS = ["spqt_cb_packed_bytes", "spqt_cb_quantize", "spqt_cb_dequantize", "spqt_cb_gemv",
               "spqt_cb_gemv_fused", "spqt_cbk_quantize", "spqt_cbk_dequantize", "spqt_cbk_gemv", "spqt_cbk_gemv_fused",
-              "spqt_cb8_packed_bytes", "spqt_cb8_quantize", "spqt_cb8_dequantize", "spqt_cb8_gemv", "spqt_cb8_gemv_fused",
-              "spqt_cb2_packed_bytes", "spqt_cb2_quantize", "spqt_cb2_dequantize", "spqt_cb2_gemv", "spqt_cb2_gemv_fused"]
+              "spqt_cb8_packed_bytes", "spqt_cb8_quantize", "spqt_cb8_dequantize", "spqt_cb8_gemv", "spqt_cb8_gemv_fused", "spqt_cb8_gemv_rows",
+              "spqt_cb2_packed_bytes", "spqt_cb2_quantize", "spqt_cb2_dequantize", "spqt_cb2_gemv", "spqt_cb2_gemv_fused", "spqt_cb2_gemv_rows"]
 CB_CHUNK_BYTES = 18432
 CB8_CHUNK_BYTES = 17408
 CB2_CHUNK_BYTES = 20480
@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
         L.spqt_cb2_quantize.argtypes = [vp, i64, i64, vp, sz]
         L.spqt_cb2_dequantize.argtypes = [vp, i64, i64, vp]
         L.spqt_cb2_gemv.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cb8_gemv_rows.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
+        L.spqt_cb2_gemv_rows.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_cb8_gemv_fused.argtypes = [vp, i64, i64, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         L.spqt_cb2_gemv_fused.argtypes = [vp, i64, i64, vp, c.c_float, vp, vp, sz, vp, c.POINTER(LaunchCfg)]
         for name in EXPORTS[1:] + CB_EXPORTS:
@@ -557,3 +559,34 @@ def spqt_cb2_gemv_fused(packed, M: int, K: int, x, threshold: float, y, workspac
                         waves: int = 0) -> None:
     """2-bit column-block gather + GEMV in one launch, batch 1."""
     _width_fused("spqt_cb2_gemv_fused", spqt_cb2_packed_bytes, packed, M, K, x, threshold, y, workspace, stream, splits, waves)
+
+
+def _width_rows(fn_name, bytes_fn, packed, M, K, x, idx, count, y, workspace, stream, splits, waves):
+    import torch
+    pp = _dev(packed, torch.uint8, "packed")
+    xp = _dev(x, torch.float16, "x")
+    yp, yflags = _y_out(y)
+    batch = x.numel() // K
+    if x.numel() != batch * K or y.numel() != batch * M or packed.numel() < bytes_fn(M, K):
+        raise SpqtError(f"{fn_name}: x / y / packed sizes do not match M, K")
+    ip = cp = None
+    if idx is not None:
+        ip = _dev(idx, torch.int32, "idx")
+        cp = _dev(count, torch.int32, "count")
+    wp, wbytes = None, 0
+    if workspace is not None:
+        wp, wbytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+    cfg = _cfg(splits, waves, yflags)
+    _check(getattr(lib(), fn_name)(pp, M, K, xp, batch, ip, cp, yp, wp, wbytes, _stream_ptr(stream), ctypes.byref(cfg)))
+
+
+def spqt_cb8_gemv_rows(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
+                       waves: int = 0) -> None:
+    """8-bit column-block GEMV for x fp16[batch][K], batch 1..4, on the union list (or dense)."""
+    _width_rows("spqt_cb8_gemv_rows", spqt_cb8_packed_bytes, packed, M, K, x, idx, count, y, workspace, stream, splits, waves)
+
+
+def spqt_cb2_gemv_rows(packed, M: int, K: int, x, idx, count, y, workspace, stream=None, splits: int = 0,
+                       waves: int = 0) -> None:
+    """2-bit column-block GEMV for x fp16[batch][K], batch 1..3, on the union list (or dense)."""
+    _width_rows("spqt_cb2_gemv_rows", spqt_cb2_packed_bytes, packed, M, K, x, idx, count, y, workspace, stream, splits, waves)

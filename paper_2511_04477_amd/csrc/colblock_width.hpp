@@ -8,10 +8,12 @@
 // Everything else follows spqt_cb_gemv_kernel: even split of the index list over the S x WAVES
 // wavefronts of a block-row (Section 4.2.3), the scales folded into x by the lane that owns the list
 // entry, two-stage software pipeline with unpredicated clamped loads, one fold of the 8 column-lanes at
-// the end, reduction through LDS and the tagged-word exchange.  One activation row; three modes:
-// list-driven, dense (every column, no list), and ONE-LAUNCH (FUSED): the kernel applies the sparsity test
-// of Section 2 itself on static 64-column units - lane l tests column 64 u + l, a ballot gives the kept
-// set, mbcnt the rank, and the kept columns are staged in rank order - so no index list exists.
+// the end, reduction through LDS and the tagged-word exchange.  Three modes: list-driven, dense (every
+// column, no list), and ONE-LAUNCH (FUSED, one activation row): the kernel applies the sparsity test of
+// Section 2 itself on static 64-column units - lane l tests column 64 u + l, a ballot gives the kept set,
+// mbcnt the rank, and the kept columns are staged in rank order - so no index list exists.
+// BATCH activation rows (Section 3.3: small beams) share the union index list and ONE pass over the
+// weights; every row has its own staged products, accumulators and offset sums.
 //
 // A format type F provides
 //   kRows, kBlocks            rows of a block-row, 32-row blocks in it (one fp16 scale each per column)
@@ -29,14 +31,15 @@
 
 namespace spqt {
 
-template <class F, int WAVES, bool DENSE, bool FUSED>
+template <class F, int WAVES, bool DENSE, bool FUSED, int BATCH = 1>
 __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x,
                                                     const int32_t *__restrict__ idx, const int32_t *__restrict__ count,
                                                     float *__restrict__ y, void *partials, int32_t *ws_flags, int K, int NC,
                                                     int S, int T, int M, float thr) {
     __shared__ uint32_t stage_off[WAVES][kPassCols];                                          // byte offset of each column
-    __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][kPassCols][F::kBlocks];     // x * scale per block
-    __shared__ __attribute__((aligned(16))) float red[WAVES][1][F::kRows];
+    static_assert(!FUSED || BATCH == 1, "the one-launch mode takes one activation row");
+    __shared__ __attribute__((aligned(16))) float stage_xs[WAVES][BATCH][kPassCols][F::kBlocks];   // x * scale per block
+    __shared__ __attribute__((aligned(16))) float red[WAVES][BATCH][F::kRows];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -62,10 +65,14 @@ __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ 
 
     const uint8_t *row_base = packed + (size_t)t * NC * F::kChunkBytes;
 
-    float acc[F::kAcc];
-    typename F::Sums bs = F::zero_sums();
+    float acc[BATCH][F::kAcc];
+    typename F::Sums bs[BATCH];
 #pragma unroll
-    for (int i = 0; i < F::kAcc; ++i) acc[i] = 0.0f;
+    for (int b = 0; b < BATCH; ++b) {
+        bs[b] = F::zero_sums();
+#pragma unroll
+        for (int i = 0; i < F::kAcc; ++i) acc[b][i] = 0.0f;
+    }
 
     if (pos < end) {
         // The weights of the 64 staged columns: 8 loads of 8 columns each.
@@ -79,16 +86,27 @@ __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ 
         };
         // MULTIPLY stage: the lane that owns entry `ent` stages the products x * s_b of its column
         // (xf = 0 for a filler entry); every lane then reads the products of its own block(s).
-        auto multiply = [&](int n, float xf, int ent, typename F::Scales sv, const u32x4(&w)[8]) {
-            F::stage(xf, sv, stage_xs[wave][ent]);
+        auto multiply = [&](int n, const float(&xf)[BATCH], int ent, typename F::Scales sv, const u32x4(&w)[8]) {
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) F::stage(xf[b], sv, stage_xs[wave][b][ent]);
             __builtin_amdgcn_wave_barrier();
-            typename F::Mine xl[8];
+            if (BATCH == 1) {
+                typename F::Mine xl[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) xl[u] = F::read_mine(stage_xs[wave][u * 8 + cg], seg);
-            F::step(w[0], xl[0], acc, bs);
+                for (int u = 0; u < 8; ++u) xl[u] = F::read_mine(stage_xs[wave][0][u * 8 + cg], seg);
+                F::step(w[0], xl[0], acc[0], bs[0]);
 #pragma unroll
-            for (int u = 1; u < 8; ++u)
-                if (u * 8 < n) F::step(w[u], xl[u], acc, bs);
+                for (int u = 1; u < 8; ++u)
+                    if (u * 8 < n) F::step(w[u], xl[u], acc[0], bs[0]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (u == 0 || u * 8 < n) {
+#pragma unroll
+                        for (int b = 0; b < BATCH; ++b)
+                            F::step(w[u], F::read_mine(stage_xs[wave][b][u * 8 + cg], seg), acc[b], bs[b]);
+                    }
+            }
             __builtin_amdgcn_wave_barrier();
         };
 
@@ -100,7 +118,7 @@ __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ 
             // threshold, rank, stage the offsets, request the next unit's x, this unit's scales (every
             // lane its own column's) and weights.  Kept columns go to entries 0..n-1 in ascending order;
             // the other lanes fill entries n..63 with the unit's first kept column and x = 0.
-            auto fetch_unit = [&](uint32_t xr, int u, u32x4(&w)[8], int &n_out, float &xf_out, int &ent_out,
+            auto fetch_unit = [&](uint32_t xr, int u, u32x4(&w)[8], int &n_out, float(&xf_out)[BATCH], int &ent_out,
                                   typename F::Scales &sv_out, uint32_t &xr_next) {
                 const bool any = u < end;
                 const float xv = half_bits_to_float(xr);
@@ -123,10 +141,10 @@ __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ 
                 __builtin_amdgcn_wave_barrier();
                 load_weights(w);
                 n_out = n;
-                xf_out = keep ? xv : 0.0f;
+                xf_out[0] = keep ? xv : 0.0f;
                 ent_out = entry;
             };
-            float xfA, xfB;
+            float xfA[BATCH], xfB[BATCH];
             int entA, entB;
             uint32_t xa = x[pos * kPassCols + lane], xb;
             fetch_unit(xa, pos, wA, nA, xfA, entA, svA, xb);
@@ -149,7 +167,7 @@ __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ 
             };
             // FETCH stage of the pass at list position p: the next pass's entries, this pass's x, scales
             // and weights.  Lanes past the pass point at its first column and later carry x = 0.
-            auto fetch = [&](int kk, int p, u32x4(&w)[8], int &n_out, uint32_t &xraw_out, typename F::Scales &sv_out,
+            auto fetch = [&](int kk, int p, u32x4(&w)[8], int &n_out, uint32_t(&xraw_out)[BATCH], typename F::Scales &sv_out,
                              int &k_after) {
                 const int left = end - p;
                 const int n = left < 0 ? 0 : (left < kPassCols ? left : kPassCols);
@@ -158,17 +176,21 @@ __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ 
                 const int kc = lane < n ? kk : k_first;
                 const uint32_t chunk_off = (uint32_t)(kc >> 7) * (uint32_t)F::kChunkBytes;
                 const uint32_t col = (uint32_t)(kc & (kGroup - 1));
-                xraw_out = x[kc];
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) xraw_out[b] = x[(size_t)b * K + kc];
                 sv_out = F::load_scales(row_base + (size_t)(chunk_off + col * (uint32_t)(2 * F::kBlocks)));
                 stage_off[wave][lane] = chunk_off + (uint32_t)F::kScaleBytes + col * 128u;
                 __builtin_amdgcn_wave_barrier();
                 load_weights(w);
                 n_out = n;
             };
-            auto multiply_list = [&](int n, uint32_t xraw, typename F::Scales sv, const u32x4(&w)[8]) {
-                multiply(n, lane < n ? half_bits_to_float(xraw) : 0.0f, lane, sv, w);
+            auto multiply_list = [&](int n, const uint32_t(&xraw)[BATCH], typename F::Scales sv, const u32x4(&w)[8]) {
+                float xf[BATCH];
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) xf[b] = lane < n ? half_bits_to_float(xraw[b]) : 0.0f;
+                multiply(n, xf, lane, sv, w);
             };
-            uint32_t xrA, xrB;
+            uint32_t xrA[BATCH], xrB[BATCH];
             int kA, kB;
             kA = fetch_k(pos);
             fetch(kA, pos, wA, nA, xrA, svA, kB);
@@ -190,20 +212,22 @@ __device__ __forceinline__ void colblock_width_gemv(const uint8_t *__restrict__ 
         }
     }
 
-    F::finish(acc, bs, seg, cgr, red[wave][0]);
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) F::finish(acc[b], bs[b], seg, cgr, red[wave][b]);
     __syncthreads();
-    combine_block_row<WAVES, 1, F::kRows>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
+    combine_block_row<WAVES, BATCH, F::kRows>(&red[0][0][0], tid, t, s, S, partials, ws_flags, y, M);
 }
 
 // Host side shared by the entry points: argument checks, launch shape, workspace, grid.  `launch` starts the
-// kernel for (waves, mode) with mode 0 = index list, 1 = dense, 2 = one launch.
+// kernel for (waves, mode) with mode 0 = index list, 1 = dense, 2 = one launch (batch 1 only).
 template <class F, class Launch>
-int colblock_width_run(int mode, int max_splits, int default_splits, const void *packed_dev, int64_t M, int64_t K,
+int colblock_width_run(int mode, int batch, int max_splits, int default_splits, const void *packed_dev, int64_t M, int64_t K,
                        const void *x_dev, const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                        void *workspace_dev, size_t workspace_bytes, const spqt_launch_cfg *cfg, Launch launch) {
     if (!packed_dev || !x_dev || !y_dev) return SPQT_EINVAL;
     if (mode == 0 && !count_dev) return SPQT_EINVAL;
     if (int rc = check_shape(M, K, kGroup)) return rc;
+    if (batch < 1 || batch > SPQT_MAX_BATCH || (mode == 2 && batch != 1)) return SPQT_ESHAPE;
     if (cfg && (cfg->flags & ~SPQT_CFG_Y_FP16)) return SPQT_EINVAL;
     const int y_half = cfg && (cfg->flags & SPQT_CFG_Y_FP16) ? 1 : 0;
     if ((uintptr_t)packed_dev % 128 != 0 || (uintptr_t)x_dev % 2 != 0 || (uintptr_t)y_dev % (y_half ? 2 : 4) != 0)
@@ -217,7 +241,7 @@ int colblock_width_run(int mode, int max_splits, int default_splits, const void 
     if (S < 1 || S > max_splits) return SPQT_EINVAL;
     if (waves != 1 && waves != 2 && waves != 4) return SPQT_EINVAL;
     size_t need = 0;
-    spqt_workspace_bytes(M, K, 1, &need);
+    spqt_workspace_bytes(M, K, batch, &need);
     void *partials = nullptr;
     int32_t *ws_flags = nullptr;
     if (S > 1) {

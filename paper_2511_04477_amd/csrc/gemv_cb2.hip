@@ -1,4 +1,4 @@
-// spqt_cb2_gemv, spqt_cb2_gemv_fused: the column-block GEMV for 2-bit codes ("ZZ-CB32-W2", spqt_colblock.h).
+// spqt_cb2_gemv, spqt_cb2_gemv_rows, spqt_cb2_gemv_fused: the column-block GEMV for 2-bit codes ("ZZ-CB32-W2", spqt_colblock.h).
 //
 // Paper Section 4.1.3 states that the column-wise layout carries over to other bit-widths, 2 to 8 bits.
 // The kernel body is the one all widths other than 4 share (colblock_width.hpp); this file holds what
@@ -25,6 +25,7 @@ using namespace spqt;
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kMaxSplits2 = 16;                            // keeps the exchange words inside spqt_workspace_bytes
+constexpr int kMaxRows2 = SPQT_CB2_MAX_BATCH;              // activation rows spqt_cb2_gemv_rows takes
 
 struct W2 {
     static constexpr int kRows = SPQT_CB2_TILE_ROWS;           // 512 rows per block-row
@@ -106,23 +107,40 @@ struct W2 {
 };
 static_assert(W2::kChunkBytes == W2::kScaleBytes + kGroup * 128, "chunk size");
 
-template <int WAVES, bool DENSE, bool FUSED>
+template <int WAVES, bool DENSE, bool FUSED, int BATCH>
 __global__ __launch_bounds__(WAVES * 64) void spqt_cb2_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ count, float *__restrict__ y, void *partials, int32_t *ws_flags, int K, int NC, int S,
     int T, int M, float thr) {
-    colblock_width_gemv<W2, WAVES, DENSE, FUSED>(packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, thr);
+    colblock_width_gemv<W2, WAVES, DENSE, FUSED, BATCH>(packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, thr);
 }
 
-#define SPQT_CB2_LAUNCH(W, D, F)                                                                                      \
-    hipLaunchKernelGGL((spqt_cb2_gemv_kernel<W, D, F>), dim3(grid), dim3(W * 64), 0, st, pk, xp, idx_dev, count_dev, \
+#define SPQT_CB2_LAUNCH(W, D, F, B)                                                                                \
+    hipLaunchKernelGGL((spqt_cb2_gemv_kernel<W, D, F, B>), dim3(grid), dim3(W * 64), 0, st, pk, xp, idx_dev, count_dev, \
                        (float *)y_dev, partials, ws_flags, (int)K, NC, S, T, m_and_flags, thr)
+// mode 0 = index list, 1 = dense, 2 = one launch (one activation row)
+#define SPQT_CB2_MODES(W, B)                                   \
+    do {                                                         \
+        if (md == 0) SPQT_CB2_LAUNCH(W, false, false, B);          \
+        else if (md == 1) SPQT_CB2_LAUNCH(W, true, false, B);      \
+        else SPQT_CB2_LAUNCH(W, false, true, 1);                   \
+    } while (0)
+#define SPQT_CB2_ROWS(W)                          \
+    do {                                            \
+        switch (batch) {                            \
+            case 1: SPQT_CB2_MODES(W, 1); break;      \
+            case 2: SPQT_CB2_MODES(W, 2); break;      \
+            default: SPQT_CB2_MODES(W, 3); break;     \
+        }                                           \
+    } while (0)
 
-int run2(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+int run2(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
          const int32_t *count_dev, float thr, void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
          const spqt_launch_cfg *cfg) {
-    // about one workgroup of 4 wavefronts per CU: the 64 accumulators and two stages of weights leave
-    // room for one wavefront per SIMD; S a power of two <= 16
+    // a fourth activation row's 64 accumulators no longer fit the register file next to two stages of weights
+    if (batch > kMaxRows2) return SPQT_ESHAPE;
+    // about one workgroup of 4 wavefronts per CU: the 64 accumulators per activation row and two stages
+    // of weights leave room for one wavefront per SIMD; S a power of two <= 16
     const int64_t T64 = (M + W2::kRows - 1) / W2::kRows;
     int S0 = 1;
     while (S0 * 2 <= kMaxSplits2 && (int64_t)S0 * 2 * T64 <= 256) S0 *= 2;
@@ -131,18 +149,12 @@ int run2(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x_d
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
     return colblock_width_run<W2>(
-        mode, kMaxSplits2, S0, packed_dev, M, K, x_dev, idx_dev, count_dev, y_dev, workspace_dev, workspace_bytes, cfg,
+        mode, batch, kMaxSplits2, S0, packed_dev, M, K, x_dev, idx_dev, count_dev, y_dev, workspace_dev, workspace_bytes, cfg,
         [&](int waves, int md, int grid, void *partials, int32_t *ws_flags, int NC, int S, int T, int m_and_flags) {
-            switch (waves * 4 + md) {
-                case 4: SPQT_CB2_LAUNCH(1, false, false); break;
-                case 5: SPQT_CB2_LAUNCH(1, true, false); break;
-                case 6: SPQT_CB2_LAUNCH(1, false, true); break;
-                case 8: SPQT_CB2_LAUNCH(2, false, false); break;
-                case 9: SPQT_CB2_LAUNCH(2, true, false); break;
-                case 10: SPQT_CB2_LAUNCH(2, false, true); break;
-                case 16: SPQT_CB2_LAUNCH(4, false, false); break;
-                case 17: SPQT_CB2_LAUNCH(4, true, false); break;
-                default: SPQT_CB2_LAUNCH(4, false, true); break;
+            switch (waves) {
+                case 1: SPQT_CB2_ROWS(1); break;
+                case 2: SPQT_CB2_ROWS(2); break;
+                default: SPQT_CB2_ROWS(4); break;
             }
             return hipGetLastError();
         });
@@ -154,7 +166,7 @@ extern "C" int spqt_cb2_gemv(const void *packed_dev, int64_t M, int64_t K, const
                              const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                              void *workspace_dev, size_t workspace_bytes, void *stream,
                              const spqt_launch_cfg *cfg) {
-    return run2(idx_dev ? 0 : 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev, workspace_bytes,
+    return run2(idx_dev ? 0 : 1, 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev, workspace_bytes,
                 stream, cfg);
 }
 
@@ -162,5 +174,13 @@ extern "C" int spqt_cb2_gemv_fused(const void *packed_dev, int64_t M, int64_t K,
                                    void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
                                    const spqt_launch_cfg *cfg) {
     if (threshold != threshold) return SPQT_EINVAL;
-    return run2(2, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev, workspace_bytes, stream, cfg);
+    return run2(2, 1, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev, workspace_bytes, stream, cfg);
+}
+
+extern "C" int spqt_cb2_gemv_rows(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
+                                  const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
+                                  void *workspace_dev, size_t workspace_bytes, void *stream,
+                                  const spqt_launch_cfg *cfg) {
+    return run2(idx_dev ? 0 : 1, batch, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
+                workspace_bytes, stream, cfg);
 }

@@ -1,4 +1,4 @@
-// spqt_cb8_gemv, spqt_cb8_gemv_fused: the column-block GEMV for 8-bit codes ("ZZ-CB32-W8", spqt_colblock.h).
+// spqt_cb8_gemv, spqt_cb8_gemv_rows, spqt_cb8_gemv_fused: the column-block GEMV for 8-bit codes ("ZZ-CB32-W8", spqt_colblock.h).
 //
 // Paper Section 4.1.3 states that the column-wise layout carries over to other bit-widths.  The kernel
 // body is the one all widths other than 4 share (colblock_width.hpp); this file holds what 8 bits
@@ -80,26 +80,42 @@ struct W8 {
 };
 static_assert(W8::kChunkBytes == W8::kScaleBytes + kGroup * 128, "chunk size");
 
-template <int WAVES, bool DENSE, bool FUSED>
+template <int WAVES, bool DENSE, bool FUSED, int BATCH>
 __global__ __launch_bounds__(WAVES * 64) void spqt_cb8_gemv_kernel(
     const uint8_t *__restrict__ packed, const uint16_t *__restrict__ x, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ count, float *__restrict__ y, void *partials, int32_t *ws_flags, int K, int NC, int S,
     int T, int M, float thr) {
-    colblock_width_gemv<W8, WAVES, DENSE, FUSED>(packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, thr);
+    colblock_width_gemv<W8, WAVES, DENSE, FUSED, BATCH>(packed, x, idx, count, y, partials, ws_flags, K, NC, S, T, M, thr);
 }
 
-#define SPQT_CB8_LAUNCH(W, D, F)                                                                                      \
-    hipLaunchKernelGGL((spqt_cb8_gemv_kernel<W, D, F>), dim3(grid), dim3(W * 64), 0, st, pk, xp, idx_dev, count_dev, \
+#define SPQT_CB8_LAUNCH(W, D, F, B)                                                                                \
+    hipLaunchKernelGGL((spqt_cb8_gemv_kernel<W, D, F, B>), dim3(grid), dim3(W * 64), 0, st, pk, xp, idx_dev, count_dev, \
                        (float *)y_dev, partials, ws_flags, (int)K, NC, S, T, m_and_flags, thr)
+// mode 0 = index list, 1 = dense, 2 = one launch (one activation row)
+#define SPQT_CB8_MODES(W, B)                                   \
+    do {                                                         \
+        if (md == 0) SPQT_CB8_LAUNCH(W, false, false, B);          \
+        else if (md == 1) SPQT_CB8_LAUNCH(W, true, false, B);      \
+        else SPQT_CB8_LAUNCH(W, false, true, 1);                   \
+    } while (0)
+#define SPQT_CB8_ROWS(W)                          \
+    do {                                            \
+        switch (batch) {                            \
+            case 1: SPQT_CB8_MODES(W, 1); break;      \
+            case 2: SPQT_CB8_MODES(W, 2); break;      \
+            case 3: SPQT_CB8_MODES(W, 3); break;      \
+            default: SPQT_CB8_MODES(W, 4); break;     \
+        }                                           \
+    } while (0)
 
-int run8(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
+int run8(int mode, int batch, const void *packed_dev, int64_t M, int64_t K, const void *x_dev, const int32_t *idx_dev,
          const int32_t *count_dev, float thr, void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
          const spqt_launch_cfg *cfg) {
     // same targets as the 4-bit column-block kernel: about 512 (list) / 1024 (dense) workgroups of
     // 4 wavefronts, 256 on matrices large enough to be bandwidth-bound; S a power of two <= 16
     const int64_t T64 = (M + W8::kRows - 1) / W8::kRows;
     const bool big = M > 0 && K > 0 && (size_t)M * (size_t)K >= ((size_t)64 << 20);
-    const int64_t target = big ? 256 : (mode == 1 ? 1024 : 512);
+    const int64_t target = big && batch == 1 ? 256 : (mode == 1 && batch == 1 ? 1024 : 512);
     int S0 = 1;
     while (S0 * 2 <= 16 && (int64_t)S0 * 2 * T64 <= target) S0 *= 2;
     while (mode == 2 && S0 > 1 && (int64_t)S0 * 4 * kPassCols > K) S0 /= 2;   // one launch: at least one unit per wavefront
@@ -107,18 +123,12 @@ int run8(int mode, const void *packed_dev, int64_t M, int64_t K, const void *x_d
     const uint8_t *pk = (const uint8_t *)packed_dev;
     const uint16_t *xp = (const uint16_t *)x_dev;
     return colblock_width_run<W8>(
-        mode, SPQT_MAX_SPLITS, S0, packed_dev, M, K, x_dev, idx_dev, count_dev, y_dev, workspace_dev, workspace_bytes, cfg,
+        mode, batch, SPQT_MAX_SPLITS, S0, packed_dev, M, K, x_dev, idx_dev, count_dev, y_dev, workspace_dev, workspace_bytes, cfg,
         [&](int waves, int md, int grid, void *partials, int32_t *ws_flags, int NC, int S, int T, int m_and_flags) {
-            switch (waves * 4 + md) {
-                case 4: SPQT_CB8_LAUNCH(1, false, false); break;
-                case 5: SPQT_CB8_LAUNCH(1, true, false); break;
-                case 6: SPQT_CB8_LAUNCH(1, false, true); break;
-                case 8: SPQT_CB8_LAUNCH(2, false, false); break;
-                case 9: SPQT_CB8_LAUNCH(2, true, false); break;
-                case 10: SPQT_CB8_LAUNCH(2, false, true); break;
-                case 16: SPQT_CB8_LAUNCH(4, false, false); break;
-                case 17: SPQT_CB8_LAUNCH(4, true, false); break;
-                default: SPQT_CB8_LAUNCH(4, false, true); break;
+            switch (waves) {
+                case 1: SPQT_CB8_ROWS(1); break;
+                case 2: SPQT_CB8_ROWS(2); break;
+                default: SPQT_CB8_ROWS(4); break;
             }
             return hipGetLastError();
         });
@@ -130,7 +140,7 @@ extern "C" int spqt_cb8_gemv(const void *packed_dev, int64_t M, int64_t K, const
                              const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
                              void *workspace_dev, size_t workspace_bytes, void *stream,
                              const spqt_launch_cfg *cfg) {
-    return run8(idx_dev ? 0 : 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev, workspace_bytes,
+    return run8(idx_dev ? 0 : 1, 1, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev, workspace_bytes,
                 stream, cfg);
 }
 
@@ -138,5 +148,13 @@ extern "C" int spqt_cb8_gemv_fused(const void *packed_dev, int64_t M, int64_t K,
                                    void *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
                                    const spqt_launch_cfg *cfg) {
     if (threshold != threshold) return SPQT_EINVAL;
-    return run8(2, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev, workspace_bytes, stream, cfg);
+    return run8(2, 1, packed_dev, M, K, x_dev, nullptr, nullptr, threshold, y_dev, workspace_dev, workspace_bytes, stream, cfg);
+}
+
+extern "C" int spqt_cb8_gemv_rows(const void *packed_dev, int64_t M, int64_t K, const void *x_dev, int batch,
+                                  const int32_t *idx_dev, const int32_t *count_dev, void *y_dev,
+                                  void *workspace_dev, size_t workspace_bytes, void *stream,
+                                  const spqt_launch_cfg *cfg) {
+    return run8(idx_dev ? 0 : 1, batch, packed_dev, M, K, x_dev, idx_dev, count_dev, 0.0f, y_dev, workspace_dev,
+                workspace_bytes, stream, cfg);
 }

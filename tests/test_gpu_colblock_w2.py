@@ -260,3 +260,64 @@ def test_cb2_one_launch_clustered_ties_and_fp16(gpu):
     assert_close(got, ref, "clustered")
     h = run_one_launch(gpu, packed, M, K, x, thr, splits=4, waves=4, half=True)
     assert np.array_equal(h.view(np.uint16), got.astype(np.float16).view(np.uint16))
+
+
+def run_rows(gpu, packed_np, M, K, x_np, thr, dense=False, splits=0, waves=0, half=False):
+    torch, spqt, dev = gpu
+    B = x_np.shape[0]
+    packed = torch.from_numpy(packed_np).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(x_np)).to(dev)
+    buf = torch.full((B * M + 256,), 321.0, dtype=torch.float16 if half else torch.float32, device=dev)
+    y = buf[128:128 + B * M]
+    ws = spqt.new_workspace(M, K, B)
+    if dense:
+        spqt.spqt_cb2_gemv_rows(packed, M, K, x, None, None, y, ws, splits=splits, waves=waves)
+    else:
+        idx = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        spqt.spqt_gather(x, thr, idx, cnt)
+        spqt.spqt_cb2_gemv_rows(packed, M, K, x, idx, cnt, y, ws, splits=splits, waves=waves)
+    torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert np.all(out[:128] == 321.0) and np.all(out[128 + B * M:] == 321.0), "write outside y"
+    return out[128:128 + B * M].reshape(B, M)
+
+
+@pytest.mark.parametrize("M,K", [(512, 128), (1024, 1024), (2048, 2048), (300, 1024)])
+@pytest.mark.parametrize("batch", [2, 3])
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 1), (3, 2), (8, 4)])
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.9])
+def test_cb2_several_rows_on_the_union_list(gpu, M, K, batch, splits, waves, sparsity):
+    """Several activation rows share the union of their kept columns and one pass over the weights:
+    every listed column contributes to every row, as the oracle's batch form does."""
+    import paper_2511_04477_amd as spqt
+    W = make_fp_weights(512 * ((M + 511) // 512), K, 9502 + M + K)[:M].copy()
+    x = make_x(K, "laplace", 9602 + M + K, batch=batch)
+    thr = quantile_threshold(x, sparsity)
+    say(f"cb2 rows M={M} K={K} batch={batch} splits={splits} waves={waves} s={sparsity}")
+    q, s = c2.quantize(c2.pad_rows(W))
+    ref = c2.gemv(q, s, x, thr)[:, :M]
+    assert_close(run_rows(gpu, spqt.spqt_cb2_quantize(W), M, K, x, thr, splits=splits, waves=waves), ref, "cb2 rows")
+
+
+def test_cb2_rows_dense_fp16_and_limits(gpu):
+    """Dense mode with several rows, fp16 output, one row through the rows entry point equals the batch-1 entry
+    point bit for bit, and a row count past the limit is refused."""
+    torch, spqt, dev = gpu
+    M, K = 1024, 1024
+    W = make_fp_weights(M, K, 9702)
+    x = make_x(K, "laplace", 9703, batch=3)
+    packed = spqt.spqt_cb2_quantize(W)
+    q, s = c2.quantize(W)
+    say("cb2 rows dense")
+    d32 = run_rows(gpu, packed, M, K, x, 0.0, dense=True)
+    assert_close(d32, c2.gemv(q, s, x, 0.0), "rows dense")
+    d16 = run_rows(gpu, packed, M, K, x, 0.0, dense=True, half=True)
+    assert np.array_equal(d16.view(np.uint16), d32.astype(np.float16).view(np.uint16))
+    thr = quantile_threshold(x[0:1], 0.5)
+    one = run_rows(gpu, packed, M, K, x[0:1], thr, splits=4, waves=4)
+    assert np.array_equal(one.view(np.uint32), run(gpu, packed, M, K, x[0:1], thr, splits=4, waves=4).view(np.uint32))
+    xb = torch.zeros((4, K), dtype=torch.float16, device=dev)
+    yb = torch.zeros((4) * M, dtype=torch.float32, device=dev)
+    with pytest.raises(spqt.SpqtError):
+        spqt.spqt_cb2_gemv_rows(torch.from_numpy(packed).to(dev), M, K, xb, None, None, yb, spqt.new_workspace(M, K, 4))

@@ -181,6 +181,10 @@ def test_colblock_bad_arguments():
     assert L.spqt_cb2_gemv_fused(None, 256, 128, 16, ctypes.c_float(0.5), 16, None, 0, None, None) == -1
     assert L.spqt_cb8_gemv_fused(128, 256, 128, 16, ctypes.c_float(float("nan")), 16, None, 0, None, None) == -1
     assert L.spqt_cb8_gemv_fused(128, 256, 100, 16, ctypes.c_float(0.5), 16, None, 0, None, None) == -2
+    assert L.spqt_cb2_gemv_rows(128, 512, 128, 16, 4, None, None, 16, None, 0, None, None) == -2   # at most 3 rows at 2 bits
+    assert L.spqt_cb2_gemv_rows(128, 512, 128, 16, 0, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb8_gemv_rows(128, 512, 128, 16, 5, None, None, 16, None, 0, None, None) == -2
+    assert L.spqt_cb8_gemv_rows(128, 512, 128, 16, 2, 16, None, 16, None, 0, None, None) == -1     # idx without count
     cfg = spqt.LaunchCfg(17, 4, 0)
     assert L.spqt_cb2_gemv(128, 256, 128, 16, None, None, 16, None, 0, None, ctypes.byref(cfg)) == -1   # more than 16 splits
 
