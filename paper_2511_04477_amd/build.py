@@ -1,4 +1,5 @@
-"""Compile libspqt.so for gfx950 with hipcc (cross-compiles without a GPU).
+"""Compile libspqt.so (and its benchmark, timeline and test variants) for gfx950 with hipcc, which
+cross-compiles without a GPU.
 
 Every source is compiled to an object of its own, several at a time, and the objects are linked;
 objects live in `_build/` next to this file and are rebuilt on every call.
@@ -21,6 +22,10 @@ CALIB_LIB = os.path.join(PKG, "libspqt_calib.so")       # benchmark-only helper 
 CALIB_SOURCES = ["calib.hip", "baseline_rowmajor.hip"]
 # The same kernels with wall-clock stamps per wavefront (python -m paper_2511_04477_amd.timeline).
 TIMELINE_LIB = os.path.join(PKG, "libspqt_timeline.so")
+# The group-layout GEMV entry points with silent producers and a reducer that waits for a handful of polls only:
+# what the tests use to run the give-up path of the exchange (NaN outputs, poison flag) without a stalled kernel.
+GIVEUP_LIB = os.path.join(PKG, "libspqt_giveup.so")
+GIVEUP_SOURCES = ["pack.cpp", "gemv.hip", "gemv_list.hip", "gemv_bal.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -51,23 +56,29 @@ def _run(cmd, verbose: bool) -> None:
         print(out)
 
 
-def _build_one(lib: str, sources, verbose: bool, defines=(), tag: str = "") -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def _jobs(lib: str, sources, defines=(), tag: str = ""):
+    """(compile command, ...) per source and the link command of one library."""
     objs = [os.path.join(OBJ, f"{tag}{os.path.splitext(s)[0]}.o") for s in sources]
     common = [_hipcc(), *HIPCC_FLAGS, *[f"-D{d}" for d in defines], "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    with ThreadPoolExecutor(JOBS) as pool:
-        list(pool.map(lambda so: _run([*common, "-c", "-o", so[1], os.path.join(CSRC, so[0])], verbose),
-                      zip(sources, objs)))
-    tmp = lib + f".tmp{os.getpid()}"
-    _run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs], verbose)
-    os.replace(tmp, lib)
-    return lib
+    compiles = [[*common, "-c", "-o", o, os.path.join(CSRC, s)] for s, o in zip(sources, objs)]
+    return compiles, (lib, objs)
 
 
 def build(verbose: bool = False) -> str:
-    _build_one(CALIB_LIB, CALIB_SOURCES, verbose)
-    _build_one(TIMELINE_LIB, SOURCES, verbose, defines=("SPQT_TIMELINE=1",), tag="tl_")
-    return _build_one(LIB, SOURCES, verbose)
+    os.makedirs(OBJ, exist_ok=True)
+    plan = [_jobs(CALIB_LIB, CALIB_SOURCES),
+            _jobs(TIMELINE_LIB, SOURCES, defines=("SPQT_TIMELINE=1",), tag="tl_"),
+            _jobs(GIVEUP_LIB, GIVEUP_SOURCES, defines=("SPQT_TEST_GIVE_UP=1",), tag="gu_"),
+            _jobs(LIB, SOURCES)]
+    # every object of every library in one pool (longest first), then the links
+    compiles = sorted((c for cs, _ in plan for c in cs), key=lambda c: -os.path.getsize(c[-1]))
+    with ThreadPoolExecutor(JOBS) as pool:
+        list(pool.map(lambda c: _run(c, verbose), compiles))
+    for _, (lib, objs) in plan:
+        tmp = lib + f".tmp{os.getpid()}"
+        _run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs], verbose)
+        os.replace(tmp, lib)
+    return LIB
 
 
 if __name__ == "__main__":

@@ -138,11 +138,14 @@ def main(argv=None) -> int:
     # where the slow wavefronts are: by XCD, by position inside the workgroup, by split index of the block-row
     done_all = us(d[:, 4])
     print("loop done, median per XCD: " + ", ".join(f"{np.median(done_all[xcc == i]):.2f}" for i in sorted(set(xcc.tolist()))))
+    start_all = us(d[:, 0])
+    print("start, median per XCD: " + ", ".join(f"{np.median(start_all[xcc == i]):.2f}" for i in sorted(set(xcc.tolist()))))
     if full.shape[0]:
         print("loop done, median per wavefront index in the workgroup: " + ", ".join(f"{np.median(done[:, w]):.2f}" for w in range(W)))
         print("start, median per wavefront index in the workgroup: " + ", ".join(f"{np.median(0.01 * (full[:, w, 0] - t0)):.2f}" for w in range(W)))
-    stream = us(d[:, 4]) - us(d[:, 3])
-    print(f"first weights -> loop done per wavefront: median {np.median(stream):.2f} us, max {stream.max():.2f} us")
+    if (d[:, 3] > 0).all():      # kernels without a "first weights" stamp leave it zero
+        stream = us(d[:, 4]) - us(d[:, 3])
+        print(f"first weights -> loop done per wavefront: median {np.median(stream):.2f} us, max {stream.max():.2f} us")
     return 0
 
 
