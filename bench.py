@@ -289,6 +289,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "spqt_gemv_list_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "bytes_per_launch": wl.mean_kept_bytes, "us_per_launch": round(us_gemv, 3),
+                     # kept bytes plus x, the index list and y: what the launch must touch at all
+                     "bytes_per_launch_with_x_idx_y": wl.mean_kept_bytes + 2 * K + 4 * float(np.mean(wl.n_ns)) + 4 * M,
                      "traffic": measured_traffic("spqt_gemv_list_kernel", M, K, H["sparsity"])},
     }
 
@@ -297,6 +299,8 @@ def main():
     out["context"] = {"empty_launch_us": round(t_empty, 3),
                       "plain_read_same_bytes_us": round(t_read, 3), "plain_read_bytes": read_bytes,
                       "plain_read_1GiB_GBps": round(big_gbps, 1),
+                      "gemv_frac_of_plain_read_rate": round(achieved / big_gbps, 4),
+                      "gemv_us_over_plain_read_us": round(us_gemv / t_read, 3),
                       "note": "plain streaming read of the same byte count, cold, same graph-replay timing: the practical floor for one launch"}
 
     # ---------------- sweeps ---------------------------------------------------------------
