@@ -86,6 +86,7 @@ def main(argv=None) -> int:
     ap.add_argument("--dir", required=True, help="folder holding trace/ kt/ fetch/ write/ sq/ and the logs")
     ap.add_argument("--workload", required=True, choices=sorted(LAYOUT))
     ap.add_argument("--out", required=True)
+    ap.add_argument("--traffic", default=TRAFFIC, help="the traffic table to refresh (default: profiles/hbm_traffic.txt)")
     args = ap.parse_args(argv)
     D, W = args.dir, args.workload
     lay, kname, bytes_per_weight = LAYOUT[W]
@@ -164,8 +165,8 @@ def main(argv=None) -> int:
 
     # refresh the traffic table: one line per (kernel, M, K, sparsity)
     keep = []
-    if os.path.exists(TRAFFIC):
-        for line in open(TRAFFIC):
+    if os.path.exists(args.traffic):
+        for line in open(args.traffic):
             fl = line.split()
             if line.startswith("#") or len(fl) < 5:
                 continue
@@ -174,7 +175,7 @@ def main(argv=None) -> int:
             keep.append(line.rstrip("\n"))
     for kern, nbytes in sorted(traffic_rows.items()):
         keep.append(f"{kern} {M} {K} 0.5 {nbytes} {os.path.relpath(args.out, ROOT)}")
-    with open(TRAFFIC, "w") as fh:
+    with open(args.traffic, "w") as fh:
         fh.write("# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), written by\n"
                  "# python3 -m paper_2511_04477_amd.profile_summary; columns: kernel M K sparsity bytes source\n")
         fh.write("\n".join(sorted(keep)) + "\n")
